@@ -1,0 +1,199 @@
+/*
+ * kvzap.h -- C ABI of the KVzap prune step for AMD MI355X (gfx950).
+ *
+ * KVzap (arXiv 2601.07891) prunes a transformer layer's KV cache in three
+ * steps (Sec. 3.3, Algorithm 1): a small per-layer surrogate maps every
+ * token's hidden state to one importance score per KV head; scores are compared
+ * with one global threshold tau, the most recent `window` positions being kept
+ * unconditionally; the surviving K/V rows of every head are gathered, in
+ * position order, into a cache whose length differs from head to head (Sec. 5).
+ * While decoding, the same rule is applied one token at a time, with a buffer
+ * of the scores of the tokens still inside the window (caption of Algorithm 1).
+ *
+ * General conventions
+ *   - Every pointer is a DEVICE pointer into memory owned by the caller, unless
+ *     a parameter says "host".  The library allocates no device memory, keeps no
+ *     pointer after a call returns, and never synchronises: every call only
+ *     enqueues kernels on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream).  The caller keeps all buffers alive until the stream has
+ *     drained.
+ *   - bf16 tensors are raw 16-bit patterns (upper half of an IEEE fp32).
+ *   - All tensors are dense, row-major, in the index order written beside them.
+ *     Base pointers must be 16-byte aligned (KVZAP_ERR_ALIGN otherwise).
+ *   - Scratch memory comes from a caller-provided workspace whose minimum size
+ *     is given by kvzap_workspace_bytes(); it must be 256-byte aligned and is
+ *     free for reuse once the call's kernels have run.
+ *   - Return value: KVZAP_OK (0) or a negative kvzap_status.  Arguments are
+ *     validated on the host before anything is enqueued; on error nothing is
+ *     launched and no output is written.  No call throws or aborts.
+ *   - Supported shapes: H (KV heads) in [1, 16]; D (head dim) a multiple of 8
+ *     with D <= 512 (rows are moved in 16-byte pieces); D_h a multiple of 64;
+ *     the MLP width M a multiple of 128 with M <= 1024.  Anything else returns
+ *     KVZAP_ERR_UNSUPPORTED; there is no fallback path.
+ *   - Weight storage is output-major, the way a PyTorch linear module stores
+ *     it: the paper's W1 in R^{D_h x M} (App. B) is passed as its transpose
+ *     [M, D_h], W2 in R^{M x H} as [H, M], the linear surrogate's D_h x H matrix
+ *     as [H, D_h].  Every output unit's D_h inputs are therefore contiguous.
+ */
+#ifndef KVZAP_H_
+#define KVZAP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum kvzap_status {
+  KVZAP_OK = 0,
+  KVZAP_ERR_NULL = -1,        /* a required pointer is NULL                    */
+  KVZAP_ERR_SHAPE = -2,       /* a size is negative, zero where it may not be, or overflows */
+  KVZAP_ERR_ALIGN = -3,       /* a base pointer is not 16-byte aligned         */
+  KVZAP_ERR_UNSUPPORTED = -4, /* legal but outside the supported shapes        */
+  KVZAP_ERR_CAPACITY = -5,    /* an output buffer is too small for the worst case */
+  KVZAP_ERR_WORKSPACE = -6,   /* workspace missing, misaligned or too small    */
+  KVZAP_ERR_RUNTIME = -7      /* a HIP launch failed (see hipGetLastError)     */
+} kvzap_status;
+
+/* Which call a workspace query is for. */
+typedef enum kvzap_call {
+  KVZAP_CALL_SCORE = 0,
+  KVZAP_CALL_MASK = 1,
+  KVZAP_CALL_COMPACT = 2,
+  KVZAP_CALL_DECODE_EVICT = 3
+} kvzap_call;
+
+/* Text for a status code (host pointer to a static string, never NULL). */
+const char* kvzap_status_string(int status);
+
+/* Library version, "major.minor.patch" (host pointer to a static string). */
+const char* kvzap_version(void);
+
+/*
+ * Minimum workspace size in bytes for one call.  For KVZAP_CALL_DECODE_EVICT
+ * pass T = 1 (one new token per sequence).  Returns 0 for calls that need no
+ * workspace and for invalid arguments.  Pure host function.
+ */
+size_t kvzap_workspace_bytes(int which_call, int B, int T, int Dh, int M, int H);
+
+/*
+ * kvzap_score -- the surrogate forward (Sec. 3.3; Sec. 4.1; App. B Eq. 5-6).
+ *
+ *   M == 0 : KVzap-Linear   scores[b,h,t] = sum_k hidden[b,t,k] * W1[h,k] + b1[h]
+ *   M  > 0 : KVzap-MLP      z = hidden[b,t,:] . W1[m,:] + b1[m]        (m < M)
+ *                           g = GELU(z)  (exact erf form, fp32)
+ *                           scores[b,h,t] = sum_m g[m] * W2[h,m] + b2[h]
+ *
+ *   hidden  bf16 [B, T, Dh]
+ *   W1      bf16 [M, Dh] (MLP) or [H, Dh] (linear)
+ *   b1      bf16 [M] (MLP) or [H] (linear); NULL = zero
+ *   W2      bf16 [H, M]; must be NULL iff M == 0
+ *   b2      bf16 [H]; NULL = zero; must be NULL if M == 0
+ *   scores  fp32 [B, H, T]  (positions on the last axis, as Algorithm 1 indexes
+ *           them); fully overwritten.
+ *
+ * Arithmetic: bf16 products accumulated in fp32 on the matrix cores; GELU in
+ * fp32; the GELU output enters the second projection as a bf16 pair (high part
+ * plus residual), i.e. to about 16 mantissa bits.  The sum order is fixed, so
+ * results are run-to-run deterministic.  B*T == 0 is a no-op.
+ */
+int kvzap_score(const void* hidden, const void* W1, const void* b1,
+                const void* W2, const void* b2, float* scores,
+                int B, int T, int Dh, int M, int H,
+                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * kvzap_mask -- threshold plus sliding window (Sec. 3.3; Algorithm 1).
+ *
+ *   keep[b,h,t] = t < T_b  and  ( t >= T_b - window  or  scores[b,h,t] >= tau )
+ *
+ * with T_b = seq_lens[b] (or T when seq_lens is NULL).  Equality keeps; a NaN
+ * score is dropped unless the window protects it; window = 0 protects nothing;
+ * window >= T_b keeps everything; tau may be +-infinity.
+ *
+ *   scores    fp32 [B, H, T]
+ *   seq_lens  int32 [B], 0 <= seq_lens[b] <= T, or NULL   (right-padded batch)
+ *   keep_idx  int32, capacity B*H*T entries: kept positions t, ascending within
+ *             a head, heads packed back to back in (b,h) row-major order; head
+ *             (b,h) occupies keep_idx[offsets[b*H+h] .. +lengths[b,h])
+ *   lengths   int32 [B, H]     number of kept positions
+ *   offsets   int64 [B*H + 1]  exclusive prefix sum of lengths; the last entry
+ *             is the total number of kept rows
+ *
+ * Exactly one result is correct and it is reproduced bit for bit.
+ */
+int kvzap_mask(const float* scores, float tau, int window,
+               const int32_t* seq_lens, int B, int H, int T,
+               int32_t* keep_idx, int32_t* lengths, int64_t* offsets,
+               void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * kvzap_compact -- the ragged per-head gather (Algorithm 1, last line; Sec. 5).
+ *
+ *   K_out[offsets[b*H+h] + j, :] = K[b, h, keep_idx[offsets[b*H+h] + j], :]
+ *   for j < lengths[b,h]; the same for V.  Rows are copied byte for byte.
+ *
+ *   K, V          bf16 [B, H, T, D]
+ *   keep_idx, lengths, offsets   as written by kvzap_mask (device memory)
+ *   K_out, V_out  bf16 [cap_rows, D]; must not overlap K or V
+ *   cap_rows      rows available in K_out and V_out.  The kept total lives on
+ *                 the device, so it cannot be checked on the host: rows at or
+ *                 beyond cap_rows are not written (never out of bounds), and
+ *                 cap_rows = B*H*T is always sufficient.
+ */
+int kvzap_compact(const void* K, const void* V, const int32_t* keep_idx,
+                  const int32_t* lengths, const int64_t* offsets,
+                  void* K_out, void* V_out, int64_t cap_rows,
+                  int B, int H, int T, int D, void* stream);
+
+/*
+ * kvzap_decode_evict -- one decoding step of one layer for B sequences
+ * (caption of Algorithm 1; Sec. 2 "delayed eviction with a sliding window";
+ * Sec. 3.3: the surrogate needs only the hidden state, so it runs at decode).
+ *
+ * For sequence b at position p = seq_pos[b], for every head h:
+ *   1. s = surrogate(hidden_new[b])[h]                   (as kvzap_score)
+ *   2. q = p - window is the position leaving the window.  If q >= 0, its
+ *      score is score_ring[b,h,q mod window]; if that score >= tau the pair is
+ *      appended to the head's kept prefix, otherwise it is dropped.
+ *   3. the new pair and s are stored in ring slot p mod window.
+ * Then seq_pos[b] = p + 1.  After the step, prefix + ring hold exactly the
+ * positions Algorithm 1 keeps on the first p+1 tokens.
+ *
+ * Cache layout (device memory, caller-owned, updated in place):
+ *   K_prefix, V_prefix  bf16 [total_rows, D]: head (b,h) owns the slab of rows
+ *                 slab_offsets[b*H+h] .. + slab_capacity[b*H+h]; its first
+ *                 lengths[b,h] rows are the kept pairs older than the window,
+ *                 in ascending position order (append-only)
+ *   prefix_pos    int32 [total_rows]: position of every prefix row
+ *   K_ring, V_ring  bf16 [B, H, window, D]: the pairs inside the window, the
+ *                 pair of position t in slot t mod window
+ *   score_ring    fp32 [B, H, window]: their scores
+ *   lengths       int32 [B, H], seq_pos int32 [B]
+ * With window == 0 the ring pointers may be NULL: the new token itself is
+ * tested and goes to the prefix or nowhere.
+ *
+ *   hidden_new    bf16 [B, Dh];  k_new, v_new  bf16 [B, H, D]
+ *   W1, b1, W2, b2, Dh, M       as in kvzap_score
+ *   error_flag    int32 [1], may be NULL: set to 1 on the device if a kept pair
+ *                 found its slab full (the pair is then not appended and the
+ *                 head's length stays at capacity); never cleared by the library
+ *
+ * Calls on the same state must be ordered on one stream.
+ */
+int kvzap_decode_evict(const void* hidden_new, const void* W1, const void* b1,
+                       const void* W2, const void* b2, int Dh, int M,
+                       const void* k_new, const void* v_new,
+                       void* K_prefix, void* V_prefix, int32_t* prefix_pos,
+                       const int64_t* slab_offsets, const int32_t* slab_capacity,
+                       void* K_ring, void* V_ring, float* score_ring,
+                       int32_t* lengths, int32_t* seq_pos,
+                       float tau, int window, int B, int H, int D,
+                       int32_t* error_flag,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVZAP_H_ */

@@ -1,0 +1,340 @@
+"""Float64 CPU oracle of the KVzap prune step (test infrastructure, not product).
+
+What is computed follows the paper directly:
+
+* surrogate forward   -- Sec. 3.3 and Sec. 4.1: a per-layer linear map D_h -> H,
+  or an MLP D_h -> D_h/8 -> GELU -> H, applied independently at every position;
+  weight shapes as in App. B (W1 in R^{D_h x D_h/8}, W2 in R^{D_h/8 x H}).
+* threshold + window  -- Sec. 3.3 and Algorithm 1: the last `window` positions
+  are forced to +inf, a KV pair is kept iff its score is >= tau.
+* ragged gather       -- Algorithm 1: kept rows of K and V in row-major
+  (head, position) order, hence a different length per head (Sec. 5).
+* decode              -- caption of Algorithm 1: the same rule applied one
+  token at a time with a buffer of the scores still inside the window.
+
+Everything is the plain definition written out with numpy in float64, with no
+blocking, fusion or reordering.  K/V rows are carried as raw uint16 bf16 bit
+patterns so that the gather is a byte copy.  Readings taken where the paper is
+silent are listed beside each function.
+
+Parity pins (tests/test_oracle_*.py): tau=-inf identity, tau=+inf window only,
+nested kept sets in tau, brute-force mask enumeration at tiny T, hand loops vs
+the library GEMM / erf / nonzero, exact-integer inputs, GELU identities and the
+second moment E[GELU(z)^2], the closed forms and printed percentages of App. B,
+decode == prefill on the grown prefix, conservation of lengths/offsets.
+Absolute score values for real prompts are "parity unpinned": the paper prints
+none and its trained weights are not available here.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+from scipy import special as _sp_special
+
+
+# --------------------------------------------------------------------------
+# bf16 bit patterns <-> float64 (exact: bf16 is the top half of an fp32)
+# --------------------------------------------------------------------------
+def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    """Exact up-cast of bf16 bit patterns (uint16) to float64."""
+    bits = np.ascontiguousarray(bits, dtype=np.uint16)
+    as_f32 = (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+    return as_f32.astype(np.float64)
+
+
+# --------------------------------------------------------------------------
+# surrogate forward (Sec. 3.3, Sec. 4.1, App. B Eq. 5-6)
+# --------------------------------------------------------------------------
+def gelu(z: np.ndarray) -> np.ndarray:
+    """Exact GELU, z * Phi(z), in float64 (Sec. 4.1 says only "GELU": the
+    erf form is taken, not the tanh approximation)."""
+    z = np.asarray(z, dtype=np.float64)
+    return 0.5 * z * (1.0 + _sp_special.erf(z / math.sqrt(2.0)))
+
+
+def score_linear(hidden: np.ndarray, W: np.ndarray,
+                 b: Optional[np.ndarray] = None) -> np.ndarray:
+    """KVzap-Linear (Sec. 4.1; App. B Eq. 6).
+
+    hidden [T, D_h], W [D_h, H], b [H] or None -- float64 values.
+    Returns scores [H, T]: the module's output is (T, H) (Sec. 4.1) while
+    Algorithm 1 indexes positions on the last axis, so it is transposed here.
+    """
+    hidden = np.asarray(hidden, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    S = hidden @ W
+    if b is not None:
+        S = S + np.asarray(b, dtype=np.float64)[None, :]
+    return np.ascontiguousarray(S.T)
+
+
+def score_mlp(hidden: np.ndarray, W1: np.ndarray, b1: Optional[np.ndarray],
+              W2: np.ndarray, b2: Optional[np.ndarray]) -> np.ndarray:
+    """KVzap-MLP (Sec. 4.1; App. B Eq. 5): one hidden layer of width D_h/8
+    shared by all heads, GELU, then H outputs.  No intermediate rounding.
+
+    hidden [T, D_h], W1 [D_h, M], b1 [M]|None, W2 [M, H], b2 [H]|None.
+    Returns scores [H, T].
+    """
+    hidden = np.asarray(hidden, dtype=np.float64)
+    Z = hidden @ np.asarray(W1, dtype=np.float64)
+    if b1 is not None:
+        Z = Z + np.asarray(b1, dtype=np.float64)[None, :]
+    G = gelu(Z)
+    S = G @ np.asarray(W2, dtype=np.float64)
+    if b2 is not None:
+        S = S + np.asarray(b2, dtype=np.float64)[None, :]
+    return np.ascontiguousarray(S.T)
+
+
+# --------------------------------------------------------------------------
+# threshold + sliding window (Sec. 3.3, Algorithm 1)
+# --------------------------------------------------------------------------
+def keep_mask(scores: np.ndarray, tau: float, window: int,
+              seq_len: Optional[int] = None) -> np.ndarray:
+    """keep[h, t] = (t >= T_b - window) or (scores[h, t] >= tau).
+
+    Readings: equality keeps (Algorithm 1 uses >=); a NaN score compares false
+    and is dropped unless protected; window = 0 protects nothing (the w = 0
+    ablation of Sec. 4.8 means "no local window"); window >= T keeps all;
+    with seq_len = T_b < T (right-padded batch) positions >= T_b do not exist
+    and the window is counted from T_b.
+    """
+    scores = np.asarray(scores)
+    H, T = scores.shape
+    Tb = T if seq_len is None else int(seq_len)
+    if not (0 <= Tb <= T):
+        raise ValueError("seq_len out of range")
+    if window < 0:
+        raise ValueError("window must be >= 0")
+    t = np.arange(T)
+    with np.errstate(invalid="ignore"):
+        keep = scores >= tau
+    keep = keep | (t >= Tb - window)[None, :]
+    keep = keep & (t < Tb)[None, :]
+    return keep
+
+
+def kept_indices(keep: np.ndarray) -> Tuple[List[np.ndarray], np.ndarray]:
+    """Ascending kept positions per head and their counts (Algorithm 1:
+    torch.where enumerates true entries in row-major order)."""
+    H = keep.shape[0]
+    idx = [np.nonzero(keep[h])[0].astype(np.int32) for h in range(H)]
+    lengths = np.array([len(i) for i in idx], dtype=np.int32)
+    return idx, lengths
+
+
+def exclusive_offsets(lengths: np.ndarray) -> np.ndarray:
+    """offsets[i] = sum(lengths[:i]) over (sequence, head) row-major, with the
+    grand total appended: where each head's rows start in the packed cache."""
+    flat = np.asarray(lengths, dtype=np.int64).reshape(-1)
+    out = np.zeros(flat.size + 1, dtype=np.int64)
+    np.cumsum(flat, out=out[1:])
+    return out
+
+
+def gather_rows(X_bits: np.ndarray, idx: Sequence[np.ndarray]) -> np.ndarray:
+    """Packed kept rows, heads in order, positions ascending (Algorithm 1:
+    keys[indices]).  X_bits is [H, T, D] uint16; the copy is bit-exact."""
+    X_bits = np.asarray(X_bits)
+    parts = [X_bits[h][idx[h]] for h in range(X_bits.shape[0])]
+    if not parts:
+        return np.zeros((0, X_bits.shape[-1]), dtype=X_bits.dtype)
+    return np.concatenate(parts, axis=0)
+
+
+@dataclass
+class PruneResult:
+    idx: List[List[np.ndarray]]          # [B][H] ascending int32 positions
+    lengths: np.ndarray                  # [B, H] int32
+    offsets: np.ndarray                  # [B*H + 1] int64
+    K_out: Optional[np.ndarray] = None   # [n_total, D] uint16
+    V_out: Optional[np.ndarray] = None
+
+    def flat_idx(self) -> np.ndarray:
+        parts = [i for per_b in self.idx for i in per_b]
+        return np.concatenate(parts) if parts else np.zeros(0, np.int32)
+
+
+def prune(scores: np.ndarray, tau: float, window: int,
+          K_bits: Optional[np.ndarray] = None,
+          V_bits: Optional[np.ndarray] = None,
+          seq_lens: Optional[Sequence[int]] = None) -> PruneResult:
+    """Algorithm 1 after the scorer, for a batch: scores [B, H, T],
+    K_bits / V_bits [B, H, T, D] uint16 (optional)."""
+    scores = np.asarray(scores)
+    B, H, T = scores.shape
+    all_idx, all_len = [], []
+    for b in range(B):
+        Tb = None if seq_lens is None else int(seq_lens[b])
+        idx, n = kept_indices(keep_mask(scores[b], tau, window, Tb))
+        all_idx.append(idx)
+        all_len.append(n)
+    lengths = (np.stack(all_len) if B else np.zeros((0, H), np.int32)).astype(np.int32)
+    res = PruneResult(all_idx, lengths, exclusive_offsets(lengths))
+    if K_bits is not None:
+        D = K_bits.shape[-1]
+        ks = [gather_rows(K_bits[b], all_idx[b]) for b in range(B)]
+        vs = [gather_rows(V_bits[b], all_idx[b]) for b in range(B)]
+        res.K_out = np.concatenate(ks, axis=0) if ks else np.zeros((0, D), np.uint16)
+        res.V_out = np.concatenate(vs, axis=0) if vs else np.zeros((0, D), np.uint16)
+    return res
+
+
+def compress(hidden_bits: np.ndarray, K_bits: np.ndarray, V_bits: np.ndarray,
+             weights: dict, tau: float, window: int = 128,
+             seq_lens: Optional[Sequence[int]] = None
+             ) -> Tuple[np.ndarray, PruneResult]:
+    """The whole of Algorithm 1 for one layer.
+
+    hidden_bits [B, T, D_h] uint16 bf16 patterns; weights holds float64 arrays
+    in the paper's orientation: {"W": [D_h,H], "b"} for the linear surrogate or
+    {"W1": [D_h,M], "b1", "W2": [M,H], "b2"} for the MLP (biases may be None).
+    Returns (scores [B,H,T] float64, PruneResult).
+    """
+    B = hidden_bits.shape[0]
+    per_b = []
+    for b in range(B):
+        h64 = bf16_bits_to_f64(hidden_bits[b])
+        if "W1" in weights:
+            per_b.append(score_mlp(h64, weights["W1"], weights.get("b1"),
+                                   weights["W2"], weights.get("b2")))
+        else:
+            per_b.append(score_linear(h64, weights["W"], weights.get("b")))
+    scores = np.stack(per_b)
+    return scores, prune(scores, tau, window, K_bits, V_bits, seq_lens)
+
+
+def tau_at_keep_fraction(scores: np.ndarray, window: int, keep_fraction: float,
+                         seq_lens: Optional[Sequence[int]] = None) -> float:
+    """Threshold at which `keep_fraction` of the non-window tokens (pooled over
+    sequences and heads) score >= tau: the midpoint between the two adjacent
+    order statistics, rounded to fp32 so that a float32 consumer compares
+    against the identical value.  (Workload recipe, not part of the method.)"""
+    scores = np.asarray(scores, dtype=np.float64)
+    B, H, T = scores.shape
+    pool = []
+    for b in range(B):
+        Tb = T if seq_lens is None else int(seq_lens[b])
+        pool.append(scores[b, :, :max(Tb - window, 0)].reshape(-1))
+    pool = np.sort(np.concatenate(pool))
+    n = pool.size
+    if n < 2:
+        raise ValueError("not enough non-window tokens for a quantile")
+    k = int(round(keep_fraction * n))          # tokens kept = the k largest
+    k = min(max(k, 1), n - 1)
+    lo, hi = pool[n - k - 1], pool[n - k]
+    return float(np.float32(0.5 * (lo + hi)))
+
+
+# --------------------------------------------------------------------------
+# decode (caption of Algorithm 1; Sec. 2 "delayed eviction with a sliding
+# window"; Sec. 3.3: the surrogate depends only on hidden states, so it can be
+# applied while decoding)
+# --------------------------------------------------------------------------
+@dataclass
+class DecodeHeadState:
+    positions: List[int] = field(default_factory=list)   # ascending
+    K_rows: List[np.ndarray] = field(default_factory=list)
+    V_rows: List[np.ndarray] = field(default_factory=list)
+
+
+class DecodeOracle:
+    """Canonical decode state: per (sequence, head) the ascending list of kept
+    positions with their rows; per sequence the next position p; per
+    (sequence, head) the scores of the positions still inside the window.
+
+    One step for sequence b at position p (reading of the caption):
+      1. s = surrogate(h_new)                       (H scores)
+      2. q = p - w is the position that leaves the window once p is appended;
+         if q >= 0 and not (score[q] >= tau) the pair at q is removed from the
+         head (for w = 0 this is the new token itself: q = p);
+      3. the new pair is appended at position p and its score remembered.
+    After the step the kept set equals Algorithm 1 applied to the p+1 scores.
+    """
+
+    def __init__(self, B: int, H: int, window: int, tau: float):
+        self.B, self.H, self.w, self.tau = B, H, int(window), float(tau)
+        self.heads = [[DecodeHeadState() for _ in range(H)] for _ in range(B)]
+        self.next_pos = [0] * B
+        self.win_scores = [[dict() for _ in range(H)] for _ in range(B)]
+
+    def load_prefill(self, b: int, scores_b: np.ndarray,
+                     K_bits_b: np.ndarray, V_bits_b: np.ndarray) -> None:
+        """Initialise sequence b from a prefill of T tokens pruned by
+        Algorithm 1 with the same tau and window."""
+        H, T = scores_b.shape
+        keep = keep_mask(scores_b, self.tau, self.w)
+        for h in range(H):
+            st = self.heads[b][h]
+            pos = np.nonzero(keep[h])[0]
+            st.positions = [int(t) for t in pos]
+            st.K_rows = [K_bits_b[h, t].copy() for t in pos]
+            st.V_rows = [V_bits_b[h, t].copy() for t in pos]
+            self.win_scores[b][h] = {int(t): float(scores_b[h, t])
+                                     for t in range(max(T - self.w, 0), T)}
+        self.next_pos[b] = T
+
+    def step(self, scores_new: np.ndarray, k_new: np.ndarray,
+             v_new: np.ndarray) -> None:
+        """scores_new [B, H] float64, k_new / v_new [B, H, D] uint16."""
+        for b in range(self.B):
+            p = self.next_pos[b]
+            q = p - self.w
+            for h in range(self.H):
+                st = self.heads[b][h]
+                ws = self.win_scores[b][h]
+                # the new token enters first, so that for w = 0 it is itself
+                # the token that "leaves" (q == p)
+                st.positions.append(p)
+                st.K_rows.append(np.array(k_new[b, h], copy=True))
+                st.V_rows.append(np.array(v_new[b, h], copy=True))
+                ws[p] = float(scores_new[b, h])
+                if q >= 0:
+                    s_q = ws.pop(q)
+                    if not (s_q >= self.tau):
+                        j = st.positions.index(q)
+                        del st.positions[j], st.K_rows[j], st.V_rows[j]
+            self.next_pos[b] = p + 1
+
+    def canonical(self, b: int, h: int):
+        st = self.heads[b][h]
+        D = st.K_rows[0].shape[0] if st.K_rows else 0
+        K = np.stack(st.K_rows) if st.K_rows else np.zeros((0, D), np.uint16)
+        V = np.stack(st.V_rows) if st.V_rows else np.zeros((0, D), np.uint16)
+        return np.array(st.positions, dtype=np.int64), K, V
+
+
+# --------------------------------------------------------------------------
+# analytic overhead model (App. B Eq. 4-6 and the overhead table)
+# --------------------------------------------------------------------------
+def flops_layer_linear_projections(H_Q: int, H: int, D: int, D_h: int,
+                                   D_int: int) -> int:
+    """Eq. 4: attention projections plus SwiGLU FFN, per token."""
+    return 4 * D_h * (H_Q * D + H * D) + 6 * D_h * D_int
+
+
+def flops_kvzap_mlp(D_h: int, H: int) -> int:
+    """Eq. 5: 2*D_h*(D_h/8) + 2*(D_h/8)*H per token."""
+    M = D_h // 8
+    return 2 * D_h * M + 2 * M * H
+
+
+def flops_kvzap_linear(D_h: int, H: int) -> int:
+    """Eq. 6: 2*D_h*H per token."""
+    return 2 * D_h * H
+
+
+def param_count(kind: str, L: int, D_h: int, H: int, biases: bool = False) -> int:
+    """Parameters of a list of L per-layer surrogates (Sec. 4.1 shapes)."""
+    M = D_h // 8
+    if kind == "mlp":
+        per = D_h * M + M * H + ((M + H) if biases else 0)
+    elif kind == "linear":
+        per = D_h * H + (H if biases else 0)
+    else:
+        raise ValueError(kind)
+    return L * per

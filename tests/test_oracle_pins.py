@@ -1,0 +1,327 @@
+"""Pins for the CPU oracle: each checks it against something other than itself
+(closed forms, values the paper prints, brute force, textbook identities)."""
+import math
+import os
+import random
+
+import numpy as np
+import pytest
+
+from oracle import brute_force as BF
+from oracle import kvzap_oracle as O
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rand_bits(rng, shape):
+    # random finite bf16 patterns, including -0 and subnormals
+    b = rng.integers(0, 1 << 16, size=shape, dtype=np.uint16)
+    exp = (b >> 7) & 0xFF
+    b[exp == 0xFF] &= np.uint16(0x807F)  # strip inf/nan exponents
+    return b
+
+
+# ---- bf16 up-cast ---------------------------------------------------------
+def test_bf16_upcast_known_patterns():
+    bits = np.array([0x3F80, 0xBF80, 0x4000, 0x3F00, 0x0000, 0x8000, 0x4049, 0x0001],
+                    dtype=np.uint16)
+    got = O.bf16_bits_to_f64(bits)
+    want = [1.0, -1.0, 2.0, 0.5, 0.0, -0.0, 3.140625, 2.0 ** -133]
+    assert got.tolist() == want
+    assert math.copysign(1.0, got[5]) == -1.0
+
+
+# ---- P7: GELU identities --------------------------------------------------
+def test_gelu_identities_and_library():
+    x = np.linspace(-8, 8, 4001)
+    g = O.gelu(x)
+    assert O.gelu(np.array([0.0]))[0] == 0.0
+    np.testing.assert_allclose(g - O.gelu(-x), x, atol=1e-14)        # odd part is x/2*2
+    assert abs(O.gelu(np.array([40.0]))[0] - 40.0) < 1e-300 + 1e-12
+    assert abs(O.gelu(np.array([-40.0]))[0]) < 1e-300
+    for xi in (-3.0, -1.0, -0.1, 0.3, 1.0, 2.5):
+        ref = xi * 0.5 * math.erfc(-xi / math.sqrt(2.0))              # x * Phi(x)
+        assert abs(O.gelu(np.array([xi]))[0] - ref) < 1e-15
+    # minimum of x*Phi(x): a textbook value, rules out the tanh/sigmoid forms' shapes
+    xm = x[np.argmin(g)]
+    assert abs(xm + 0.7518) < 5e-3 and abs(g.min() + 0.16997) < 1e-4
+
+
+def test_gelu_second_moment_closed_form():
+    # E[GELU(z)^2], z~N(0,1) by Gauss-Hermite quadrature (independent of the sample)
+    xs, ws = np.polynomial.hermite_e.hermegauss(200)
+    m2 = float(np.sum(ws * O.gelu(xs) ** 2) / math.sqrt(2 * math.pi))
+    assert abs(m2 - 0.4252) < 2e-4
+    # E[GELU(z)] = E[phi(z)] = 1/(2 sqrt(pi)) by Stein's lemma.  Hence, for fixed W2 and
+    # (nearly) independent unit-variance pre-activations, head h's scores over tokens have
+    # mean E[g]*sum(W2[:,h]) and variance (m2 - E[g]^2)*||W2[:,h]||^2.
+    m1 = float(np.sum(ws * O.gelu(xs)) / math.sqrt(2 * math.pi))
+    assert abs(m1 - 0.5 / math.sqrt(math.pi)) < 1e-12
+    rng = np.random.default_rng(0)
+    T, Dh, M, H = 4096, 1024, 512, 8
+    hid = rng.standard_normal((T, Dh))
+    W2 = rng.standard_normal((M, H)) / math.sqrt(M)
+    S = O.score_mlp(hid, rng.standard_normal((Dh, M)) / math.sqrt(Dh), None, W2, None)
+    for h in range(H):
+        assert abs(S[h].mean() - m1 * W2[:, h].sum()) < 0.05
+        want_std = math.sqrt((m2 - m1 * m1) * float((W2[:, h] ** 2).sum()))
+        assert abs(S[h].std() / want_std - 1.0) < 0.06
+
+
+# ---- P5: library steps against hand loops ---------------------------------
+def test_scorers_against_python_loops():
+    rng = random.Random(3)
+    T, Dh, M, H = 5, 7, 4, 3
+    hid = [[rng.uniform(-2, 2) for _ in range(Dh)] for _ in range(T)]
+    W1 = [[rng.uniform(-1, 1) for _ in range(M)] for _ in range(Dh)]
+    b1 = [rng.uniform(-1, 1) for _ in range(M)]
+    W2 = [[rng.uniform(-1, 1) for _ in range(H)] for _ in range(M)]
+    b2 = [rng.uniform(-1, 1) for _ in range(H)]
+    WL = [[rng.uniform(-1, 1) for _ in range(H)] for _ in range(Dh)]
+    bL = [rng.uniform(-1, 1) for _ in range(H)]
+    S_mlp = O.score_mlp(np.array(hid), np.array(W1), np.array(b1), np.array(W2), np.array(b2))
+    S_lin = O.score_linear(np.array(hid), np.array(WL), np.array(bL))
+    assert S_mlp.shape == (H, T) and S_lin.shape == (H, T)
+    for t in range(T):
+        g = []
+        for m in range(M):
+            z = b1[m] + sum(hid[t][k] * W1[k][m] for k in range(Dh))
+            g.append(0.5 * z * (1.0 + math.erf(z / math.sqrt(2.0))))
+        for h in range(H):
+            s = b2[h] + sum(g[m] * W2[m][h] for m in range(M))
+            assert abs(S_mlp[h, t] - s) < 1e-13
+            sl = bL[h] + sum(hid[t][k] * WL[k][h] for k in range(Dh))
+            assert abs(S_lin[h, t] - sl) < 1e-13
+    # no bias == zero bias
+    np.testing.assert_array_equal(
+        O.score_linear(np.array(hid), np.array(WL), None),
+        O.score_linear(np.array(hid), np.array(WL), np.zeros(H)))
+
+
+def test_one_hot_weights_select_columns():
+    # W = columns of the identity -> score[h, t] = hidden[t, c_h]: catches a transposed operand
+    rng = np.random.default_rng(1)
+    T, Dh, H = 9, 16, 4
+    hid = rng.standard_normal((T, Dh))
+    cols = [3, 0, 15, 7]
+    W = np.zeros((Dh, H))
+    for h, c in enumerate(cols):
+        W[c, h] = 1.0
+    S = O.score_linear(hid, W, None)
+    for h, c in enumerate(cols):
+        np.testing.assert_array_equal(S[h], hid[:, c])
+
+
+# ---- P6: exact integer inputs ---------------------------------------------
+def test_exact_integer_scores():
+    rng = np.random.default_rng(5)
+    T, Dh, H = 33, 64, 8
+    hid = rng.integers(-4, 5, (T, Dh)).astype(np.float64)
+    W = rng.integers(-1, 2, (Dh, H)).astype(np.float64)
+    b = rng.integers(-3, 4, H).astype(np.float64)
+    S = O.score_linear(hid, W, b)
+    want = (hid.astype(np.int64) @ W.astype(np.int64) + b.astype(np.int64)).T
+    np.testing.assert_array_equal(S, want.astype(np.float64))
+
+
+# ---- P1, P2, P3, P10 ------------------------------------------------------
+@pytest.mark.parametrize("T,w", [(1, 0), (1, 1), (7, 0), (7, 3), (7, 7), (7, 50), (300, 128)])
+def test_tau_limits_and_window(T, w):
+    rng = np.random.default_rng(T * 100 + w)
+    B, H, D = 2, 3, 8
+    S = rng.standard_normal((B, H, T))
+    K = _rand_bits(rng, (B, H, T, D))
+    V = _rand_bits(rng, (B, H, T, D))
+    lo = O.prune(S, -np.inf, w, K, V)
+    assert (lo.lengths == T).all()
+    np.testing.assert_array_equal(lo.K_out, K.reshape(-1, D))     # identity, byte for byte
+    np.testing.assert_array_equal(lo.V_out, V.reshape(-1, D))
+    hi = O.prune(S, np.inf, w, K, V)
+    assert (hi.lengths == min(w, T)).all()
+    for b in range(B):
+        for h in range(H):
+            np.testing.assert_array_equal(hi.idx[b][h], np.arange(T - min(w, T), T))
+    np.testing.assert_array_equal(hi.K_out.reshape(B, H, min(w, T), D), K[:, :, T - min(w, T):, :])
+
+
+def test_window_boundary_off_by_one():
+    # scores all below tau: exactly positions T-w .. T-1 survive, T-w-1 does not
+    T, w = 10, 4
+    S = np.full((1, 1, T), -1.0)
+    r = O.prune(S, 0.0, w)
+    assert r.idx[0][0].tolist() == [6, 7, 8, 9]
+
+
+def test_monotone_and_nested_in_tau():
+    rng = np.random.default_rng(11)
+    S = rng.standard_normal((2, 4, 200))
+    prev = None
+    for tau in np.linspace(-3, 3, 25):
+        r = O.prune(S, tau, 16)
+        sets = [[set(i.tolist()) for i in per_b] for per_b in r.idx]
+        if prev is not None:
+            for b in range(2):
+                for h in range(4):
+                    assert sets[b][h] <= prev[b][h]
+        prev = sets
+        # conservation
+        assert r.offsets[-1] == r.lengths.sum()
+        np.testing.assert_array_equal(np.diff(r.offsets), r.lengths.reshape(-1))
+        for per_b in r.idx:
+            for i in per_b:
+                assert set(range(200 - 16, 200)) <= set(i.tolist())
+                assert (np.diff(i) > 0).all() and i.min() >= 0 and i.max() < 200
+
+
+def test_ties_nan_and_inf_scores():
+    S = np.array([[[0.5, 0.25, np.nan, np.inf, -np.inf, 0.5, np.nan, 0.1]]])
+    r = O.prune(S, 0.5, 1)
+    assert r.idx[0][0].tolist() == [0, 3, 5, 7]       # equality keeps; NaN dropped; last protected
+    r = O.prune(S, np.inf, 2)
+    assert r.idx[0][0].tolist() == [3, 6, 7]          # +inf score >= +inf; NaN kept only by window
+    r = O.prune(S, -np.inf, 0)
+    assert r.idx[0][0].tolist() == [0, 1, 3, 4, 5, 7]  # NaN >= -inf is false
+
+
+def test_seq_lens_right_padding():
+    rng = np.random.default_rng(2)
+    B, H, T, D = 3, 2, 40, 4
+    S = rng.standard_normal((B, H, T))
+    K = _rand_bits(rng, (B, H, T, D)); V = _rand_bits(rng, (B, H, T, D))
+    lens = [40, 17, 0]
+    r = O.prune(S, 0.3, 5, K, V, seq_lens=lens)
+    for b, Tb in enumerate(lens):
+        single = O.prune(S[b:b + 1, :, :Tb], 0.3, 5, K[b:b + 1, :, :Tb], V[b:b + 1, :, :Tb])
+        for h in range(H):
+            np.testing.assert_array_equal(r.idx[b][h], single.idx[0][h])
+    assert (r.lengths[2] == 0).all()
+
+
+# ---- P4: brute force ------------------------------------------------------
+@pytest.mark.parametrize("seed", range(6))
+def test_brute_force_tiny(seed):
+    rng = random.Random(seed)
+    T = rng.randint(1, 10)
+    w = rng.randint(0, T + 1)
+    grid = [x * 0.5 for x in range(-3, 4)]           # coarse grid -> ties with tau happen
+    scores = [rng.choice(grid) for _ in range(T)]
+    tau = rng.choice(grid)
+    masks = BF.consistent_masks(scores, tau, w)
+    assert len(masks) == 1
+    keep = O.keep_mask(np.array([scores]), tau, w)
+    assert keep[0].tolist() == masks[0]
+    rows = [[rng.randrange(65536) for _ in range(3)] for _ in range(T)]
+    idx, n = O.kept_indices(keep)
+    got = O.gather_rows(np.array([rows], dtype=np.uint16), idx)
+    assert got.tolist() == BF.gather_loop(rows, masks[0])
+
+
+def test_threshold_sweep_equals_topk():
+    # between consecutive sorted scores the non-window kept set is the top-k by score
+    rng = np.random.default_rng(9)
+    T, w = 12, 3
+    s = rng.permutation(T).astype(np.float64)         # distinct
+    order = np.argsort(-s[:T - w])
+    srt = np.sort(s[:T - w])[::-1]
+    for k in range(1, T - w):
+        tau = 0.5 * (srt[k - 1] + srt[k])
+        idx, _ = O.kept_indices(O.keep_mask(s[None, :], tau, w))
+        non_window = [t for t in idx[0].tolist() if t < T - w]
+        assert sorted(non_window) == sorted(order[:k].tolist())
+
+
+def test_tau_at_keep_fraction():
+    rng = np.random.default_rng(4)
+    S = rng.standard_normal((2, 8, 1000))
+    for frac in (0.25, 0.5, 0.9):
+        tau = O.tau_at_keep_fraction(S, 128, frac)
+        assert tau == float(np.float32(tau))
+        kept = (S[:, :, :1000 - 128] >= tau).mean()
+        assert abs(kept - frac) < 1e-3
+
+
+# ---- P8: closed forms and printed values ----------------------------------
+def test_overhead_table_matches_printed_values():
+    rows = [l.split() for l in open(os.path.join(GOLD, "overhead_table.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) == 3
+    for name, HQ, H, D, Dh, Dint, mlp_pct, lin_pct in rows:
+        HQ, H, D, Dh, Dint = map(int, (HQ, H, D, Dh, Dint))
+        C = O.flops_layer_linear_projections(HQ, H, D, Dh, Dint)
+        assert round(100.0 * O.flops_kvzap_mlp(Dh, H) / C, 2) == float(mlp_pct)
+        assert round(100.0 * O.flops_kvzap_linear(Dh, H) / C, 2) == float(lin_pct)
+    assert O.flops_kvzap_mlp(4096, 8) == (4096 // 4) * (4096 + 8) == 4202496
+    assert O.flops_kvzap_mlp(5120, 8) == 6563840
+    assert O.flops_kvzap_linear(4096, 8) == 65536
+    assert O.flops_layer_linear_projections(32, 8, 128, 4096, 12288) == 385875968
+
+
+def test_parameter_counts_match_printed_values():
+    rows = [l.split() for l in open(os.path.join(GOLD, "param_counts.txt"))
+            if l.strip() and not l.startswith("#")]
+    for name, kind, L, Dh, H, printed, dec in rows:
+        for biases in (False, True):
+            n = O.param_count(kind, int(L), int(Dh), int(H), biases)
+            assert round(n / 1e6, int(dec)) == float(printed)
+    # eight separate per-head MLPs would be ~8x larger: the shared-MLP reading is the one that fits
+    assert round(8 * O.param_count("mlp", 36, 4096, 1) / 1e6) != 76
+
+
+# ---- P9: decode == prefill on the grown prefix ----------------------------
+@pytest.mark.parametrize("w,T0,n", [(0, 5, 9), (1, 0, 7), (4, 0, 12), (4, 3, 12), (4, 11, 10), (128, 200, 150)])
+def test_decode_equals_prefill(w, T0, n):
+    rng = np.random.default_rng(w * 1000 + T0)
+    B, H, D = 2, 3, 4
+    tau = 0.1
+    S = rng.standard_normal((B, H, T0 + n))
+    S[0, 0, ::5] = tau                                # exact ties
+    K = _rand_bits(rng, (B, H, T0 + n, D)); V = _rand_bits(rng, (B, H, T0 + n, D))
+    dec = O.DecodeOracle(B, H, w, tau)
+    for b in range(B):
+        dec.load_prefill(b, S[b, :, :T0], K[b, :, :T0], V[b, :, :T0])
+    for i in range(n):
+        t = T0 + i
+        dec.step(S[:, :, t], K[:, :, t], V[:, :, t])
+        if i in (0, n // 2, n - 1):
+            ref = O.prune(S[:, :, :t + 1], tau, w, K[:, :, :t + 1], V[:, :, :t + 1])
+            for b in range(B):
+                for h in range(H):
+                    pos, Kc, Vc = dec.canonical(b, h)
+                    np.testing.assert_array_equal(pos, ref.idx[b][h])
+                    o = ref.offsets[b * H + h]
+                    np.testing.assert_array_equal(Kc.reshape(-1, D), ref.K_out[o:o + len(pos)])
+                    np.testing.assert_array_equal(Vc.reshape(-1, D), ref.V_out[o:o + len(pos)])
+
+
+def test_decode_tau_limits():
+    rng = np.random.default_rng(0)
+    B, H, D, w, T0, n = 1, 2, 4, 3, 6, 8
+    S = rng.standard_normal((B, H, T0 + n))
+    K = _rand_bits(rng, (B, H, T0 + n, D)); V = _rand_bits(rng, (B, H, T0 + n, D))
+    for tau, growth in ((-np.inf, 1), (np.inf, 0)):
+        dec = O.DecodeOracle(B, H, w, tau)
+        dec.load_prefill(0, S[0, :, :T0], K[0, :, :T0], V[0, :, :T0])
+        n0 = [len(dec.heads[0][h].positions) for h in range(H)]
+        for i in range(n):
+            dec.step(S[:, :, T0 + i], K[:, :, T0 + i], V[:, :, T0 + i])
+            for h in range(H):
+                assert len(dec.heads[0][h].positions) == n0[h] + growth * (i + 1)
+
+
+# ---- whole Algorithm 1 on bf16 inputs --------------------------------------
+def test_compress_end_to_end_small():
+    from paper_2601_07891_amd import synth
+    wl = synth.with_size(synth.CONFIGS["c2_llama8b_32k_mlp"], T=300, Dh=256)
+    w = synth.make_weights(wl); hid = synth.make_hidden(wl); K, V = synth.make_kv(wl)
+    S, r0 = O.compress(synth.bits(hid), synth.bits(K), synth.bits(V), synth.oracle_weights(w), 0.0, 128)
+    tau = O.tau_at_keep_fraction(S, 128, 0.5)
+    S2, r = O.compress(synth.bits(hid), synth.bits(K), synth.bits(V), synth.oracle_weights(w), tau, 128)
+    np.testing.assert_array_equal(S, S2)
+    Kb = synth.bits(K)
+    for h in range(wl.H):
+        want = [t for t in range(300) if t >= 300 - 128 or S[0, h, t] >= tau]
+        assert r.idx[0][h].tolist() == want
+        o = r.offsets[h]
+        np.testing.assert_array_equal(r.K_out[o:o + len(want)], Kb[0, h, want])
+    removed = 1.0 - r.lengths.sum() / (wl.H * 300)
+    assert abs(removed - 0.5 * (300 - 128) / 300) < 0.02
