@@ -1,0 +1,249 @@
+"""ctypes binding of libkvzap.so: the same four calls as include/kvzap.h.
+
+Argument marshalling only: tensors are checked for device, dtype and
+contiguity, outputs and workspaces are allocated with torch when the caller
+does not pass them, raw pointers and the current HIP stream are handed to the C
+ABI.  Every step of the prune path runs in the library's kernels; there is no
+fallback, and a missing library is an error.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libkvzap.so")
+
+CALL_SCORE, CALL_MASK, CALL_COMPACT, CALL_DECODE_EVICT = 0, 1, 2, 3
+
+_c_void_p, _c_int, _c_float, _c_size_t, _c_int64 = (
+    ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t, ctypes.c_int64)
+
+# name -> (restype, argtypes); mirrors include/kvzap.h
+SIGNATURES = {
+    "kvzap_status_string": (ctypes.c_char_p, [_c_int]),
+    "kvzap_version": (ctypes.c_char_p, []),
+    "kvzap_workspace_bytes": (_c_size_t, [_c_int] * 6),
+    "kvzap_score": (_c_int, [_c_void_p] * 6 + [_c_int] * 5 + [_c_void_p, _c_size_t, _c_void_p]),
+    "kvzap_mask": (_c_int, [_c_void_p, _c_float, _c_int, _c_void_p, _c_int, _c_int, _c_int,
+                            _c_void_p, _c_void_p, _c_void_p, _c_void_p, _c_size_t, _c_void_p]),
+    "kvzap_compact": (_c_int, [_c_void_p] * 7 + [_c_int64] + [_c_int] * 4 + [_c_void_p]),
+    "kvzap_decode_evict": (_c_int, [_c_void_p] * 5 + [_c_int, _c_int] + [_c_void_p] * 12 +
+                           [_c_float] + [_c_int] * 4 + [_c_void_p, _c_void_p, _c_size_t,
+                                                        _c_void_p]),
+}
+
+
+class KvzapError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().kvzap_status_string(status).decode()
+        super().__init__(f"{where} failed: {msg} (status {status})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libkvzap.so (built by `python -m paper_2601_07891_amd.build`)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with __graft_entry__.build() "
+                "or `python paper_2601_07891_amd/build.py`; there is no fallback path")
+        handle = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(handle, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = handle
+    return _lib
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, torch.cuda.Stream):
+        return stream.cuda_stream or None
+    return int(stream) or None
+
+
+def _check(t: Optional[torch.Tensor], dtype, name: str, optional: bool = False):
+    if t is None:
+        if optional:
+            return
+        raise ValueError(f"{name} is required")
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    if t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+
+
+def _workspace(nbytes: int, device, workspace: Optional[torch.Tensor]):
+    if nbytes == 0:
+        return workspace, (0 if workspace is None else workspace.numel() * workspace.element_size())
+    if workspace is None:
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    return workspace, workspace.numel() * workspace.element_size()
+
+
+def kvzap_workspace_bytes(which_call: int, B: int, T: int, Dh: int, M: int, H: int) -> int:
+    return int(lib().kvzap_workspace_bytes(which_call, B, T, Dh, M, H))
+
+
+def kvzap_score(hidden: torch.Tensor, W1: torch.Tensor, b1: Optional[torch.Tensor],
+                W2: Optional[torch.Tensor], b2: Optional[torch.Tensor],
+                scores: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """hidden bf16 [B,T,Dh]; MLP: W1 [M,Dh], b1 [M], W2 [H,M], b2 [H];
+    linear: W1 [H,Dh], b1 [H], W2 = b2 = None.  Returns scores fp32 [B,H,T]."""
+    bf = torch.bfloat16
+    _check(hidden, bf, "hidden"); _check(W1, bf, "W1")
+    _check(b1, bf, "b1", True); _check(W2, bf, "W2", True); _check(b2, bf, "b2", True)
+    B, T, Dh = hidden.shape
+    if W2 is not None:
+        M, H = W1.shape[0], W2.shape[0]
+        if W1.shape != (M, Dh) or W2.shape != (H, M):
+            raise ValueError("W1 must be [M,Dh] and W2 [H,M]")
+        if (b1 is not None and b1.shape != (M,)) or (b2 is not None and b2.shape != (H,)):
+            raise ValueError("b1 must be [M] and b2 [H]")
+    else:
+        M, H = 0, W1.shape[0]
+        if W1.shape != (H, Dh) or (b1 is not None and b1.shape != (H,)):
+            raise ValueError("W1 must be [H,Dh] and b1 [H]")
+    if scores is None:
+        scores = torch.empty((B, H, T), dtype=torch.float32, device=hidden.device)
+    _check(scores, torch.float32, "scores")
+    if scores.shape != (B, H, T):
+        raise ValueError("scores must be [B,H,T]")
+    rc = lib().kvzap_score(_ptr(hidden), _ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2), _ptr(scores),
+                           B, T, Dh, M, H, None, 0, _stream(stream))
+    if rc != 0:
+        raise KvzapError(rc, "kvzap_score")
+    return scores
+
+
+def kvzap_mask(scores: torch.Tensor, tau: float, window: int,
+               seq_lens: Optional[torch.Tensor] = None,
+               keep_idx: Optional[torch.Tensor] = None,
+               lengths: Optional[torch.Tensor] = None,
+               offsets: Optional[torch.Tensor] = None,
+               workspace: Optional[torch.Tensor] = None, stream=None
+               ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+    """scores fp32 [B,H,T] -> (keep_idx int32 [B*H*T] packed, lengths int32 [B,H],
+    offsets int64 [B*H+1])."""
+    _check(scores, torch.float32, "scores")
+    _check(seq_lens, torch.int32, "seq_lens", True)
+    B, H, T = scores.shape
+    dev = scores.device
+    if keep_idx is None:
+        keep_idx = torch.empty(B * H * T, dtype=torch.int32, device=dev)
+    if lengths is None:
+        lengths = torch.empty((B, H), dtype=torch.int32, device=dev)
+    if offsets is None:
+        offsets = torch.empty(B * H + 1, dtype=torch.int64, device=dev)
+    _check(keep_idx, torch.int32, "keep_idx"); _check(lengths, torch.int32, "lengths")
+    _check(offsets, torch.int64, "offsets")
+    if keep_idx.numel() < B * H * T or lengths.numel() != B * H or offsets.numel() != B * H + 1:
+        raise ValueError("output buffers have the wrong size")
+    ws, ws_bytes = _workspace(kvzap_workspace_bytes(CALL_MASK, B, T, 0, 0, H), dev, workspace)
+    rc = lib().kvzap_mask(_ptr(scores), float(tau), int(window), _ptr(seq_lens), B, H, T,
+                          _ptr(keep_idx), _ptr(lengths), _ptr(offsets), _ptr(ws), ws_bytes,
+                          _stream(stream))
+    if rc != 0:
+        raise KvzapError(rc, "kvzap_mask")
+    return keep_idx, lengths, offsets
+
+
+def kvzap_compact(K: torch.Tensor, V: torch.Tensor, keep_idx: torch.Tensor,
+                  lengths: torch.Tensor, offsets: torch.Tensor,
+                  K_out: Optional[torch.Tensor] = None, V_out: Optional[torch.Tensor] = None,
+                  cap_rows: Optional[int] = None, stream=None
+                  ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """K, V bf16 [B,H,T,D] -> packed (K_out, V_out) bf16 [cap_rows, D]."""
+    bf = torch.bfloat16
+    _check(K, bf, "K"); _check(V, bf, "V")
+    _check(keep_idx, torch.int32, "keep_idx"); _check(lengths, torch.int32, "lengths")
+    _check(offsets, torch.int64, "offsets")
+    B, H, T, D = K.shape
+    if V.shape != K.shape:
+        raise ValueError("K and V must have the same shape")
+    if cap_rows is None:
+        cap_rows = B * H * T if K_out is None else K_out.shape[0]
+    if K_out is None:
+        K_out = torch.empty((cap_rows, D), dtype=bf, device=K.device)
+    if V_out is None:
+        V_out = torch.empty((cap_rows, D), dtype=bf, device=K.device)
+    _check(K_out, bf, "K_out"); _check(V_out, bf, "V_out")
+    if K_out.shape[0] < cap_rows or V_out.shape[0] < cap_rows or K_out.shape[1] != D:
+        raise ValueError("K_out / V_out smaller than cap_rows")
+    rc = lib().kvzap_compact(_ptr(K), _ptr(V), _ptr(keep_idx), _ptr(lengths), _ptr(offsets),
+                             _ptr(K_out), _ptr(V_out), int(cap_rows), B, H, T, D,
+                             _stream(stream))
+    if rc != 0:
+        raise KvzapError(rc, "kvzap_compact")
+    return K_out, V_out
+
+
+class DecodeState:
+    """Device buffers of the decode cache layout described in include/kvzap.h
+    (allocation and bookkeeping only; all updates happen in the library)."""
+
+    def __init__(self, B: int, H: int, D: int, window: int, slab_capacity, device):
+        cap = torch.as_tensor(slab_capacity, dtype=torch.int32).reshape(B * H)
+        off = torch.zeros(B * H, dtype=torch.int64)
+        off[1:] = torch.cumsum(cap.to(torch.int64), 0)[:-1]
+        total = int(cap.to(torch.int64).sum())
+        bf = torch.bfloat16
+        self.B, self.H, self.D, self.window = B, H, D, window
+        self.slab_capacity = cap.to(device)
+        self.slab_offsets = off.to(device)
+        self.K_prefix = torch.zeros((max(total, 1), D), dtype=bf, device=device)
+        self.V_prefix = torch.zeros((max(total, 1), D), dtype=bf, device=device)
+        self.prefix_pos = torch.full((max(total, 1),), -1, dtype=torch.int32, device=device)
+        w = max(window, 1)
+        self.K_ring = torch.zeros((B, H, w, D), dtype=bf, device=device)
+        self.V_ring = torch.zeros((B, H, w, D), dtype=bf, device=device)
+        self.score_ring = torch.zeros((B, H, w), dtype=torch.float32, device=device)
+        self.lengths = torch.zeros((B, H), dtype=torch.int32, device=device)
+        self.seq_pos = torch.zeros(B, dtype=torch.int32, device=device)
+        self.error_flag = torch.zeros(4, dtype=torch.int32, device=device)
+
+
+def kvzap_decode_evict(hidden_new: torch.Tensor, W1: torch.Tensor, b1, W2, b2,
+                       k_new: torch.Tensor, v_new: torch.Tensor, state: DecodeState,
+                       tau: float, workspace: Optional[torch.Tensor] = None,
+                       stream=None) -> None:
+    """One decode step of one layer: hidden_new bf16 [B,Dh], k_new/v_new bf16 [B,H,D];
+    `state` is updated in place."""
+    bf = torch.bfloat16
+    _check(hidden_new, bf, "hidden_new"); _check(W1, bf, "W1"); _check(b1, bf, "b1", True)
+    _check(W2, bf, "W2", True); _check(b2, bf, "b2", True)
+    _check(k_new, bf, "k_new"); _check(v_new, bf, "v_new")
+    B, Dh = hidden_new.shape
+    M = W1.shape[0] if W2 is not None else 0
+    st = state
+    if (B, st.H, st.D) != tuple(k_new.shape) or k_new.shape != v_new.shape or B != st.B:
+        raise ValueError("k_new / v_new must be [B,H,D] matching the state")
+    ws, ws_bytes = _workspace(
+        kvzap_workspace_bytes(CALL_DECODE_EVICT, B, 1, Dh, M, st.H), hidden_new.device, workspace)
+    ring = st.window > 0
+    rc = lib().kvzap_decode_evict(
+        _ptr(hidden_new), _ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2), Dh, M,
+        _ptr(k_new), _ptr(v_new), _ptr(st.K_prefix), _ptr(st.V_prefix), _ptr(st.prefix_pos),
+        _ptr(st.slab_offsets), _ptr(st.slab_capacity),
+        _ptr(st.K_ring) if ring else None, _ptr(st.V_ring) if ring else None,
+        _ptr(st.score_ring) if ring else None, _ptr(st.lengths), _ptr(st.seq_pos),
+        float(tau), int(st.window), B, st.H, st.D, _ptr(st.error_flag),
+        _ptr(ws), ws_bytes, _stream(stream))
+    if rc != 0:
+        raise KvzapError(rc, "kvzap_decode_evict")

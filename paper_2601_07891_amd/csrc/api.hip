@@ -1,0 +1,168 @@
+// Host side of the C ABI: argument validation and dispatch.  Nothing here
+// touches device memory or synchronises; every entry point either returns an
+// error before any launch or enqueues its kernels on the caller's stream.
+#include <limits.h>
+
+#include "kvzap_internal.h"
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
+
+constexpr int kMaxH = 16;
+constexpr int kMaxD = 512;
+constexpr int kMaxM = 640;
+constexpr size_t kLdsBytes = 160 * 1024;
+
+// shape rules shared by kvzap_score and kvzap_decode_evict
+int check_scorer_shape(int Dh, int M, int H) {
+  if (Dh <= 0 || M < 0 || H <= 0) return KVZAP_ERR_SHAPE;
+  if (H > kMaxH || Dh % 64 != 0) return KVZAP_ERR_UNSUPPORTED;
+  if (M > 0) {
+    if (M % 128 != 0 || M > kMaxM) return KVZAP_ERR_UNSUPPORTED;
+  } else {
+    if ((size_t)H * ((size_t)Dh * 2 + 64) > kLdsBytes) return KVZAP_ERR_UNSUPPORTED;
+  }
+  return KVZAP_OK;
+}
+
+size_t mask_workspace(int B, int H, int T) {
+  const size_t n = (size_t)B * H * kvzap::mask_chunks(T);
+  return kvzap::align_up(n * sizeof(int32_t), 256) + kvzap::align_up(n * sizeof(int64_t), 256);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* kvzap_status_string(int status) {
+  switch (status) {
+    case KVZAP_OK: return "ok";
+    case KVZAP_ERR_NULL: return "a required pointer is NULL";
+    case KVZAP_ERR_SHAPE: return "invalid size argument";
+    case KVZAP_ERR_ALIGN: return "pointer is not 16-byte aligned";
+    case KVZAP_ERR_UNSUPPORTED: return "shape outside the supported set";
+    case KVZAP_ERR_CAPACITY: return "output capacity too small";
+    case KVZAP_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case KVZAP_ERR_RUNTIME: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+const char* kvzap_version(void) { return "0.1.0"; }
+
+size_t kvzap_workspace_bytes(int which_call, int B, int T, int Dh, int M, int H) {
+  if (B <= 0 || T <= 0 || H <= 0) return 0;
+  switch (which_call) {
+    case KVZAP_CALL_MASK:
+      if ((long long)B * H > 65535) return 0;
+      return mask_workspace(B, H, T);
+    case KVZAP_CALL_DECODE_EVICT:
+      if (check_scorer_shape(Dh, M, H) != KVZAP_OK) return 0;
+      return kvzap::decode_workspace_bytes(B, Dh, M, H);
+    case KVZAP_CALL_SCORE:
+    case KVZAP_CALL_COMPACT:
+    default:
+      return 0;
+  }
+}
+
+int kvzap_score(const void* hidden, const void* W1, const void* b1, const void* W2,
+                const void* b2, float* scores, int B, int T, int Dh, int M, int H,
+                void* workspace, size_t workspace_bytes, void* stream) {
+  (void)workspace; (void)workspace_bytes;
+  if (B < 0 || T < 0) return KVZAP_ERR_SHAPE;
+  const int rc = check_scorer_shape(Dh, M, H);
+  if (rc != KVZAP_OK) return rc;
+  if ((long long)B * T > (long long)INT_MAX * 64) return KVZAP_ERR_SHAPE;
+  if ((long long)B * T == 0) return KVZAP_OK;
+  if (!hidden || !W1 || !scores) return KVZAP_ERR_NULL;
+  if (M > 0 && !W2) return KVZAP_ERR_NULL;
+  if (M == 0 && (W2 || b2)) return KVZAP_ERR_SHAPE;
+  if (!aligned16(hidden) || !aligned16(W1) || !aligned16(scores) || !aligned16(W2) ||
+      !aligned16(b1) || !aligned16(b2))
+    return KVZAP_ERR_ALIGN;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (M > 0) return kvzap::launch_score_mlp(hidden, W1, b1, W2, b2, scores, B, T, Dh, M, H, s);
+  return kvzap::launch_score_linear(hidden, W1, b1, scores, B, T, Dh, H, s);
+}
+
+int kvzap_mask(const float* scores, float tau, int window, const int32_t* seq_lens, int B,
+               int H, int T, int32_t* keep_idx, int32_t* lengths, int64_t* offsets,
+               void* workspace, size_t workspace_bytes, void* stream) {
+  if (B <= 0 || H <= 0 || T <= 0 || window < 0) return KVZAP_ERR_SHAPE;
+  if (tau != tau) return KVZAP_ERR_SHAPE;                 // NaN threshold
+  if ((long long)B * H > 65535) return KVZAP_ERR_UNSUPPORTED;
+  if (!scores || !keep_idx || !lengths || !offsets) return KVZAP_ERR_NULL;
+  if (!aligned16(scores) || !aligned16(keep_idx) || !aligned16(lengths) ||
+      !aligned16(offsets) || !aligned16(seq_lens))
+    return KVZAP_ERR_ALIGN;
+  if (!workspace || !aligned256(workspace) || workspace_bytes < mask_workspace(B, H, T))
+    return KVZAP_ERR_WORKSPACE;
+  return kvzap::launch_mask(scores, tau, window, seq_lens, B, H, T, keep_idx, lengths, offsets,
+                            workspace, static_cast<hipStream_t>(stream));
+}
+
+int kvzap_compact(const void* K, const void* V, const int32_t* keep_idx,
+                  const int32_t* lengths, const int64_t* offsets, void* K_out, void* V_out,
+                  int64_t cap_rows, int B, int H, int T, int D, void* stream) {
+  if (B <= 0 || H <= 0 || T <= 0 || D <= 0 || cap_rows < 0) return KVZAP_ERR_SHAPE;
+  if (D % 8 != 0 || D > kMaxD || (long long)B * H > 65535) return KVZAP_ERR_UNSUPPORTED;
+  if (!K || !V || !keep_idx || !lengths || !offsets || !K_out || !V_out) return KVZAP_ERR_NULL;
+  if (!aligned16(K) || !aligned16(V) || !aligned16(keep_idx) || !aligned16(lengths) ||
+      !aligned16(offsets) || !aligned16(K_out) || !aligned16(V_out))
+    return KVZAP_ERR_ALIGN;
+  {  // the gather is not an in-place operation
+    const size_t in_bytes = (size_t)B * H * T * D * 2, out_bytes = (size_t)cap_rows * D * 2;
+    auto overlaps = [](const void* a, size_t na, const void* b, size_t nb) {
+      const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+      return x < y + nb && y < x + na;
+    };
+    if (overlaps(K, in_bytes, K_out, out_bytes) || overlaps(V, in_bytes, K_out, out_bytes) ||
+        overlaps(K, in_bytes, V_out, out_bytes) || overlaps(V, in_bytes, V_out, out_bytes) ||
+        overlaps(K_out, out_bytes, V_out, out_bytes))
+      return KVZAP_ERR_SHAPE;
+  }
+  return kvzap::launch_compact(K, V, keep_idx, lengths, offsets, K_out, V_out, cap_rows, B * H,
+                               T, D, static_cast<hipStream_t>(stream));
+}
+
+int kvzap_decode_evict(const void* hidden_new, const void* W1, const void* b1, const void* W2,
+                       const void* b2, int Dh, int M, const void* k_new, const void* v_new,
+                       void* K_prefix, void* V_prefix, int32_t* prefix_pos,
+                       const int64_t* slab_offsets, const int32_t* slab_capacity, void* K_ring,
+                       void* V_ring, float* score_ring, int32_t* lengths, int32_t* seq_pos,
+                       float tau, int window, int B, int H, int D, int32_t* error_flag,
+                       void* workspace, size_t workspace_bytes, void* stream) {
+  if (B <= 0 || H <= 0 || D <= 0 || window < 0) return KVZAP_ERR_SHAPE;
+  if (tau != tau) return KVZAP_ERR_SHAPE;
+  const int rc = check_scorer_shape(Dh, M, H);
+  if (rc != KVZAP_OK) return rc;
+  if (D % 8 != 0 || D > kMaxD || B > 65535) return KVZAP_ERR_UNSUPPORTED;
+  if (!hidden_new || !W1 || !k_new || !v_new || !K_prefix || !V_prefix || !prefix_pos ||
+      !slab_offsets || !slab_capacity || !lengths || !seq_pos)
+    return KVZAP_ERR_NULL;
+  if (window > 0 && (!K_ring || !V_ring || !score_ring)) return KVZAP_ERR_NULL;
+  if (M > 0 && !W2) return KVZAP_ERR_NULL;
+  if (M == 0 && (W2 || b2)) return KVZAP_ERR_SHAPE;
+  const void* ptrs[] = {hidden_new, W1, b1, W2, b2, k_new, v_new, K_prefix, V_prefix,
+                        prefix_pos, slab_offsets, slab_capacity, K_ring, V_ring, score_ring,
+                        lengths, seq_pos};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return KVZAP_ERR_ALIGN;
+  const size_t need = kvzap::decode_workspace_bytes(B, Dh, M, H);
+  if (need > 0 && (!workspace || !aligned256(workspace) || workspace_bytes < need))
+    return KVZAP_ERR_WORKSPACE;
+  kvzap::DecodeArgs a;
+  a.hidden_new = hidden_new; a.W1 = W1; a.b1 = b1; a.W2 = W2; a.b2 = b2;
+  a.Dh = Dh; a.M = M; a.k_new = k_new; a.v_new = v_new;
+  a.K_prefix = K_prefix; a.V_prefix = V_prefix; a.prefix_pos = prefix_pos;
+  a.slab_offsets = slab_offsets; a.slab_capacity = slab_capacity;
+  a.K_ring = K_ring; a.V_ring = V_ring; a.score_ring = score_ring;
+  a.lengths = lengths; a.seq_pos = seq_pos; a.tau = tau; a.window = window;
+  a.B = B; a.H = H; a.D = D; a.error_flag = error_flag; a.workspace = workspace;
+  return kvzap::launch_decode_evict(a, static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,215 @@
+// One decoding step of one layer (caption of Algorithm 1; Sec. 2 "delayed
+// eviction with a sliding window"): score the new token of each sequence with
+// the surrogate, test the token that leaves the window against tau, append it
+// to the head's kept prefix or drop it, and put the new pair in its ring slot.
+//
+// Two launches:
+//   1. decode_partial : the first MLP projection for B new tokens is a skinny
+//      GEMM bound by reading W1 once; (unit-block x K-slice) blocks run
+//      v_mfma_f32_32x32x16_bf16 on operands loaded straight from global memory
+//      and write fp32 partial sums (fixed order -> deterministic).
+//   2. decode_finish  : one block per sequence sums the K-slices, applies bias,
+//      GELU and the M -> H projection in fp32, then performs the O(1)-row cache
+//      update of its H heads.  For the linear surrogate step 1 is skipped and the
+//      block computes the H dot products itself.
+// State layout: an append-only ascending prefix per (b,h) plus a `window`-row
+// ring indexed by position mod window: a token that leaves the window is copied
+// ring -> prefix tail if kept and is simply overwritten by the new token if not,
+// because the new token's slot (p mod w) is the leaving token's slot.
+#include "kvzap_internal.h"
+
+namespace kvzap {
+namespace {
+
+constexpr int kPThreads = 256;
+
+// how many K-slices the first projection is cut into
+inline int decode_ksplit(int B, int Dh, int M) {
+  const int nub = M / 32, ntb = (B + 63) / 64;
+  int target = 128 / (nub * ntb);
+  if (target < 1) target = 1;
+  const int units = Dh / 64;               // a slice is a multiple of 64 inputs
+  int ks = 1;
+  for (int d = 1; d <= units && d <= target; ++d)
+    if (units % d == 0) ks = d;
+  return ks;
+}
+
+__global__ __launch_bounds__(kPThreads) void decode_partial_kernel(
+    const unsigned short* __restrict__ hidden, const unsigned short* __restrict__ W1,
+    float* __restrict__ partial, int B, int Dh, int M, int kslice) {
+  __shared__ float red[4][2][16][64];
+  const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+  const int l32 = lane & 31, kg = lane >> 5;
+  const int ub = blockIdx.x, ks = blockIdx.y, tok0 = blockIdx.z * 64;
+  const int kw = kslice / 4;                           // inputs per wavefront (multiple of 16)
+  const int k_begin = ks * kslice + wid * kw + kg * 8;
+  const unsigned short* a_ptr = W1 + (size_t)(ub * 32 + l32) * Dh + k_begin;
+  const unsigned short* b_ptr[2];
+#pragma unroll
+  for (int tb = 0; tb < 2; ++tb) {
+    int tok = tok0 + tb * 32 + l32;
+    if (tok > B - 1) tok = B - 1;                      // clamp, discarded later
+    b_ptr[tb] = hidden + (size_t)tok * Dh + k_begin;
+  }
+  floatx16 acc[2];
+#pragma unroll
+  for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[tb][e] = 0.0f;
+  for (int k = 0; k < kw; k += 16) {
+    const bf16x8 a = *reinterpret_cast<const bf16x8*>(a_ptr + k);
+    const bf16x8 b0 = *reinterpret_cast<const bf16x8*>(b_ptr[0] + k);
+    const bf16x8 b1 = *reinterpret_cast<const bf16x8*>(b_ptr[1] + k);
+    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b0, acc[0], 0, 0, 0);
+    acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b1, acc[1], 0, 0, 0);
+  }
+#pragma unroll
+  for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) red[wid][tb][r][lane] = acc[tb][r];
+  __syncthreads();
+  for (int e = tid; e < 2 * 16 * 64; e += kPThreads) {
+    const int ln = e & 63, r = (e >> 6) & 15, tb = e >> 10;
+    const float s = ((red[0][tb][r][ln] + red[1][tb][r][ln]) + red[2][tb][r][ln]) + red[3][tb][r][ln];
+    const int unit = ub * 32 + 8 * (r / 4) + 4 * (ln >> 5) + (r % 4);
+    const int tok = tok0 + tb * 32 + (ln & 31);
+    if (tok < B) partial[((size_t)ks * B + tok) * M + unit] = s;
+  }
+}
+
+constexpr int kFThreads = 256;
+
+__device__ __forceinline__ float block_sum(float v, float* scratch) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float s = 0.f;
+#pragma unroll
+  for (int w = 0; w < kFThreads / 64; ++w) s += scratch[w];
+  return s;
+}
+
+__global__ __launch_bounds__(kFThreads) void decode_finish_kernel(DecodeArgs a, int ksplit) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  float* g = reinterpret_cast<float*>(smem);          // [M] (MLP) -- or unused
+  __shared__ float s_new[16], scratch[kFThreads / 64];
+  __shared__ int s_len[16], s_keep[16];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const int H = a.H, D = a.D, w = a.window, M = a.M, Dh = a.Dh;
+  const unsigned short* b1 = static_cast<const unsigned short*>(a.b1);
+  const unsigned short* b2 = static_cast<const unsigned short*>(a.b2);
+
+  // ---- 1. scores of the new token ----
+  if (M > 0) {
+    const float* partial = static_cast<const float*>(a.workspace);
+    for (int m = tid; m < M; m += kFThreads) {
+      float z = 0.f;
+      for (int ks = 0; ks < ksplit; ++ks) z += partial[((size_t)ks * a.B + b) * M + m];
+      if (b1) z += bf16_bits_to_float(b1[m]);
+      g[m] = 0.5f * z * (1.0f + erff(z * 0.70710678118654752f));
+    }
+    __syncthreads();
+    const unsigned short* W2 = static_cast<const unsigned short*>(a.W2);
+    for (int h = 0; h < H; ++h) {
+      float v = 0.f;
+      for (int m = tid; m < M; m += kFThreads) v += g[m] * bf16_bits_to_float(W2[(size_t)h * M + m]);
+      const float s = block_sum(v, scratch);
+      if (tid == 0) s_new[h] = s + (b2 ? bf16_bits_to_float(b2[h]) : 0.f);
+    }
+  } else {
+    const unsigned short* hid = static_cast<const unsigned short*>(a.hidden_new) + (size_t)b * Dh;
+    const unsigned short* W = static_cast<const unsigned short*>(a.W1);
+    for (int h = 0; h < H; ++h) {
+      float v = 0.f;
+      for (int k = tid; k < Dh; k += kFThreads)
+        v += bf16_bits_to_float(hid[k]) * bf16_bits_to_float(W[(size_t)h * Dh + k]);
+      const float s = block_sum(v, scratch);
+      if (tid == 0) s_new[h] = s + (b1 ? bf16_bits_to_float(b1[h]) : 0.f);
+    }
+  }
+  __syncthreads();
+
+  // ---- 2. which token leaves the window, and is it kept ----
+  const int p = a.seq_pos[b];
+  const int q = p - w;
+  const int slot = (w > 0) ? (p % w) : 0;
+  if (tid < H) {
+    const int bh = b * H + tid;
+    float s_q = s_new[tid];                               // w == 0: the new token itself
+    if (w > 0 && q >= 0) s_q = a.score_ring[(size_t)bh * w + slot];
+    s_len[tid] = a.lengths[bh];
+    s_keep[tid] = (q >= 0) && (s_q >= a.tau);
+  }
+  __syncthreads();
+
+  // ---- 3. move rows: ring -> prefix tail (kept), new -> ring slot ----
+  const int lpr = D / 8;
+  const u32x4* kn = static_cast<const u32x4*>(a.k_new) + (size_t)b * H * lpr;
+  const u32x4* vn = static_cast<const u32x4*>(a.v_new) + (size_t)b * H * lpr;
+  u32x4* Kp = static_cast<u32x4*>(a.K_prefix);
+  u32x4* Vp = static_cast<u32x4*>(a.V_prefix);
+  u32x4* Kr = static_cast<u32x4*>(a.K_ring);
+  u32x4* Vr = static_cast<u32x4*>(a.V_ring);
+  for (int i = tid; i < H * lpr; i += kFThreads) {
+    const int h = i / lpr, piece = i % lpr;
+    const int bh = b * H + h;
+    const u32x4 k_in = kn[(size_t)h * lpr + piece];
+    const u32x4 v_in = vn[(size_t)h * lpr + piece];
+    const size_t ring_at = ((size_t)bh * (w > 0 ? w : 1) + slot) * lpr + piece;
+    if (s_keep[h]) {
+      const int len = s_len[h];
+      if (len < a.slab_capacity[bh]) {
+        const size_t dst = ((size_t)a.slab_offsets[bh] + len) * lpr + piece;
+        Kp[dst] = (w > 0) ? Kr[ring_at] : k_in;
+        Vp[dst] = (w > 0) ? Vr[ring_at] : v_in;
+      }
+    }
+    if (w > 0) {
+      Kr[ring_at] = k_in;
+      Vr[ring_at] = v_in;
+    }
+  }
+  // ---- 4. bookkeeping ----
+  if (tid < H) {
+    const int bh = b * H + tid;
+    if (s_keep[tid]) {
+      const int len = s_len[tid];
+      if (len < a.slab_capacity[bh]) {
+        a.prefix_pos[(size_t)a.slab_offsets[bh] + len] = q;
+        a.lengths[bh] = len + 1;
+      } else if (a.error_flag) {
+        *a.error_flag = 1;
+      }
+    }
+    if (w > 0) a.score_ring[(size_t)bh * w + slot] = s_new[tid];
+  }
+  if (tid == 0) a.seq_pos[b] = p + 1;
+}
+
+}  // namespace
+
+size_t decode_workspace_bytes(int B, int Dh, int M, int H) {
+  (void)H;
+  if (M == 0) return 0;
+  return align_up((size_t)decode_ksplit(B, Dh, M) * B * M * sizeof(float), 256);
+}
+
+int launch_decode_evict(const DecodeArgs& a, hipStream_t stream) {
+  int ks = 0;
+  if (a.M > 0) {
+    ks = decode_ksplit(a.B, a.Dh, a.M);
+    const dim3 grid(a.M / 32, ks, (a.B + 63) / 64);
+    decode_partial_kernel<<<grid, kPThreads, 0, stream>>>(
+        static_cast<const unsigned short*>(a.hidden_new),
+        static_cast<const unsigned short*>(a.W1), static_cast<float*>(a.workspace), a.B,
+        a.Dh, a.M, a.Dh / ks);
+  }
+  const size_t lds = (size_t)(a.M > 0 ? a.M : 1) * sizeof(float);
+  decode_finish_kernel<<<a.B, kFThreads, lds, stream>>>(a, ks);
+  return hipGetLastError() == hipSuccess ? KVZAP_OK : KVZAP_ERR_RUNTIME;
+}
+
+}  // namespace kvzap

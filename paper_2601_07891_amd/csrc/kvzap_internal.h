@@ -1,0 +1,67 @@
+// Internal declarations shared by the host API and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "kvzap.h"
+
+namespace kvzap {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+// tokens handled by one block of the mask kernels
+constexpr int kMaskChunk = 1024;
+
+inline int mask_chunks(int T) { return (T + kMaskChunk - 1) / kMaskChunk; }
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// bf16 bit pattern -> fp32 (exact)
+__device__ __forceinline__ float bf16_bits_to_float(unsigned short b) {
+  return __uint_as_float(((unsigned int)b) << 16);
+}
+
+// fp32 -> bf16 bit pattern, round to nearest even (finite inputs)
+__device__ __forceinline__ unsigned short float_to_bf16_bits(float f) {
+  unsigned int u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (unsigned short)(u >> 16);
+}
+
+// launchers (each returns a kvzap_status); arguments are already validated
+int launch_mask(const float* scores, float tau, int window, const int32_t* seq_lens,
+                int B, int H, int T, int32_t* keep_idx, int32_t* lengths,
+                int64_t* offsets, void* workspace, hipStream_t stream);
+
+int launch_compact(const void* K, const void* V, const int32_t* keep_idx,
+                   const int32_t* lengths, const int64_t* offsets, void* K_out,
+                   void* V_out, int64_t cap_rows, int BH, int T, int D,
+                   hipStream_t stream);
+
+int launch_score_linear(const void* hidden, const void* W, const void* b, float* scores,
+                        int B, int T, int Dh, int H, hipStream_t stream);
+
+int launch_score_mlp(const void* hidden, const void* W1, const void* b1, const void* W2,
+                     const void* b2, float* scores, int B, int T, int Dh, int M, int H,
+                     hipStream_t stream);
+
+struct DecodeArgs {
+  const void* hidden_new; const void* W1; const void* b1; const void* W2; const void* b2;
+  int Dh, M;
+  const void* k_new; const void* v_new;
+  void* K_prefix; void* V_prefix; int32_t* prefix_pos;
+  const int64_t* slab_offsets; const int32_t* slab_capacity;
+  void* K_ring; void* V_ring; float* score_ring;
+  int32_t* lengths; int32_t* seq_pos;
+  float tau; int window, B, H, D;
+  int32_t* error_flag;
+  void* workspace;
+};
+int launch_decode_evict(const DecodeArgs& a, hipStream_t stream);
+size_t decode_workspace_bytes(int B, int Dh, int M, int H);
+
+}  // namespace kvzap

@@ -1,0 +1,164 @@
+// Threshold + sliding-window mask and per-head index lists (Sec. 3.3, Algorithm 1).
+//
+// Three small launches over scores [B*H, T] (4 bytes per flag, so the whole
+// stage moves ~1 % of the bytes of the K/V compaction that follows):
+//   1. count : one block per 1024-token chunk of one (b,h) row counts its kept flags
+//   2. scan  : a single block turns the chunk counts into exclusive prefixes and
+//              writes lengths[B,H] and offsets[B*H+1]
+//   3. emit  : every chunk recomputes its flags (scores are L2-resident by now),
+//              ranks them with a wave ballot + LDS scan and writes the ascending
+//              kept positions at its prefix
+// No block waits for another, so there is nothing that can spin.
+#include "kvzap_internal.h"
+
+namespace kvzap {
+namespace {
+
+constexpr int kThreads = 256;            // 4 wavefronts
+constexpr int kPerThread = kMaskChunk / kThreads;  // 4 consecutive tokens
+static_assert(kPerThread == 4, "one float4 per thread");
+
+struct Flags4 { unsigned bits; };
+
+// keep flags of tokens t0..t0+3 of one (b,h) row
+__device__ __forceinline__ unsigned keep_bits4(const float* __restrict__ row, int t0, int T,
+                                               int Tb, int window, float tau, bool vec_ok) {
+  float s[4];
+  if (vec_ok && t0 + 3 < T) {
+    const floatx4 v = *reinterpret_cast<const floatx4*>(row + t0);
+    s[0] = v.x; s[1] = v.y; s[2] = v.z; s[3] = v.w;
+  } else {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) s[e] = (t0 + e < T) ? row[t0 + e] : 0.0f;
+  }
+  const int first_protected = Tb - window;   // may be negative: everything protected
+  unsigned bits = 0;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int t = t0 + e;
+    const bool keep = (t < Tb) && ((t >= first_protected) || (s[e] >= tau));
+    bits |= (keep ? 1u : 0u) << e;
+  }
+  return bits;
+}
+
+__global__ __launch_bounds__(kThreads) void mask_count_kernel(
+    const float* __restrict__ scores, float tau, int window,
+    const int32_t* __restrict__ seq_lens, int H, int T, int nchunks,
+    int32_t* __restrict__ chunk_counts) {
+  const int chunk = blockIdx.x, bh = blockIdx.y;
+  const int Tb = seq_lens ? seq_lens[bh / H] : T;
+  const float* row = scores + (size_t)bh * T;
+  const bool vec_ok = (T % 4) == 0;
+  const int t0 = chunk * kMaskChunk + threadIdx.x * kPerThread;
+  const int c = __popc(keep_bits4(row, t0, T, Tb, window, tau, vec_ok));
+  // block sum: wave reduce then LDS
+  int v = c;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+  __shared__ int wave_sum[kThreads / 64];
+  if ((threadIdx.x & 63) == 0) wave_sum[threadIdx.x >> 6] = v;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int tot = 0;
+#pragma unroll
+    for (int w = 0; w < kThreads / 64; ++w) tot += wave_sum[w];
+    chunk_counts[(size_t)bh * nchunks + chunk] = tot;
+  }
+}
+
+constexpr int kScanThreads = 1024;
+
+__global__ __launch_bounds__(kScanThreads) void mask_scan_kernel(
+    const int32_t* __restrict__ chunk_counts, int64_t* chunk_prefix,
+    int BH, int nchunks, int32_t* __restrict__ lengths, int64_t* __restrict__ offsets) {
+  __shared__ long long wave_tot[kScanThreads / 64];
+  __shared__ long long carry_s;
+  const int n = BH * nchunks;
+  const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+  if (threadIdx.x == 0) carry_s = 0;
+  __syncthreads();
+  for (int base = 0; base < n; base += kScanThreads) {
+    const int i = base + threadIdx.x;
+    const long long v = (i < n) ? (long long)chunk_counts[i] : 0;
+    long long incl = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const long long up = __shfl_up(incl, off, 64);
+      if (lane >= off) incl += up;
+    }
+    if (lane == 63) wave_tot[wid] = incl;
+    __syncthreads();
+    long long before = carry_s;
+    for (int w = 0; w < wid; ++w) before += wave_tot[w];
+    if (i < n) chunk_prefix[i] = before + incl - v;
+    __syncthreads();
+    if (threadIdx.x == kScanThreads - 1) carry_s = before + incl;
+    __syncthreads();
+  }
+  // head starts: the prefix of a head's first chunk; written by this block above
+  __threadfence_block();
+  __syncthreads();
+  for (int bh = threadIdx.x; bh <= BH; bh += kScanThreads) {
+    const long long start = (bh < BH) ? chunk_prefix[(size_t)bh * nchunks] : carry_s;
+    offsets[bh] = start;
+    if (bh < BH) {
+      const long long end = (bh + 1 < BH) ? chunk_prefix[(size_t)(bh + 1) * nchunks] : carry_s;
+      lengths[bh] = (int32_t)(end - start);
+    }
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void mask_emit_kernel(
+    const float* __restrict__ scores, float tau, int window,
+    const int32_t* __restrict__ seq_lens, int H, int T, int nchunks,
+    const int64_t* __restrict__ chunk_prefix, int32_t* __restrict__ keep_idx) {
+  const int chunk = blockIdx.x, bh = blockIdx.y;
+  const int Tb = seq_lens ? seq_lens[bh / H] : T;
+  const float* row = scores + (size_t)bh * T;
+  const bool vec_ok = (T % 4) == 0;
+  const int t0 = chunk * kMaskChunk + threadIdx.x * kPerThread;
+  const unsigned bits = keep_bits4(row, t0, T, Tb, window, tau, vec_ok);
+  const int c = __popc(bits);
+  // exclusive scan of c over the block: within the wave by shuffles, across waves via LDS
+  const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+  int incl = c;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int up = __shfl_up(incl, off, 64);
+    if (lane >= off) incl += up;
+  }
+  __shared__ int wave_tot[kThreads / 64];
+  if (lane == 63) wave_tot[wid] = incl;
+  __syncthreads();
+  int before = 0;
+#pragma unroll
+  for (int w = 0; w < kThreads / 64; ++w) before += (w < wid) ? wave_tot[w] : 0;
+  int64_t pos = chunk_prefix[(size_t)bh * nchunks + chunk] + before + incl - c;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    if (bits & (1u << e)) keep_idx[pos++] = t0 + e;
+  }
+}
+
+}  // namespace
+
+int launch_mask(const float* scores, float tau, int window, const int32_t* seq_lens,
+                int B, int H, int T, int32_t* keep_idx, int32_t* lengths,
+                int64_t* offsets, void* workspace, hipStream_t stream) {
+  const int BH = B * H;
+  const int nchunks = mask_chunks(T);
+  int32_t* chunk_counts = static_cast<int32_t*>(workspace);
+  int64_t* chunk_prefix = reinterpret_cast<int64_t*>(
+      static_cast<char*>(workspace) + align_up((size_t)BH * nchunks * sizeof(int32_t), 256));
+  const dim3 grid(nchunks, BH);
+  mask_count_kernel<<<grid, kThreads, 0, stream>>>(scores, tau, window, seq_lens, H, T,
+                                                   nchunks, chunk_counts);
+  mask_scan_kernel<<<1, kScanThreads, 0, stream>>>(chunk_counts, chunk_prefix, BH, nchunks,
+                                                   lengths, offsets);
+  mask_emit_kernel<<<grid, kThreads, 0, stream>>>(scores, tau, window, seq_lens, H, T,
+                                                  nchunks, chunk_prefix, keep_idx);
+  return hipGetLastError() == hipSuccess ? KVZAP_OK : KVZAP_ERR_RUNTIME;
+}
+
+}  // namespace kvzap

@@ -1,0 +1,120 @@
+// KVzap-Linear forward (Sec. 3.3, Sec. 4.1; App. B Eq. 6): scores = hidden . W^T + b.
+//
+// With H = 8 outputs the arithmetic intensity is H flop per byte of hidden
+// state: the kernel is bound by streaming `hidden` from HBM exactly once.  Plain
+// vector ALUs would need 64 FMAs plus bf16 unpacking per 16-byte load, which at
+// 8 TB/s is more than the chip's fp32 vector rate; the matrix cores do the same
+// work at a few per cent utilisation, so the contraction runs on
+// v_mfma_f32_16x16x32_bf16 with tokens on the N side and heads (padded to 16) on
+// the M side:
+//   A (16 x 32)  = W rows (heads) from LDS, staged once per block
+//   B (32 x 16)  = 16 tokens x 32 inputs, loaded straight from global memory in
+//                  the instruction's operand layout (lane = token + 16*k-group,
+//                  16 bytes per lane), no LDS round trip for the streamed data
+//   C (16 x 16)  = fp32 accumulators, heads 0..15 x 16 tokens
+// Each wavefront owns groups of 16 consecutive tokens and walks the whole D_h.
+#include "kvzap_internal.h"
+
+namespace kvzap {
+namespace {
+
+constexpr int kThreads = 1024;         // 16 wavefronts share one copy of W in LDS
+constexpr int kWaves = kThreads / 64;
+constexpr int kUnroll = 8;             // independent 16-byte loads in flight per lane
+
+__global__ __launch_bounds__(kThreads) void score_linear_kernel(
+    const unsigned short* __restrict__ hidden, const unsigned short* __restrict__ W,
+    const unsigned short* __restrict__ bias, float* __restrict__ scores,
+    long long rows, int T, int Dh, int H, int groups_per_block) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  // W as [H][Dh/8 + 4] 16-byte pieces: the 64-byte pad per row spreads the 16
+  // (head, k-group) pieces one ds_read_b128 touches over distinct banks
+  u32x4* sW = reinterpret_cast<u32x4*>(smem);
+  const int pieces_per_row = Dh / 8;
+  const int lds_stride = pieces_per_row + 4;
+  for (int i = threadIdx.x; i < H * pieces_per_row; i += kThreads) {
+    const int h = i / pieces_per_row, p = i % pieces_per_row;
+    sW[h * lds_stride + p] = reinterpret_cast<const u32x4*>(W + (size_t)h * Dh)[p];
+  }
+  __syncthreads();
+
+  const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+  const int col = lane & 15;          // token within the group (B operand) / head (A operand)
+  const int kg = lane >> 4;           // which 8 of the 32 inputs of one MFMA
+  const long long ngroups = (rows + 15) / 16;
+  const long long g_begin = (long long)blockIdx.x * groups_per_block;
+  long long g_end = g_begin + groups_per_block;
+  if (g_end > ngroups) g_end = ngroups;
+  // lanes of the padded heads (col >= H) read a real row and zero it afterwards
+  const bool head_ok = col < H;
+  const u32x4* sWrow = sW + (size_t)(col % H) * lds_stride + kg;   // + 4*i per MFMA step
+  const int steps = Dh / 32;
+  const int steps_main = steps / kUnroll * kUnroll;
+  const u32x4 zero4 = {0u, 0u, 0u, 0u};
+
+  for (long long g = g_begin + wid; g < g_end; g += kWaves) {
+    long long r = g * 16 + col;
+    const bool valid = r < rows;
+    if (!valid) r = rows - 1;          // clamp: loads stay in bounds, result discarded
+    const u32x4* hrow = reinterpret_cast<const u32x4*>(hidden + (size_t)r * Dh) + kg;
+    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int i0 = 0; i0 < steps_main; i0 += kUnroll) {
+      u32x4 b[kUnroll];
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u)
+        b[u] = __builtin_nontemporal_load(hrow + (size_t)(i0 + u) * 4);
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        const u32x4 a = head_ok ? sWrow[(size_t)(i0 + u) * 4] : zero4;
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+            __builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b[u]), acc, 0, 0, 0);
+      }
+    }
+    for (int i = steps_main; i < steps; ++i) {
+      const u32x4 b = __builtin_nontemporal_load(hrow + (size_t)i * 4);
+      const u32x4 a = head_ok ? sWrow[(size_t)i * 4] : zero4;
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+          __builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+    }
+    // C layout: lane holds token `col`, heads 4*kg + e
+    if (valid) {
+      const long long bidx = r / T;
+      const long long t = r - bidx * T;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int h = 4 * kg + e;
+        if (h < H) {
+          const float bv = bias ? bf16_bits_to_float(bias[h]) : 0.0f;
+          scores[((size_t)bidx * H + h) * T + t] = acc[e] + bv;
+        }
+      }
+    }
+  }
+}
+
+}  // namespace
+
+int launch_score_linear(const void* hidden, const void* W, const void* b, float* scores,
+                        int B, int T, int Dh, int H, hipStream_t stream) {
+  const long long rows = (long long)B * T;
+  const long long ngroups = (rows + 15) / 16;
+  // about four blocks per CU's worth of work units, at least one group per wavefront
+  long long blocks = 256 * 2;
+  long long gpb = (ngroups + blocks - 1) / blocks;
+  if (gpb < kWaves) gpb = kWaves;
+  blocks = (ngroups + gpb - 1) / gpb;
+  const size_t lds = (size_t)H * ((size_t)Dh * 2 + 64);   // validated <= 160 KB by the caller
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(score_linear_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+      return KVZAP_ERR_RUNTIME;
+    attr_set = true;
+  }
+  score_linear_kernel<<<dim3((unsigned)blocks), kThreads, lds, stream>>>(
+      static_cast<const unsigned short*>(hidden), static_cast<const unsigned short*>(W),
+      static_cast<const unsigned short*>(b), scores, rows, T, Dh, H, (int)gpb);
+  return hipGetLastError() == hipSuccess ? KVZAP_OK : KVZAP_ERR_RUNTIME;
+}
+
+}  // namespace kvzap

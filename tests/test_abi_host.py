@@ -1,0 +1,157 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the
+header declares, and rejects bad arguments before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2601_07891_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _ensure_built():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2601_07891_amd import build
+        build.build(verbose=False)
+
+
+@pytest.fixture(scope="module")
+def lib():
+    _ensure_built()
+    return binding.lib()
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "kvzap.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(kvzap_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_functions()
+    assert set(names) == set(binding.SIGNATURES)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings(lib):
+    seen = set()
+    for code in range(0, -8, -1):
+        s = lib.kvzap_status_string(code).decode()
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 8
+    assert lib.kvzap_status_string(-99).decode() == "unknown status"
+    assert re.fullmatch(r"\d+\.\d+\.\d+", lib.kvzap_version().decode())
+
+
+def test_workspace_queries(lib):
+    q = lib.kvzap_workspace_bytes
+    assert q(binding.CALL_SCORE, 1, 1024, 4096, 512, 8) == 0
+    assert q(binding.CALL_COMPACT, 1, 1024, 0, 0, 8) == 0
+    n = q(binding.CALL_MASK, 1, 131072, 0, 0, 8)
+    chunks = 8 * 128
+    assert n >= chunks * 12 and n % 256 == 0
+    assert q(binding.CALL_MASK, 0, 1024, 0, 0, 8) == 0
+    assert q(binding.CALL_DECODE_EVICT, 64, 1, 4096, 512, 8) >= 64 * 512 * 4
+    assert q(binding.CALL_DECODE_EVICT, 64, 1, 4096, 0, 8) == 0
+    assert q(binding.CALL_DECODE_EVICT, 64, 1, 4096, 100, 8) == 0     # unsupported width
+
+
+P = 0x10000      # fake, aligned, never dereferenced: all calls below fail validation first
+ERR = dict(null=-1, shape=-2, align=-3, unsupported=-4, capacity=-5, workspace=-6)
+
+
+def test_score_argument_errors(lib):
+    f = lib.kvzap_score
+    assert f(None, P, None, None, None, P, 1, 16, 4096, 0, 8, None, 0, None) == ERR["null"]
+    assert f(P, P, None, None, None, None, 1, 16, 4096, 0, 8, None, 0, None) == ERR["null"]
+    assert f(P, P, None, None, None, P, 1, 16, 4096, 512, 8, None, 0, None) == ERR["null"]   # MLP without W2
+    assert f(P, P, None, P, None, P, 1, 16, 4096, 0, 8, None, 0, None) == ERR["shape"]      # linear with W2
+    assert f(P, P, None, None, None, P, -1, 16, 4096, 0, 8, None, 0, None) == ERR["shape"]
+    assert f(P, P, None, None, None, P, 1, 16, 0, 0, 8, None, 0, None) == ERR["shape"]
+    assert f(P, P, None, None, None, P, 1, 16, 4100, 0, 8, None, 0, None) == ERR["unsupported"]
+    assert f(P, P, None, P, None, P, 1, 16, 4096, 500, 8, None, 0, None) == ERR["unsupported"]
+    assert f(P, P, None, P, None, P, 1, 16, 4096, 768, 8, None, 0, None) == ERR["unsupported"]
+    assert f(P, P, None, None, None, P, 1, 16, 4096, 0, 17, None, 0, None) == ERR["unsupported"]
+    assert f(P + 2, P, None, None, None, P, 1, 16, 4096, 0, 8, None, 0, None) == ERR["align"]
+    assert f(P, P, P + 4, None, None, P, 1, 16, 4096, 0, 8, None, 0, None) == ERR["align"]
+    # empty input is a no-op that needs no pointers
+    assert f(None, None, None, None, None, None, 1, 0, 4096, 0, 8, None, 0, None) == 0
+
+
+def test_mask_argument_errors(lib):
+    f = lib.kvzap_mask
+    ws = lib.kvzap_workspace_bytes(binding.CALL_MASK, 1, 1024, 0, 0, 8)
+    ok = dict(scores=P, tau=0.0, window=128, seq=None, B=1, H=8, T=1024, idx=P, lens=P, offs=P,
+              ws=0x20000, wsb=ws, stream=None)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(a["scores"], a["tau"], a["window"], a["seq"], a["B"], a["H"], a["T"], a["idx"],
+                 a["lens"], a["offs"], a["ws"], a["wsb"], a["stream"])
+
+    assert call(scores=None) == ERR["null"]
+    assert call(idx=None) == ERR["null"]
+    assert call(window=-1) == ERR["shape"]
+    assert call(T=0) == ERR["shape"]
+    assert call(tau=float("nan")) == ERR["shape"]
+    assert call(B=10000, H=8) == ERR["unsupported"]
+    assert call(scores=P + 4) == ERR["align"]
+    assert call(ws=None) == ERR["workspace"]
+    assert call(wsb=ws - 1) == ERR["workspace"]
+    assert call(ws=0x20010) == ERR["workspace"]
+
+
+def test_compact_argument_errors(lib):
+    f = lib.kvzap_compact
+    big = 1 << 40
+    ok = [P, P + (1 << 30), P, P, P, big, big + (1 << 30), 8192, 1, 8, 1024, 128, None]
+
+    def call(i=None, v=None):
+        a = list(ok)
+        if i is not None:
+            a[i] = v
+        return f(*a)
+
+    assert call(0, None) == ERR["null"]
+    assert call(5, None) == ERR["null"]
+    assert call(11, 100) == ERR["unsupported"]
+    assert call(11, 1024) == ERR["unsupported"]
+    assert call(11, 0) == ERR["shape"]
+    assert call(7, -1) == ERR["shape"]
+    assert call(1, P + 6) == ERR["align"]
+    assert call(5, P) == ERR["shape"]                 # K_out aliases K
+    assert call(6, big) == ERR["shape"]               # V_out aliases K_out
+
+
+def test_decode_argument_errors(lib):
+    f = lib.kvzap_decode_evict
+    ws = lib.kvzap_workspace_bytes(binding.CALL_DECODE_EVICT, 4, 1, 4096, 512, 8)
+    ok = [P, P, None, P, None, 4096, 512, P, P, P, P, P, P, P, P, P, P, P, P,
+          0.0, 128, 4, 8, 128, None, 0x20000, ws, None]
+
+    def call(i=None, v=None):
+        a = list(ok)
+        if i is not None:
+            a[i] = v
+        return f(*a)
+
+    assert call(0, None) == ERR["null"]
+    assert call(14, None) == ERR["null"]              # ring required when window > 0
+    assert call(3, None) == ERR["null"]               # MLP needs W2
+    assert call(20, -1) == ERR["shape"]
+    assert call(6, 100) == ERR["unsupported"]
+    assert call(23, 12) == ERR["unsupported"]
+    assert call(9, P + 8) == ERR["align"]
+    assert call(25, None) == ERR["workspace"]
+    assert call(26, ws - 1) == ERR["workspace"]
+
+
+def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(FileNotFoundError):
+        binding.lib()

@@ -1,0 +1,161 @@
+"""GPU parity of kvzap_decode_evict against the decode oracle (canonical view:
+prefix rows followed by ring rows, sorted by position)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import kvzap_oracle as O
+from paper_2601_07891_amd import binding, synth
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _state_from_prefill(B, H, D, w, tau, S0, K0, V0, extra_cap):
+    """Build the device decode state from a prefill pruned by the oracle (test plumbing)."""
+    T0 = S0.shape[2]
+    ref = O.prune(S0, tau, w)
+    caps = np.zeros((B, H), dtype=np.int64)
+    for b in range(B):
+        for h in range(H):
+            caps[b, h] = len(ref.idx[b][h]) + extra_cap
+    st = binding.DecodeState(B, H, D, w, caps, DEV)
+    Kp = np.zeros((int(caps.sum()), D), np.uint16); Vp = np.zeros_like(Kp)
+    pos = np.full(int(caps.sum()), -1, np.int32)
+    lens = np.zeros((B, H), np.int32)
+    Kr = np.zeros((B, H, max(w, 1), D), np.uint16); Vr = np.zeros_like(Kr)
+    Sr = np.zeros((B, H, max(w, 1)), np.float32)
+    off = np.concatenate([[0], np.cumsum(caps.reshape(-1))[:-1]])
+    for b in range(B):
+        for h in range(H):
+            o = off[b * H + h]
+            for t in ref.idx[b][h]:
+                if t < T0 - w:
+                    Kp[o + lens[b, h]] = K0[b, h, t]; Vp[o + lens[b, h]] = V0[b, h, t]
+                    pos[o + lens[b, h]] = t; lens[b, h] += 1
+                else:
+                    Kr[b, h, t % w] = K0[b, h, t]; Vr[b, h, t % w] = V0[b, h, t]
+                    Sr[b, h, t % w] = S0[b, h, t]
+    st.K_prefix.copy_(torch.from_numpy(Kp.view(np.int16)).view(torch.bfloat16))
+    st.V_prefix.copy_(torch.from_numpy(Vp.view(np.int16)).view(torch.bfloat16))
+    st.prefix_pos.copy_(torch.from_numpy(pos))
+    st.K_ring.copy_(torch.from_numpy(Kr.view(np.int16)).view(torch.bfloat16))
+    st.V_ring.copy_(torch.from_numpy(Vr.view(np.int16)).view(torch.bfloat16))
+    st.score_ring.copy_(torch.from_numpy(Sr))
+    st.lengths.copy_(torch.from_numpy(lens))
+    st.seq_pos.fill_(T0)
+    return st
+
+
+def _canonical_gpu(st, b, h):
+    bh = b * st.H + h
+    o = int(st.slab_offsets[bh]); n = int(st.lengths.reshape(-1)[bh]); p = int(st.seq_pos[b])
+    pos = parity.to_np(st.prefix_pos[o:o + n]).astype(np.int64)
+    Kc = parity.to_np(st.K_prefix[o:o + n]); Vc = parity.to_np(st.V_prefix[o:o + n])
+    w = st.window
+    win = list(range(max(p - w, 0), p)) if w > 0 else []
+    slots = [t % w for t in win]
+    Kw = parity.to_np(st.K_ring[b, h])[slots] if win else np.zeros((0, st.D), np.uint16)
+    Vw = parity.to_np(st.V_ring[b, h])[slots] if win else np.zeros((0, st.D), np.uint16)
+    return (np.concatenate([pos, np.array(win, np.int64)]),
+            np.concatenate([Kc, Kw]), np.concatenate([Vc, Vw]))
+
+
+def _run_case(scorer, exact, B, H, D, Dh, M, w, T0, steps, tau, seed):
+    rng = np.random.default_rng(seed)
+    T = T0 + steps
+    if exact:
+        hid, wts = synth.make_exact_case(B * T, Dh, H, M, seed=seed)
+        hid = hid.reshape(B, T, Dh)
+    else:
+        wl = synth.Workload("d", L=1, B=B, T=T, Dh=Dh, H=H, D=D, scorer=scorer, seed=seed,
+                            bias_std=0.1)
+        hid = synth.make_hidden(wl)
+        g = torch.Generator().manual_seed(seed)
+        if scorer == "mlp":
+            wts = {"W1": (torch.randn((M, Dh), generator=g) * Dh ** -0.5).bfloat16(),
+                   "b1": (torch.randn((M,), generator=g) * 0.1).bfloat16(),
+                   "W2": (torch.randn((H, M), generator=g) * M ** -0.5).bfloat16(),
+                   "b2": (torch.randn((H,), generator=g) * 0.1).bfloat16()}
+        else:
+            wts = {"W1": (torch.randn((H, Dh), generator=g) * Dh ** -0.5).bfloat16(),
+                   "b1": (torch.randn((H,), generator=g) * 0.1).bfloat16(), "W2": None, "b2": None}
+    K = torch.randint(-32768, 32768, (B, H, T, D), dtype=torch.int16,
+                      generator=torch.Generator().manual_seed(seed + 1)).view(torch.bfloat16)
+    V = torch.randint(-32768, 32768, (B, H, T, D), dtype=torch.int16,
+                      generator=torch.Generator().manual_seed(seed + 2)).view(torch.bfloat16)
+    ow = synth.oracle_weights(wts)
+    S = []
+    for b in range(B):
+        h64 = O.bf16_bits_to_f64(synth.bits(hid[b]))
+        S.append(O.score_mlp(h64, ow["W1"], ow["b1"], ow["W2"], ow["b2"]) if "W1" in ow
+                 else O.score_linear(h64, ow["W"], ow["b"]))
+    S = np.stack(S)                                       # [B,H,T] float64
+    Kb, Vb = synth.bits(K), synth.bits(V)
+    # oracle: prefill T0 then decode; the GPU starts from the same prefill state
+    dec = O.DecodeOracle(B, H, w, tau)
+    for b in range(B):
+        dec.load_prefill(b, S[b, :, :T0], Kb[b, :, :T0], Vb[b, :, :T0])
+    S0 = S[:, :, :T0].astype(np.float32).astype(np.float64) if T0 else S[:, :, :0]
+    st = _state_from_prefill(B, H, D, w, tau, S[:, :, :T0], Kb[:, :, :T0], Vb[:, :, :T0], steps + 1)
+    d = {k: (None if v is None else v.to(DEV)) for k, v in wts.items()}
+    hid_d, K_d, V_d = hid.to(DEV), K.to(DEV), V.to(DEV)
+    for i in range(steps):
+        t = T0 + i
+        binding.kvzap_decode_evict(hid_d[:, t].contiguous(), d["W1"], d["b1"], d["W2"], d["b2"],
+                                   K_d[:, :, t].contiguous(), V_d[:, :, t].contiguous(), st, tau)
+        dec.step(S[:, :, t], Kb[:, :, t], Vb[:, :, t])
+    torch.cuda.synchronize()
+    assert int(st.error_flag[0]) == 0
+    assert (parity.to_np(st.seq_pos) == T).all()
+    band = 0.0 if exact else parity.BAND
+    for b in range(B):
+        for h in range(H):
+            pos, Kc, Vc = _canonical_gpu(st, b, h)
+            rpos, rK, rV = dec.canonical(b, h)
+            assert (np.diff(pos) > 0).all()
+            amb = np.abs(S[b, h] - tau) < band if band else np.zeros(T, bool)
+            np.testing.assert_array_equal(pos[~amb[pos]], rpos[~amb[rpos]])
+            np.testing.assert_array_equal(Kc, Kb[b, h][pos])      # rows are exact copies
+            np.testing.assert_array_equal(Vc, Vb[b, h][pos])
+            if not amb.any():
+                np.testing.assert_array_equal(Kc, rK.reshape(-1, D))
+    return st
+
+
+@pytest.mark.parametrize("w,T0,steps", [(0, 0, 9), (1, 0, 7), (4, 0, 12), (4, 3, 12), (4, 11, 10),
+                                        (128, 300, 200)])
+def test_decode_linear_exact(w, T0, steps):
+    _run_case("linear", True, B=3, H=8, D=128, Dh=256, M=0, w=w, T0=T0, steps=steps, tau=1.0,
+              seed=w * 10 + T0)
+
+
+@pytest.mark.parametrize("w,T0,steps", [(0, 5, 9), (4, 3, 12), (128, 200, 160)])
+def test_decode_mlp(w, T0, steps):
+    _run_case("mlp", False, B=5, H=8, D=128, Dh=1024, M=128, w=w, T0=T0, steps=steps, tau=0.05,
+              seed=w + 1)
+
+
+def test_decode_config5_shape_short():
+    # the decode benchmark's shape (B=64, D_h=4096, M=512) with short caches
+    _run_case("mlp", False, B=64, H=8, D=128, Dh=4096, M=512, w=128, T0=150, steps=140, tau=0.0,
+              seed=7)
+
+
+def test_decode_linear_random_and_other_dims():
+    _run_case("linear", False, B=2, H=3, D=64, Dh=512, M=0, w=16, T0=40, steps=40, tau=0.0, seed=3)
+
+
+def test_decode_full_slab_sets_error_flag():
+    B, H, D, Dh, w = 1, 2, 128, 256, 2
+    hid, wts = synth.make_exact_case(8, Dh, H, 0, seed=1)
+    st = binding.DecodeState(B, H, D, w, np.full((B, H), 2), DEV)
+    d = {k: (None if v is None else v.to(DEV)) for k, v in wts.items()}
+    kv = torch.ones((B, H, D), dtype=torch.bfloat16, device=DEV)
+    for t in range(8):
+        binding.kvzap_decode_evict(hid[:, t].to(DEV).contiguous(), d["W1"], d["b1"], None, None,
+                                   kv, kv, st, float("-inf"))
+    torch.cuda.synchronize()
+    assert int(st.error_flag[0]) == 1
+    assert (parity.to_np(st.lengths) == 2).all()                  # never beyond capacity

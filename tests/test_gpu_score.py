@@ -1,0 +1,122 @@
+"""GPU parity of kvzap_score (linear and MLP surrogates) against the float64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import kvzap_oracle as O
+from paper_2601_07891_amd import binding, synth
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _dev(w):
+    return {k: (None if v is None else v.to(DEV)) for k, v in w.items()}
+
+
+def _oracle_scores(hid, w):
+    ow = synth.oracle_weights(w)
+    out = []
+    for b in range(hid.shape[0]):
+        h64 = O.bf16_bits_to_f64(synth.bits(hid[b]))
+        if "W1" in ow:
+            out.append(O.score_mlp(h64, ow["W1"], ow["b1"], ow["W2"], ow["b2"]))
+        else:
+            out.append(O.score_linear(h64, ow["W"], ow["b"]))
+    return np.stack(out)
+
+
+def _gpu_scores(hid, w):
+    d = _dev(w)
+    s = binding.kvzap_score(hid.to(DEV), d["W1"], d["b1"], d["W2"], d["b2"])
+    torch.cuda.synchronize()
+    return s
+
+
+LINEAR_SHAPES = [(1, 1024, 4096, 8), (2, 333, 5120, 8), (1, 1, 64, 1), (3, 17, 192, 5),
+                 (1, 4099, 4096, 8), (1, 50, 1024, 16)]
+
+
+@pytest.mark.parametrize("B,T,Dh,H", LINEAR_SHAPES)
+def test_linear_random(B, T, Dh, H):
+    wl = synth.Workload("t", L=1, B=B, T=T, Dh=Dh, H=H, scorer="linear", seed=T, bias_std=0.1)
+    w = synth.make_weights(wl); hid = synth.make_hidden(wl)
+    parity.assert_scores_close(_gpu_scores(hid, w), _oracle_scores(hid, w))
+
+
+@pytest.mark.parametrize("T,Dh,H", [(1000, 4096, 8), (77, 320, 3)])
+def test_linear_exact_integers(T, Dh, H):
+    # every partial sum is a small integer: fp32 accumulation in any order is exact
+    hid, w = synth.make_exact_case(T, Dh, H, 0, seed=T)
+    got = parity.to_np(_gpu_scores(hid, w)).astype(np.float64)
+    np.testing.assert_array_equal(got, _oracle_scores(hid, w))
+
+
+def test_linear_one_hot_weights_pick_columns():
+    T, Dh, H = 130, 4096, 8
+    wl = synth.Workload("t", L=1, B=1, T=T, Dh=Dh, H=H, scorer="linear", seed=1)
+    hid = synth.make_hidden(wl)
+    W = torch.zeros((H, Dh), dtype=torch.bfloat16)
+    cols = [0, 7, 8, 31, 32, 2047, 4000, 4095]
+    for h, c in enumerate(cols):
+        W[h, c] = 1.0
+    got = parity.to_np(_gpu_scores(hid, {"W1": W, "b1": None, "W2": None, "b2": None}))
+    want = hid[0].float().numpy()[:, cols].T
+    np.testing.assert_array_equal(got[0], want)
+
+
+MLP_SHAPES = [(1, 300, 256, 128, 8), (2, 129, 1024, 128, 8), (1, 1000, 4096, 512, 8),
+              (1, 257, 5120, 640, 8), (1, 64, 2048, 256, 3), (1, 1, 3072, 384, 16),
+              (3, 50, 4096, 512, 8)]
+
+
+@pytest.mark.parametrize("B,T,Dh,M,H", MLP_SHAPES)
+def test_mlp_random(B, T, Dh, M, H):
+    wl = synth.Workload("t", L=1, B=B, T=T, Dh=Dh, H=H, scorer="mlp", seed=T + M, bias_std=0.1)
+    g = torch.Generator().manual_seed(T)
+    w = {"W1": (torch.randn((M, Dh), generator=g) * Dh ** -0.5).bfloat16(),
+         "b1": (torch.randn((M,), generator=g) * 0.1).bfloat16(),
+         "W2": (torch.randn((H, M), generator=g) * M ** -0.5).bfloat16(),
+         "b2": (torch.randn((H,), generator=g) * 0.1).bfloat16()}
+    hid = synth.make_hidden(wl)
+    err = parity.assert_scores_close(_gpu_scores(hid, w), _oracle_scores(hid, w))
+    assert err < 5e-3
+
+
+def test_mlp_no_bias_and_unit_selectivity():
+    # W2 one-hot: score[h] = GELU(z[unit_h]); checks the unit <-> lane/register mapping
+    # of the fused second projection for every unit position in a 32-block
+    T, Dh, M, H = 70, 512, 512, 8
+    wl = synth.Workload("t", L=1, B=1, T=T, Dh=Dh, H=H, scorer="mlp", seed=2)
+    hid = synth.make_hidden(wl)
+    g = torch.Generator().manual_seed(0)
+    W1 = (torch.randn((M, Dh), generator=g) * Dh ** -0.5).bfloat16()
+    for base in range(0, 64, 8):
+        W2 = torch.zeros((H, M), dtype=torch.bfloat16)
+        units = [(base + 37 * h + 64 * h) % M for h in range(H)]
+        for h, u in enumerate(units):
+            W2[h, u] = 1.0
+        w = {"W1": W1, "b1": None, "W2": W2, "b2": None}
+        parity.assert_scores_close(_gpu_scores(hid, w), _oracle_scores(hid, w))
+        z = hid[0].double().numpy() @ W1.double().numpy().T
+        want = O.gelu(z)[:, units].T
+        got = parity.to_np(_gpu_scores(hid, w))[0].astype(np.float64)
+        assert np.abs(got - want).max() < 2e-4
+
+
+def test_mlp_exact_first_projection():
+    # integer inputs: z is exact, so the only error left is GELU + second projection
+    T, Dh, M, H = 200, 256, 128, 8
+    hid, w = synth.make_exact_case(T, Dh, H, M, seed=3)
+    got = parity.to_np(_gpu_scores(hid, w)).astype(np.float64)
+    want = _oracle_scores(hid, w)
+    assert np.abs(got - want).max() <= 1e-4 * np.maximum(np.abs(want), 1).max()
+
+
+def test_scores_deterministic():
+    wl = synth.with_size(synth.CONFIGS["c2_llama8b_32k_mlp"], T=2000)
+    w = synth.make_weights(wl); hid = synth.make_hidden(wl)
+    a = _gpu_scores(hid, w).clone()
+    b = _gpu_scores(hid, w)
+    assert torch.equal(a, b)
