@@ -1,0 +1,225 @@
+#!/usr/bin/env python3
+"""Benchmark of the KVzap prune step (score -> mask -> compact) on one MI355X.
+
+One "step" is one pass of the whole prune path over every layer of the workload
+(default: the Qwen3-8B-shaped 128k-token prefill, 36 layers resident in HBM).
+Prints ONE JSON line; `value` is prune-step tokens/sec per layer, i.e. layer-tokens
+pruned per second with all inputs already in HBM.  The CPU oracle is timed next
+to it on a bounded sample (a baseline, not the target) and also supplies tau.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2601_07891_amd import binding, synth  # noqa: E402
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def _oracle_sample(wl, layer0, sample_tokens):
+    """Run the float64 oracle on the first `sample_tokens` tokens of layer 0 (every
+    sequence).  Returns (tau, timing dict, oracle scores)."""
+    from oracle import kvzap_oracle as O       # cpu_baseline leg only
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    hid = layer0["hidden"][:, :sample_tokens].contiguous()
+    K = layer0["K"][:, :, :sample_tokens].contiguous()
+    V = layer0["V"][:, :, :sample_tokens].contiguous()
+    hb, Kb, Vb = synth.bits(hid), synth.bits(K), synth.bits(V)
+    ow = synth.oracle_weights(layer0["w"])
+    B = hb.shape[0]
+    t0 = time.perf_counter()
+    S = []
+    for b in range(B):
+        h64 = O.bf16_bits_to_f64(hb[b])
+        S.append(O.score_mlp(h64, ow["W1"], ow["b1"], ow["W2"], ow["b2"]) if "W1" in ow
+                 else O.score_linear(h64, ow["W"], ow["b"]))
+        del h64
+    S = np.stack(S)
+    t1 = time.perf_counter()
+    # the sample is a prefix of each sequence: none of its tokens is in the window
+    tau = O.tau_at_keep_fraction(S, 0, wl.keep_fraction)
+    t2 = time.perf_counter()
+    res = O.prune(S, tau, 0, Kb, Vb)
+    t3 = time.perf_counter()
+    total = (t1 - t0) + (t3 - t2)
+    info = {"value": B * sample_tokens / total, "unit": "tokens/s per layer",
+            "cores": int(threads), "kind": "oracle",
+            "sample": f"layer 0, first {sample_tokens} tokens of each of {B} sequence(s), "
+                      f"float64 numpy score+mask+compact, window not in the sample",
+            "score_s": t1 - t0, "mask_compact_s": t3 - t2,
+            "kept_fraction": float(res.lengths.sum()) / (B * wl.H * sample_tokens)}
+    return tau, info, S
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default="c3_qwen8b_128k_mlp", choices=sorted(synth.CONFIGS))
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = config's)")
+    ap.add_argument("--sample-tokens", type=int, default=32768,
+                    help="tokens per sequence the CPU oracle is timed on")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(the path shards by layer / sequence / KV head with no communication)",
+              file=sys.stderr)
+        return 2
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    binding.lib()                                   # fail loudly if the library is not built
+    wl = synth.CONFIGS[args.config]
+    if wl.T == 1:
+        print("bench.py: the decode workload is measured by tests/bench of kvzap_decode_evict",
+              file=sys.stderr)
+        return 2
+    L = args.layers or wl.L
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    B, T, H, D, Dh, M = wl.B, wl.T, wl.H, wl.D, wl.Dh, wl.M
+
+    # ---- resident inputs and preallocated outputs for every layer ----
+    layers = []
+    for l in range(L):
+        w = synth.make_weights(wl, l, dev)
+        hidden = synth.make_hidden(wl, l, dev)
+        K, V = synth.make_kv(wl, l, dev)
+        cap = B * H * T
+        layers.append(dict(
+            w=w, hidden=hidden, K=K, V=V,
+            scores=torch.empty((B, H, T), dtype=torch.float32, device=dev),
+            idx=torch.empty(cap, dtype=torch.int32, device=dev),
+            n=torch.empty((B, H), dtype=torch.int32, device=dev),
+            off=torch.empty(B * H + 1, dtype=torch.int64, device=dev),
+            K_out=torch.empty((cap, D), dtype=torch.bfloat16, device=dev),
+            V_out=torch.empty((cap, D), dtype=torch.bfloat16, device=dev)))
+    ws = torch.empty(max(binding.kvzap_workspace_bytes(binding.CALL_MASK, B, T, 0, 0, H), 256),
+                     dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+
+    # ---- CPU oracle on a bounded sample: the reported baseline, and tau ----
+    sample_tokens = min(args.sample_tokens, max(T - wl.window, 1))
+    cpu_info = None
+    tau, cpu_info, S_ref = _oracle_sample(wl, layers[0], sample_tokens)
+
+    def score(ly):
+        w = ly["w"]
+        binding.kvzap_score(ly["hidden"], w["W1"], w["b1"], w["W2"], w["b2"], ly["scores"])
+
+    def mask(ly):
+        binding.kvzap_mask(ly["scores"], tau, wl.window, None, ly["idx"], ly["n"], ly["off"], ws)
+
+    def compact(ly):
+        binding.kvzap_compact(ly["K"], ly["V"], ly["idx"], ly["n"], ly["off"], ly["K_out"],
+                              ly["V_out"], B * H * T)
+
+    def step(events=None):
+        for ly in layers:
+            if events is not None:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                score(ly)
+                e1.record()
+                events.append((e0, e1))
+            else:
+                score(ly)
+            mask(ly)
+            compact(ly)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # sanity: the GPU scores of the sample agree with the oracle's (not a timed part)
+    got = layers[0]["scores"][:, :, :sample_tokens].double().cpu().numpy()
+    score_err = float(np.max(np.abs(got - S_ref) / np.maximum(np.abs(S_ref), 1.0)))
+
+    score_events = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(score_events)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens_per_step = L * B * T
+    value = tokens_per_step / (ms_per_step * 1e-3)
+    score_ms = float(np.mean([a.elapsed_time(b) for a, b in score_events]))
+
+    # ---- per-stage figures (outside the timed region) ----
+    def time_stage(fn, reps=3):
+        ev = []
+        for _ in range(reps):
+            for ly in layers:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(); fn(ly); e1.record()
+                ev.append((e0, e1))
+        torch.cuda.synchronize()
+        return float(np.mean([a.elapsed_time(b) for a, b in ev]))
+
+    mask_ms = time_stage(mask)
+    compact_ms = time_stage(compact)
+    kept_rows = float(np.mean([int(ly["off"][-1]) for ly in layers]))
+    kept_fraction = kept_rows / (B * H * T)
+
+    flops_per_token = 2 * Dh * M + 2 * M * H if M else 2 * Dh * H          # App. B Eq. 5 / Eq. 6
+    score_flops = flops_per_token * B * T
+    row_bytes = D * 2
+    compact_bytes = kept_rows * (2 * 2 * row_bytes + 4)      # read+write K and V rows, read idx
+    if M:
+        roofline = {"kernel": "score_mlp_kernel", "bound": "mfma",
+                    "achieved": score_flops / (score_ms * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS,
+                    "unit": "TFLOP/s", "traffic": None}
+    else:
+        roofline = {"kernel": "score_linear_kernel", "bound": "hbm",
+                    "achieved": (B * T * (2 * Dh + 4 * H)) / (score_ms * 1e-3) / 1e9,
+                    "peak": PEAK_HBM_GBS, "unit": "GB/s", "traffic": None}
+    roofline["frac"] = roofline["achieved"] / roofline["peak"]
+    roofline["avg_launch_ms"] = score_ms
+    compact_roof = {"kernel": "compact_kernel", "bound": "hbm",
+                    "achieved": compact_bytes / (compact_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                    "unit": "GB/s", "traffic": None, "avg_launch_ms": compact_ms}
+    compact_roof["frac"] = compact_roof["achieved"] / compact_roof["peak"]
+
+    out = {
+        "metric": "prune-step tokens/sec per layer (score+mask+compact)",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "layers": L, "batch": B, "seq_len": T, "d_model": Dh,
+                   "mlp_width": M, "kv_heads": H, "head_dim": D, "window": wl.window,
+                   "keep_fraction_target": wl.keep_fraction, "tau": tau,
+                   "kept_fraction_measured": kept_fraction, "scorer": wl.scorer,
+                   "generator": f"torch {torch.__version__} cuda philox, seeds per layer"},
+        "roofline": roofline,
+        "roofline_compact": compact_roof,
+        "stages_ms_per_layer": {"score": score_ms, "mask": mask_ms, "compact": compact_ms,
+                                "sum": score_ms + mask_ms + compact_ms,
+                                "wall": ms_per_step / L},
+        "score_max_rel_err_vs_oracle_sample": score_err,
+        "cpu_baseline": cpu_info,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
