@@ -28,18 +28,20 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
 
 def _oracle_sample(wl, layer0, sample_tokens):
-    """Run the float64 oracle on the first `sample_tokens` tokens of layer 0 (every
-    sequence).  Returns (tau, timing dict, oracle scores)."""
+    """Run the float64 oracle on the first `sample_tokens` tokens of every sequence
+    of layer 0 (all of them, window included, when sample_tokens == T).
+    Returns (tau, cpu_baseline dict, oracle scores [B,H,sample_tokens])."""
     from oracle import kvzap_oracle as O       # cpu_baseline leg only
     try:
         from threadpoolctl import threadpool_info
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = len(os.sched_getaffinity(0))
-    hid = layer0["hidden"][:, :sample_tokens].contiguous()
-    K = layer0["K"][:, :, :sample_tokens].contiguous()
-    V = layer0["V"][:, :, :sample_tokens].contiguous()
-    hb, Kb, Vb = synth.bits(hid), synth.bits(K), synth.bits(V)
+    full = sample_tokens == wl.T
+    window = wl.window if full else 0          # a proper prefix holds no window token
+    hb = synth.bits(layer0["hidden"][:, :sample_tokens])
+    Kb = synth.bits(layer0["K"][:, :, :sample_tokens])
+    Vb = synth.bits(layer0["V"][:, :, :sample_tokens])
     ow = synth.oracle_weights(layer0["w"])
     B = hb.shape[0]
     t0 = time.perf_counter()
@@ -51,16 +53,16 @@ def _oracle_sample(wl, layer0, sample_tokens):
         del h64
     S = np.stack(S)
     t1 = time.perf_counter()
-    # the sample is a prefix of each sequence: none of its tokens is in the window
-    tau = O.tau_at_keep_fraction(S, 0, wl.keep_fraction)
+    tau = O.tau_at_keep_fraction(S, window, wl.keep_fraction)     # workload recipe, untimed
     t2 = time.perf_counter()
-    res = O.prune(S, tau, 0, Kb, Vb)
+    res = O.prune(S, tau, window, Kb, Vb)
     t3 = time.perf_counter()
     total = (t1 - t0) + (t3 - t2)
-    info = {"value": B * sample_tokens / total, "unit": "tokens/s per layer",
+    what = "all" if full else "first"
+    info = {"value": B * sample_tokens / total, "unit": "tokens/s",
             "cores": int(threads), "kind": "oracle",
-            "sample": f"layer 0, first {sample_tokens} tokens of each of {B} sequence(s), "
-                      f"float64 numpy score+mask+compact, window not in the sample",
+            "sample": f"layer 0 of {wl.name}: {what} {sample_tokens} tokens of each of {B} "
+                      f"sequence(s); float64 numpy score + mask + compact, one pass",
             "score_s": t1 - t0, "mask_compact_s": t3 - t2,
             "kept_fraction": float(res.lengths.sum()) / (B * wl.H * sample_tokens)}
     return tau, info, S
@@ -73,9 +75,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", default="c3_qwen8b_128k_mlp", choices=sorted(synth.CONFIGS))
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = config's)")
-    ap.add_argument("--sample-tokens", type=int, default=32768,
-                    help="tokens per sequence the CPU oracle is timed on")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sample-tokens", type=int, default=0,
+                    help="tokens per sequence the CPU oracle is timed on (0 = all of layer 0)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -116,9 +119,17 @@ def main() -> int:
     torch.cuda.synchronize()
 
     # ---- CPU oracle on a bounded sample: the reported baseline, and tau ----
-    sample_tokens = min(args.sample_tokens, max(T - wl.window, 1))
-    cpu_info = None
+    sample_tokens = T if args.sample_tokens <= 0 else min(args.sample_tokens, T)
+    if sample_tokens < T:
+        sample_tokens = min(sample_tokens, max(T - wl.window, 1))
     tau, cpu_info, S_ref = _oracle_sample(wl, layers[0], sample_tokens)
+    if args.copy_calibration:                   # 1 GiB read + 1 GiB written by a plain copy
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     def score(ly):
         w = ly["w"]
