@@ -116,6 +116,8 @@ def main() -> int:
             V_out=torch.empty((cap, D), dtype=torch.bfloat16, device=dev)))
     ws = torch.empty(max(binding.kvzap_workspace_bytes(binding.CALL_MASK, B, T, 0, 0, H), 256),
                      dtype=torch.uint8, device=dev)
+    ws_score = torch.empty(max(binding.kvzap_workspace_bytes(binding.CALL_SCORE, B, T, Dh, M, H), 256),
+                           dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
 
     # ---- CPU oracle on a bounded sample: the reported baseline, and tau ----
@@ -133,7 +135,7 @@ def main() -> int:
 
     def score(ly):
         w = ly["w"]
-        binding.kvzap_score(ly["hidden"], w["W1"], w["b1"], w["W2"], w["b2"], ly["scores"])
+        binding.kvzap_score(ly["hidden"], w["W1"], w["b1"], w["W2"], w["b2"], ly["scores"], ws_score)
 
     def mask(ly):
         binding.kvzap_mask(ly["scores"], tau, wl.window, None, ly["idx"], ly["n"], ly["off"], ws)
@@ -196,7 +198,7 @@ def main() -> int:
     row_bytes = D * 2
     compact_bytes = kept_rows * (2 * 2 * row_bytes + 4)      # read+write K and V rows, read idx
     if M:
-        roofline = {"kernel": "score_mlp_kernel", "bound": "mfma",
+        roofline = {"kernel": "score_mlp_frag_kernel", "bound": "mfma",
                     "achieved": score_flops / (score_ms * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS,
                     "unit": "TFLOP/s", "traffic": None}
     else:

@@ -103,7 +103,8 @@ def kvzap_workspace_bytes(which_call: int, B: int, T: int, Dh: int, M: int, H: i
 
 def kvzap_score(hidden: torch.Tensor, W1: torch.Tensor, b1: Optional[torch.Tensor],
                 W2: Optional[torch.Tensor], b2: Optional[torch.Tensor],
-                scores: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+                scores: Optional[torch.Tensor] = None,
+                workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
     """hidden bf16 [B,T,Dh]; MLP: W1 [M,Dh], b1 [M], W2 [H,M], b2 [H];
     linear: W1 [H,Dh], b1 [H], W2 = b2 = None.  Returns scores fp32 [B,H,T]."""
     bf = torch.bfloat16
@@ -125,8 +126,10 @@ def kvzap_score(hidden: torch.Tensor, W1: torch.Tensor, b1: Optional[torch.Tenso
     _check(scores, torch.float32, "scores")
     if scores.shape != (B, H, T):
         raise ValueError("scores must be [B,H,T]")
+    ws, ws_bytes = _workspace(kvzap_workspace_bytes(CALL_SCORE, B, T, Dh, M, H), hidden.device,
+                              workspace)
     rc = lib().kvzap_score(_ptr(hidden), _ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2), _ptr(scores),
-                           B, T, Dh, M, H, None, 0, _stream(stream))
+                           B, T, Dh, M, H, _ptr(ws), ws_bytes, _stream(stream))
     if rc != 0:
         raise KvzapError(rc, "kvzap_score")
     return scores

@@ -62,6 +62,8 @@ size_t kvzap_workspace_bytes(int which_call, int B, int T, int Dh, int M, int H)
       if (check_scorer_shape(Dh, M, H) != KVZAP_OK) return 0;
       return kvzap::decode_workspace_bytes(B, Dh, M, H);
     case KVZAP_CALL_SCORE:
+      if (check_scorer_shape(Dh, M, H) != KVZAP_OK) return 0;
+      return M > 0 ? kvzap::align_up((size_t)M * Dh * 2, 256) : 0;   // W1 in fragment order
     case KVZAP_CALL_COMPACT:
     default:
       return 0;
@@ -71,7 +73,6 @@ size_t kvzap_workspace_bytes(int which_call, int B, int T, int Dh, int M, int H)
 int kvzap_score(const void* hidden, const void* W1, const void* b1, const void* W2,
                 const void* b2, float* scores, int B, int T, int Dh, int M, int H,
                 void* workspace, size_t workspace_bytes, void* stream) {
-  (void)workspace; (void)workspace_bytes;
   if (B < 0 || T < 0) return KVZAP_ERR_SHAPE;
   const int rc = check_scorer_shape(Dh, M, H);
   if (rc != KVZAP_OK) return rc;
@@ -84,7 +85,11 @@ int kvzap_score(const void* hidden, const void* W1, const void* b1, const void* 
       !aligned16(b1) || !aligned16(b2))
     return KVZAP_ERR_ALIGN;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (M > 0) return kvzap::launch_score_mlp(hidden, W1, b1, W2, b2, scores, B, T, Dh, M, H, s);
+  if (M > 0) {
+    const size_t need = kvzap::align_up((size_t)M * Dh * 2, 256);
+    if (!workspace || !aligned256(workspace) || workspace_bytes < need) return KVZAP_ERR_WORKSPACE;
+    return kvzap::launch_score_mlp(hidden, W1, b1, W2, b2, scores, B, T, Dh, M, H, workspace, s);
+  }
   return kvzap::launch_score_linear(hidden, W1, b1, scores, B, T, Dh, H, s);
 }
 

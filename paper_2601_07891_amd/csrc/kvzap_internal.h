@@ -47,7 +47,7 @@ int launch_score_linear(const void* hidden, const void* W, const void* b, float*
 
 int launch_score_mlp(const void* hidden, const void* W1, const void* b1, const void* W2,
                      const void* b2, float* scores, int B, int T, int Dh, int M, int H,
-                     hipStream_t stream);
+                     void* workspace, hipStream_t stream);
 
 struct DecodeArgs {
   const void* hidden_new; const void* W1; const void* b1; const void* W2; const void* b2;

@@ -17,6 +17,8 @@
 // from LDS.  LDS rows are 128 B with the 16-byte piece index XOR-swizzled by the
 // row, which keeps both the ds_write_b128 and the operand ds_read_b128 free of
 // bank conflicts.
+#include <type_traits>
+
 #include "kvzap_internal.h"
 
 namespace kvzap {
@@ -26,8 +28,22 @@ constexpr int kThreads = 512;
 constexpr int kTok = 128;     // tokens per block
 constexpr int kBK = 64;       // K per LDS tile
 
+// GELU(z) = z * Phi(z) with Phi from the rational erfc approximation of Abramowitz & Stegun
+// 7.1.26 (|error| <= 1.5e-7 on erf, i.e. at fp32 rounding level): one rcp, one exp2 and
+// ten FMA-class operations per element instead of the ~40 of a library erff, which matters
+// because the epilogue's vector ALU work is not overlapped with matrix-core work.
 __device__ __forceinline__ float gelu_exact(float z) {
-  return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f));
+  const float x = fabsf(z) * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
+  float p = fmaf(t, 1.061405429f, -1.453152027f);
+  p = fmaf(t, p, 1.421413741f);
+  p = fmaf(t, p, -0.284496736f);
+  p = fmaf(t, p, 0.254829592f);
+  // exp(-x^2) = 2^(-x^2 * log2(e))
+  const float e = __builtin_amdgcn_exp2f(x * x * -1.4426950408889634f);
+  const float half_erfc = 0.5f * (t * p) * e;          // 0.5 * erfc(|z| / sqrt 2)
+  const float phi = (z >= 0.0f) ? (1.0f - half_erfc) : half_erfc;
+  return z * phi;
 }
 
 __device__ __forceinline__ int lds_off(int row, int piece) {   // bytes
@@ -198,6 +214,285 @@ __global__ __launch_bounds__(kThreads) void score_mlp_kernel(
   }
 }
 
+
+// ---------------------------------------------------------------------------
+// Main variant (D_h >= 256).  What bounds the first projection on this chip is
+// not the matrix cores but feeding them: 5 GB of L2 -> CU operand traffic per
+// 128k-token launch.  So W1 never passes through LDS here:
+//   * a tiny pre-pass copies W1 into the workspace in MFMA A-fragment order
+//     ([k-tile][32-unit block][k-step][lane] x 16 B), so that every A fragment
+//     is ONE fully coalesced 1 KB load straight into registers;
+//   * each of the 4 wavefronts owns M/4 units x all 128 tokens (UB x 4
+//     accumulator blocks in the accumulation registers) and keeps a ring of
+//     one K tile of its own A fragments in registers: a fragment is re-loaded
+//     with the next tile's data right after its MFMAs, i.e. one tile ahead;
+//   * only `hidden` goes through LDS: a ring of kPD+1 stages of 128 rows x
+//     128 B filled by load-to-LDS kPD tiles ahead (it is the HBM-latency
+//     stream), rows swizzled by XOR-ing the 16-byte piece index with row & 7
+//     on the global-address side;
+//   * one barrier per 64-wide K tile; loads and LDS reads are interleaved
+//     between the MFMAs in source order and pinned with scheduling barriers.
+// ---------------------------------------------------------------------------
+constexpr int kPD = 3;                       // hidden tiles in flight
+constexpr int kNS = kPD + 1;                 // LDS stages
+constexpr int kHStage = kTok * 128;          // bytes per stage
+
+// Wait until at most N vector-memory operations of this wavefront are outstanding
+// (they complete in issue order).  Written as asm with a memory clobber so that the
+// compiler keeps every load that precedes it in the source before it.
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// Workgroup barrier that does NOT wait for outstanding vector-memory traffic (a
+// __syncthreads() would drain the prefetched tiles).  The caller has already
+// waited for the loads it needs; every LDS read issued before this point has been
+// consumed by an MFMA, so it has completed.  The "memory" clobber keeps the
+// compiler from moving LDS accesses across it.
+__device__ __forceinline__ void block_barrier_no_drain() {
+  asm volatile("s_barrier" ::: "memory");
+}
+
+// One load-to-LDS instruction: every lane fetches 16 bytes from its own global address and
+// the wavefront's 64 pieces land at LDS bytes [lds_base, lds_base + 1024) in lane order.
+// Issued as inline asm on purpose: the compiler tracks the builtin form as an LDS write
+// that may alias every later LDS read and then waits for ALL outstanding vector-memory
+// operations before those reads, which would undo the multi-tile prefetch.  Completion is
+// tracked by hand with wait_vmcnt(); the compiler's own vmcnt waits (for ordinary loads)
+// do not know about these operations and therefore only ever wait longer, never shorter.
+// M0 (the LDS base of the instruction) is written here and used nowhere else in the kernel.
+__device__ __forceinline__ void load_to_lds_b128(const void* gptr, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+               ::"s"(lds_base), "v"(gptr)
+               : "memory");
+}
+
+__device__ __forceinline__ unsigned lds_address(const void* p) {
+  return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+
+// W1 [M][Dh] -> A-fragment order: [Dh/64][M/32][4][64 lanes] x 16 B, where lane
+// (i = lane & 31, kg = lane >> 5) of k-step kk holds W1[rb*32 + i][kt*64 + kk*16 + kg*8 .. +8]
+__global__ __launch_bounds__(256) void arrange_w1_kernel(const u32x4* __restrict__ W1,
+                                                         u32x4* __restrict__ W1f, int M, int Dh) {
+  const int n = M * (Dh / 8);
+  const int rbs = M / 32;
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+    const int lane = i & 63, kk = (i >> 6) & 3, rb = (i >> 8) % rbs, kt = i / (256 * rbs);
+    const int row = rb * 32 + (lane & 31), piece = kt * 8 + kk * 2 + (lane >> 5);
+    W1f[i] = W1[(size_t)row * (Dh / 8) + piece];
+  }
+}
+
+template <int UB>
+__global__ __launch_bounds__(256) void score_mlp_frag_kernel(
+    const unsigned short* hidden, const unsigned char* W1f,   // not __restrict__: their loads must stay ordered w.r.t. the waits
+    const unsigned short* __restrict__ b1, const unsigned short* __restrict__ W2,
+    const unsigned short* __restrict__ b2, float* __restrict__ scores,
+    long long rows, int T, int Dh, int H) {
+  constexpr int U = 128 * UB;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, kg = lane >> 5;
+  const long long row0 = (long long)blockIdx.x * kTok;
+  const int rows_here = (rows - row0 < kTok) ? (int)(rows - row0) : kTok;
+
+  // hidden load-to-LDS: instruction j (0..3) of wavefront w fills LDS chunk j*4+w of a
+  // stage = rows (j*4+w)*8 + lane/8, physical piece lane%8 <- logical piece (lane%8) ^ (row%8)
+  const unsigned char* hb = reinterpret_cast<const unsigned char*>(hidden + (size_t)row0 * Dh);
+  unsigned h_off[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    int r = (j * 4 + wid) * 8 + (lane >> 3);
+    const int p = (lane & 7) ^ (r & 7);
+    if (r > rows_here - 1) r = rows_here - 1;            // clamp: in bounds, result discarded
+    h_off[j] = (unsigned)r * (unsigned)Dh * 2u + (unsigned)p * 16u;
+  }
+  const unsigned lds0 = lds_address(smem);
+  auto dma = [&](int j, int tile) {
+    load_to_lds_b128(hb + (size_t)tile * (kBK * 2) + h_off[j],
+                     lds0 + (unsigned)((tile % kNS) * kHStage + (j * 4 + wid) * 1024));
+  };
+  // A fragments of this wavefront: unit blocks rb = wid*UB + ub
+  const unsigned char* abase = W1f + ((size_t)wid * UB * 4) * 1024 + lane * 16;
+  auto aload = [&](int tile, int ub, int kk) -> bf16x8 {
+    return *reinterpret_cast<const bf16x8*>(abase + ((size_t)(tile * (U / 32) + ub) * 4 + kk) * 1024);
+  };
+
+  floatx16 acc[UB][4];
+#pragma unroll
+  for (int ub = 0; ub < UB; ++ub)
+#pragma unroll
+    for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[ub][tb][e] = 0.0f;
+
+  const int nk = Dh / kBK;                 // >= kPD + 1 (checked by the launcher)
+  bf16x8 a[4][UB];                         // a[kk]: step kk of the current tile, then of the next
+  bf16x8 b[2][4];
+  // ---- prologue: hidden tiles 0..kPD-1 in flight, A fragments of tile 0 ----
+#pragma unroll
+  for (int d = 0; d < kPD; ++d)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) dma(j, d);
+  // same issue order as in the main loop (the compiler sizes its own waits on the A
+  // fragments by their position in the load stream, on both paths into the loop)
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+    for (int ub = 0; ub < UB; ++ub) {
+      a[kk][ub] = aload(0, ub, kk);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  // hidden tile 0 = the four oldest operations; everything younger may stay in flight
+  __builtin_amdgcn_sched_barrier(0);
+  wait_vmcnt<4 * (kPD - 1) + 4 * UB>();
+  block_barrier_no_drain();
+  auto read_b = [&](int buf, int tile, int kk, int tb) {
+    b[buf][tb] = *reinterpret_cast<const bf16x8*>(
+        smem + (tile % kNS) * kHStage + lds_off(32 * tb + l32, kk * 2 + kg));
+  };
+#pragma unroll
+  for (int tb = 0; tb < 4; ++tb) read_b(0, 0, 0, tb);
+
+  // One K tile.  MORE: tile t+1 exists; MORE_PD: tile t+kPD exists.  Both are compile-time
+  // so that the body is a single basic block whose instruction order is the source order.
+  auto tile_body = [&](int t, auto more_tag, auto more_pd_tag) {
+    constexpr bool more = decltype(more_tag)::value, more_pd = decltype(more_pd_tag)::value;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+#pragma unroll
+      for (int ub = 0; ub < UB; ++ub) {
+        // B reads for the next step, (one hidden load-to-LDS), 4 MFMAs, then re-load this
+        // A fragment with the next tile's data
+        if (kk < 3) {
+#pragma unroll
+          for (int tb = 0; tb < 4; ++tb)
+            if (tb * UB / 4 == ub) read_b((kk + 1) & 1, t, kk + 1, tb);
+        }
+        if (more_pd && ub == 0) dma(kk, t + kPD);
+#pragma unroll
+        for (int tb = 0; tb < 4; ++tb)
+          acc[ub][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk][ub], b[kk & 1][tb],
+                                                                acc[ub][tb], 0, 0, 0);
+        if (more) a[kk][ub] = aload(t + 1, ub, kk);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    if (more) {
+      // hidden tile t+1 must have landed.  Its load-to-LDS operations are followed in this
+      // wavefront's in-order vector-memory stream by at least UB + (kPD-1)*4*UB A-fragment
+      // loads (the rest of their own tile, then two whole tiles), so allowing that many
+      // operations to stay outstanding is always sufficient.
+      wait_vmcnt<UB + (kPD - 1) * 4 * UB>();
+      block_barrier_no_drain();
+#pragma unroll
+      for (int tb = 0; tb < 4; ++tb) read_b(0, t + 1, 0, tb);
+    }
+  };
+  int t = 0;
+  for (; t + kPD < nk; ++t) tile_body(t, std::true_type{}, std::true_type{});
+  for (; t + 1 < nk; ++t) tile_body(t, std::true_type{}, std::false_type{});
+  tile_body(t, std::false_type{}, std::false_type{});
+  __syncthreads();      // LDS is reused for the reduction below
+
+  // ---- epilogue: bias + GELU, then the M -> H projection as a second MFMA ----
+  const int ubase = wid * (32 * UB);
+  floatx16 acc2[4];
+#pragma unroll
+  for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc2[tb][e] = 0.0f;
+#pragma unroll
+  for (int ub = 0; ub < UB; ++ub) {
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      const int u0 = ubase + 32 * ub + 16 * s + 4 * kg;
+      u32x4 w2 = {0u, 0u, 0u, 0u};
+      if (l32 < H) {
+        const uint2 p0 = *reinterpret_cast<const uint2*>(W2 + (size_t)l32 * U + u0);
+        const uint2 p1 = *reinterpret_cast<const uint2*>(W2 + (size_t)l32 * U + u0 + 8);
+        w2.x = p0.x; w2.y = p0.y; w2.z = p1.x; w2.w = p1.y;
+      }
+      float bias[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        bias[e] = b1 ? bf16_bits_to_float(b1[u0 + 8 * (e / 4) + (e % 4)]) : 0.0f;
+#pragma unroll
+      for (int tb = 0; tb < 4; ++tb) {
+        unsigned hi[4], lo[4];
+#pragma unroll
+        for (int e2 = 0; e2 < 4; ++e2) {
+          unsigned short h16[2], l16[2];
+#pragma unroll
+          for (int q = 0; q < 2; ++q) {
+            const int e = 2 * e2 + q;
+            const float g = gelu_exact(acc[ub][tb][8 * s + e] + bias[e]);
+            h16[q] = float_to_bf16_bits(g);
+            l16[q] = float_to_bf16_bits(g - bf16_bits_to_float(h16[q]));
+          }
+          hi[e2] = (unsigned)h16[0] | ((unsigned)h16[1] << 16);
+          lo[e2] = (unsigned)l16[0] | ((unsigned)l16[1] << 16);
+        }
+        const u32x4 ghi = {hi[0], hi[1], hi[2], hi[3]};
+        const u32x4 glo = {lo[0], lo[1], lo[2], lo[3]};
+        acc2[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+            __builtin_bit_cast(bf16x8, w2), __builtin_bit_cast(bf16x8, ghi), acc2[tb], 0, 0, 0);
+        acc2[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+            __builtin_bit_cast(bf16x8, w2), __builtin_bit_cast(bf16x8, glo), acc2[tb], 0, 0, 0);
+      }
+    }
+  }
+  float* red = reinterpret_cast<float*>(smem);     // [4][H][128]
+#pragma unroll
+  for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int head = 8 * (r / 4) + 4 * kg + (r % 4);
+      if (head < H) red[(wid * H + head) * kTok + 32 * tb + l32] = acc2[tb][r];
+    }
+  __syncthreads();
+  for (int i = tid; i < H * kTok; i += 256) {
+    const int head = i / kTok, tok = i % kTok;
+    const long long r = row0 + tok;
+    if (r < rows) {
+      float s = red[(0 * H + head) * kTok + tok];
+      s += red[(1 * H + head) * kTok + tok];
+      s += red[(2 * H + head) * kTok + tok];
+      s += red[(3 * H + head) * kTok + tok];
+      if (b2) s += bf16_bits_to_float(b2[head]);
+      const long long bidx = r / T, t = r - bidx * T;
+      scores[((size_t)bidx * H + head) * T + t] = s;
+    }
+  }
+}
+
+template <int UB>
+int launch_frag(const void* hidden, const void* W1, const void* b1, const void* W2,
+                const void* b2, float* scores, long long rows, int T, int Dh, int H,
+                void* workspace, hipStream_t stream) {
+  constexpr size_t lds = (size_t)kNS * kHStage;
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(score_mlp_frag_kernel<UB>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      return KVZAP_ERR_RUNTIME;
+    attr_set = true;
+  }
+  const int M = 128 * UB;
+  arrange_w1_kernel<<<512, 256, 0, stream>>>(static_cast<const u32x4*>(W1),
+                                             static_cast<u32x4*>(workspace), M, Dh);
+  const long long blocks = (rows + kTok - 1) / kTok;
+  score_mlp_frag_kernel<UB><<<dim3((unsigned)blocks), 256, lds, stream>>>(
+      static_cast<const unsigned short*>(hidden), static_cast<const unsigned char*>(workspace),
+      static_cast<const unsigned short*>(b1), static_cast<const unsigned short*>(W2),
+      static_cast<const unsigned short*>(b2), scores, rows, T, Dh, H);
+  return hipGetLastError() == hipSuccess ? KVZAP_OK : KVZAP_ERR_RUNTIME;
+}
+
 template <int UB>
 int launch_one(const void* hidden, const void* W1, const void* b1, const void* W2,
                const void* b2, float* scores, long long rows, int T, int Dh, int H,
@@ -222,16 +517,24 @@ int launch_one(const void* hidden, const void* W1, const void* b1, const void* W
 
 int launch_score_mlp(const void* hidden, const void* W1, const void* b1, const void* W2,
                      const void* b2, float* scores, int B, int T, int Dh, int M, int H,
-                     hipStream_t stream) {
+                     void* workspace, hipStream_t stream) {
   const long long rows = (long long)B * T;
+  const bool frag = (Dh / kBK) >= kPD + 1;     // the main variant needs at least kPD+1 K tiles
+#define KVZAP_MLP_CASE(UBV)                                                                     \
+  case UBV:                                                                                     \
+    return frag ? launch_frag<UBV>(hidden, W1, b1, W2, b2, scores, rows, T, Dh, H, workspace,   \
+                                   stream)                                                      \
+                : launch_one<UBV>(hidden, W1, b1, W2, b2, scores, rows, T, Dh, H, stream);
   switch (M / 128) {
-    case 1: return launch_one<1>(hidden, W1, b1, W2, b2, scores, rows, T, Dh, H, stream);
-    case 2: return launch_one<2>(hidden, W1, b1, W2, b2, scores, rows, T, Dh, H, stream);
-    case 3: return launch_one<3>(hidden, W1, b1, W2, b2, scores, rows, T, Dh, H, stream);
-    case 4: return launch_one<4>(hidden, W1, b1, W2, b2, scores, rows, T, Dh, H, stream);
-    case 5: return launch_one<5>(hidden, W1, b1, W2, b2, scores, rows, T, Dh, H, stream);
+    KVZAP_MLP_CASE(1)
+    KVZAP_MLP_CASE(2)
+    KVZAP_MLP_CASE(3)
+    KVZAP_MLP_CASE(4)
+    case 5:   // 320 accumulator registers do not fit beside the fragment ring: staged variant
+      return launch_one<5>(hidden, W1, b1, W2, b2, scores, rows, T, Dh, H, stream);
     default: return KVZAP_ERR_UNSUPPORTED;
   }
+#undef KVZAP_MLP_CASE
 }
 
 }  // namespace kvzap

@@ -49,7 +49,8 @@ def test_status_strings(lib):
 
 def test_workspace_queries(lib):
     q = lib.kvzap_workspace_bytes
-    assert q(binding.CALL_SCORE, 1, 1024, 4096, 512, 8) == 0
+    assert q(binding.CALL_SCORE, 1, 1024, 4096, 512, 8) == 512 * 4096 * 2   # re-ordered copy of W1
+    assert q(binding.CALL_SCORE, 1, 1024, 4096, 0, 8) == 0
     assert q(binding.CALL_COMPACT, 1, 1024, 0, 0, 8) == 0
     n = q(binding.CALL_MASK, 1, 131072, 0, 0, 8)
     chunks = 8 * 128
@@ -78,6 +79,8 @@ def test_score_argument_errors(lib):
     assert f(P, P, None, None, None, P, 1, 16, 4096, 0, 17, None, 0, None) == ERR["unsupported"]
     assert f(P + 2, P, None, None, None, P, 1, 16, 4096, 0, 8, None, 0, None) == ERR["align"]
     assert f(P, P, P + 4, None, None, P, 1, 16, 4096, 0, 8, None, 0, None) == ERR["align"]
+    assert f(P, P, None, P, None, P, 1, 16, 4096, 512, 8, None, 0, None) == ERR["workspace"]
+    assert f(P, P, None, P, None, P, 1, 16, 4096, 512, 8, 0x20000, 100, None) == ERR["workspace"]
     # empty input is a no-op that needs no pointers
     assert f(None, None, None, None, None, None, 1, 0, 4096, 0, 8, None, 0, None) == 0
 
