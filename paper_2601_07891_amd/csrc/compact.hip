@@ -4,8 +4,11 @@
 // once, dropped rows are never touched.  A row of D bf16 values is moved as
 // D/8 pieces of 16 bytes; consecutive lanes take consecutive pieces, so one
 // wavefront reads and writes whole rows with 16-byte accesses (a 128-dim row
-// is 256 B = 16 lanes, four rows per wavefront instruction).  Each thread keeps
-// several independent rows of K and of V in flight to cover HBM latency.
+// is 256 B = 16 lanes, four rows per wavefront instruction).  Latency is covered
+// by parallelism, not by per-thread unrolling: a thread moves one piece of a K
+// row and one of a V row per pass and the grid holds ~16k small blocks, which
+// measured faster (5.6-5.9 TB/s) than 2-8 rows in flight per thread with fewer
+// blocks (4.6-5.4 TB/s); non-temporal accesses are worth another 15 %.
 // The grid is (tiles, B*H): blocks of one head stride over that head's kept
 // rows, so no search for the owning head is needed and short heads simply run
 // out of tiles early.
@@ -15,7 +18,7 @@ namespace kvzap {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kRowsInFlight = 4;   // rows of K and of V per thread per iteration
+constexpr int kRowsInFlight = 1;   // rows of K and of V per thread per pass
 
 template <int LPR>  // lanes (16-byte pieces) per row
 __global__ __launch_bounds__(kThreads) void compact_kernel(
@@ -91,12 +94,12 @@ int launch_compact(const void* K, const void* V, const int32_t* keep_idx,
                    void* V_out, int64_t cap_rows, int BH, int T, int D,
                    hipStream_t stream) {
   const int lpr = D / 8;
-  // enough blocks to fill 256 CUs several times over, split evenly over heads
+  // ~16k blocks (64 per CU), split evenly over heads
   int tiles_per_head;
   {
     const int rows_per_tile = (kThreads / (lpr <= kThreads ? lpr : kThreads)) * kRowsInFlight;
     const int max_tiles = (T + rows_per_tile - 1) / rows_per_tile;
-    int want = (256 * 16 + BH - 1) / BH;
+    int want = (256 * 64 + BH - 1) / BH;
     tiles_per_head = want < max_tiles ? want : max_tiles;
     if (tiles_per_head < 1) tiles_per_head = 1;
   }
