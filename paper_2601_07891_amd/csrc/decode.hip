@@ -22,12 +22,14 @@ namespace kvzap {
 namespace {
 
 constexpr int kPThreads = 256;
+constexpr int kMaxKSplit = 16;
 
 // how many K-slices the first projection is cut into
 inline int decode_ksplit(int B, int Dh, int M) {
   const int nub = M / 32, ntb = (B + 63) / 64;
-  int target = 128 / (nub * ntb);
+  int target = 256 / (nub * ntb);
   if (target < 1) target = 1;
+  if (target > kMaxKSplit) target = kMaxKSplit;
   const int units = Dh / 64;               // a slice is a multiple of 64 inputs
   int ks = 1;
   for (int d = 1; d <= units && d <= target; ++d)
@@ -57,7 +59,23 @@ __global__ __launch_bounds__(kPThreads) void decode_partial_kernel(
   for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[tb][e] = 0.0f;
-  for (int k = 0; k < kw; k += 16) {
+  // latency-bound: keep the operand loads of four k-steps (12 x 16 B per lane) in flight
+  int k = 0;
+  for (; k + 64 <= kw; k += 64) {
+    bf16x8 a[4], b0[4], b1[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      a[s] = *reinterpret_cast<const bf16x8*>(a_ptr + k + 16 * s);
+      b0[s] = *reinterpret_cast<const bf16x8*>(b_ptr[0] + k + 16 * s);
+      b1[s] = *reinterpret_cast<const bf16x8*>(b_ptr[1] + k + 16 * s);
+    }
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s], b0[s], acc[0], 0, 0, 0);
+      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s], b1[s], acc[1], 0, 0, 0);
+    }
+  }
+  for (; k < kw; k += 16) {
     const bf16x8 a = *reinterpret_cast<const bf16x8*>(a_ptr + k);
     const bf16x8 b0 = *reinterpret_cast<const bf16x8*>(b_ptr[0] + k);
     const bf16x8 b1 = *reinterpret_cast<const bf16x8*>(b_ptr[1] + k);
@@ -80,111 +98,167 @@ __global__ __launch_bounds__(kPThreads) void decode_partial_kernel(
 
 constexpr int kFThreads = 256;
 
-__device__ __forceinline__ float block_sum(float v, float* scratch) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
-  __syncthreads();
-  float s = 0.f;
-#pragma unroll
-  for (int w = 0; w < kFThreads / 64; ++w) s += scratch[w];
-  return s;
-}
-
 __global__ __launch_bounds__(kFThreads) void decode_finish_kernel(DecodeArgs a, int ksplit) {
   extern __shared__ __align__(16) unsigned char smem[];
   float* g = reinterpret_cast<float*>(smem);          // [M] (MLP) -- or unused
-  __shared__ float s_new[16], scratch[kFThreads / 64];
-  __shared__ int s_len[16], s_keep[16];
+  __shared__ float s_new[16];
+  __shared__ int s_keep[16];
   const int b = blockIdx.x, tid = threadIdx.x;
   const int H = a.H, D = a.D, w = a.window, M = a.M, Dh = a.Dh;
   const unsigned short* b1 = static_cast<const unsigned short*>(a.b1);
   const unsigned short* b2 = static_cast<const unsigned short*>(a.b2);
 
-  // ---- 1. scores of the new token ----
-  if (M > 0) {
-    const float* partial = static_cast<const float*>(a.workspace);
-    for (int m = tid; m < M; m += kFThreads) {
-      float z = 0.f;
-      for (int ks = 0; ks < ksplit; ++ks) z += partial[((size_t)ks * a.B + b) * M + m];
-      if (b1) z += bf16_bits_to_float(b1[m]);
-      g[m] = 0.5f * z * (1.0f + erff(z * 0.70710678118654752f));
-    }
-    __syncthreads();
-    const unsigned short* W2 = static_cast<const unsigned short*>(a.W2);
-    for (int h = 0; h < H; ++h) {
-      float v = 0.f;
-      for (int m = tid; m < M; m += kFThreads) v += g[m] * bf16_bits_to_float(W2[(size_t)h * M + m]);
-      const float s = block_sum(v, scratch);
-      if (tid == 0) s_new[h] = s + (b2 ? bf16_bits_to_float(b2[h]) : 0.f);
-    }
-  } else {
-    const unsigned short* hid = static_cast<const unsigned short*>(a.hidden_new) + (size_t)b * Dh;
-    const unsigned short* W = static_cast<const unsigned short*>(a.W1);
-    for (int h = 0; h < H; ++h) {
-      float v = 0.f;
-      for (int k = tid; k < Dh; k += kFThreads)
-        v += bf16_bits_to_float(hid[k]) * bf16_bits_to_float(W[(size_t)h * Dh + k]);
-      const float s = block_sum(v, scratch);
-      if (tid == 0) s_new[h] = s + (b1 ? bf16_bits_to_float(b1[h]) : 0.f);
-    }
-  }
-  __syncthreads();
-
-  // ---- 2. which token leaves the window, and is it kept ----
+  // ---- 0. everything the cache update needs that does not depend on the new score is
+  // fetched first, so that its (HBM) latency overlaps the scorer arithmetic below: the
+  // position, and per (head, 16-byte piece) the new rows, the ring rows of the slot that is
+  // about to be vacated (read speculatively: they are only used if the token is kept), the
+  // head's length, slab offset and capacity, and the leaving token's score.
   const int p = a.seq_pos[b];
   const int q = p - w;
   const int slot = (w > 0) ? (p % w) : 0;
-  if (tid < H) {
-    const int bh = b * H + tid;
-    float s_q = s_new[tid];                               // w == 0: the new token itself
-    if (w > 0 && q >= 0) s_q = a.score_ring[(size_t)bh * w + slot];
-    s_len[tid] = a.lengths[bh];
-    s_keep[tid] = (q >= 0) && (s_q >= a.tau);
-  }
-  __syncthreads();
-
-  // ---- 3. move rows: ring -> prefix tail (kept), new -> ring slot ----
   const int lpr = D / 8;
+  const int npieces = H * lpr;                         // <= 16 * 64 = 1024 -> at most 4 per thread
+  constexpr int kMaxPer = 4;
+  u32x4 k_in[kMaxPer], v_in[kMaxPer], k_old[kMaxPer], v_old[kMaxPer];
+  int len_r[kMaxPer], cap_r[kMaxPer];
+  long long slab_r[kMaxPer];
   const u32x4* kn = static_cast<const u32x4*>(a.k_new) + (size_t)b * H * lpr;
   const u32x4* vn = static_cast<const u32x4*>(a.v_new) + (size_t)b * H * lpr;
   u32x4* Kp = static_cast<u32x4*>(a.K_prefix);
   u32x4* Vp = static_cast<u32x4*>(a.V_prefix);
   u32x4* Kr = static_cast<u32x4*>(a.K_ring);
   u32x4* Vr = static_cast<u32x4*>(a.V_ring);
-  for (int i = tid; i < H * lpr; i += kFThreads) {
-    const int h = i / lpr, piece = i % lpr;
-    const int bh = b * H + h;
-    const u32x4 k_in = kn[(size_t)h * lpr + piece];
-    const u32x4 v_in = vn[(size_t)h * lpr + piece];
-    const size_t ring_at = ((size_t)bh * (w > 0 ? w : 1) + slot) * lpr + piece;
-    if (s_keep[h]) {
-      const int len = s_len[h];
-      if (len < a.slab_capacity[bh]) {
-        const size_t dst = ((size_t)a.slab_offsets[bh] + len) * lpr + piece;
-        Kp[dst] = (w > 0) ? Kr[ring_at] : k_in;
-        Vp[dst] = (w > 0) ? Vr[ring_at] : v_in;
+#pragma unroll
+  for (int c = 0; c < kMaxPer; ++c) {
+    const int i = tid + c * kFThreads;
+    if (i < npieces) {
+      const int h = i / lpr, piece = i % lpr, bh = b * H + h;
+      k_in[c] = kn[i];
+      v_in[c] = vn[i];
+      len_r[c] = a.lengths[bh];
+      cap_r[c] = a.slab_capacity[bh];
+      slab_r[c] = a.slab_offsets[bh];
+      if (w > 0 && q >= 0) {
+        const size_t ring_at = ((size_t)bh * w + slot) * lpr + piece;
+        k_old[c] = Kr[ring_at];
+        v_old[c] = Vr[ring_at];
       }
-    }
-    if (w > 0) {
-      Kr[ring_at] = k_in;
-      Vr[ring_at] = v_in;
     }
   }
-  // ---- 4. bookkeeping ----
+  float s_q_r = 0.0f;
+  if (tid < H && w > 0 && q >= 0) s_q_r = a.score_ring[(size_t)(b * H + tid) * w + slot];
+  // second-projection weights of this thread's hidden units (M <= 640 -> at most 3 per head)
+  constexpr int kMaxUnits = 3;
+  unsigned short w2r[16][kMaxUnits];
+  if (M > 0) {
+    const unsigned short* W2 = static_cast<const unsigned short*>(a.W2);
+#pragma unroll
+    for (int h = 0; h < 16; ++h)
+#pragma unroll
+      for (int u = 0; u < kMaxUnits; ++u) {
+        const int m = tid + u * kFThreads;
+        w2r[h][u] = (h < H && m < M) ? W2[(size_t)h * M + m] : (unsigned short)0;
+      }
+  }
+
+  // ---- 1. scores of the new token ----
+  if (M > 0) {
+    const float* partial = static_cast<const float*>(a.workspace);
+    for (int m = tid; m < M; m += kFThreads) {
+      // the partial sums were written by other XCDs, so each read is a trip to memory: issue
+      // all K-slices' loads together (ksplit <= kMaxKSplit), then add them in a fixed order
+      float part[kMaxKSplit];
+#pragma unroll
+      for (int ks = 0; ks < kMaxKSplit; ++ks)
+        part[ks] = (ks < ksplit) ? partial[((size_t)ks * a.B + b) * M + m] : 0.0f;
+      float z = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < kMaxKSplit; ++ks) z += part[ks];
+      if (b1) z += bf16_bits_to_float(b1[m]);
+      g[m] = 0.5f * z * (1.0f + erff(z * 0.70710678118654752f));
+    }
+    __syncthreads();
+  }
+  // all H dot products at once: every load below is independent of the others, and a single
+  // block reduction follows (a loop over heads with a barrier each would serialise H memory
+  // round trips)
+  float dot[16];
+#pragma unroll
+  for (int h = 0; h < 16; ++h) dot[h] = 0.f;
+  if (M > 0) {
+#pragma unroll
+    for (int u = 0; u < kMaxUnits; ++u) {
+      const int m = tid + u * kFThreads;
+      const float gm = (m < M) ? g[m] : 0.f;
+#pragma unroll
+      for (int h = 0; h < 16; ++h) dot[h] += gm * bf16_bits_to_float(w2r[h][u]);
+    }
+  } else {
+    const unsigned short* hid = static_cast<const unsigned short*>(a.hidden_new) + (size_t)b * Dh;
+    const unsigned short* W = static_cast<const unsigned short*>(a.W1);
+    for (int k = tid; k < Dh; k += kFThreads) {
+      const float x = bf16_bits_to_float(hid[k]);
+#pragma unroll
+      for (int h = 0; h < 16; ++h)
+        if (h < H) dot[h] += x * bf16_bits_to_float(W[(size_t)h * Dh + k]);
+    }
+  }
+  __shared__ float red[16][kFThreads / 64];
+#pragma unroll
+  for (int h = 0; h < 16; ++h) {
+    if (h < H) {
+      float v = dot[h];
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+      if ((tid & 63) == 0) red[h][tid >> 6] = v;
+    }
+  }
+  __syncthreads();
   if (tid < H) {
-    const int bh = b * H + tid;
-    if (s_keep[tid]) {
-      const int len = s_len[tid];
-      if (len < a.slab_capacity[bh]) {
-        a.prefix_pos[(size_t)a.slab_offsets[bh] + len] = q;
-        a.lengths[bh] = len + 1;
-      } else if (a.error_flag) {
-        *a.error_flag = 1;
+    float s = 0.f;
+#pragma unroll
+    for (int wv = 0; wv < kFThreads / 64; ++wv) s += red[tid][wv];
+    const unsigned short* bias = (M > 0) ? b2 : b1;
+    s_new[tid] = s + (bias ? bf16_bits_to_float(bias[tid]) : 0.f);
+  }
+  __syncthreads();
+
+  // ---- 2. is the token that leaves the window kept ----
+  if (tid < H) {
+    const float s_q = (w > 0) ? s_q_r : s_new[tid];      // w == 0: the new token itself
+    s_keep[tid] = (q >= 0) && (s_q >= a.tau);
+  }
+  __syncthreads();
+
+  // ---- 3. move rows: ring -> prefix tail (kept), new -> ring slot ----
+#pragma unroll
+  for (int c = 0; c < kMaxPer; ++c) {
+    const int i = tid + c * kFThreads;
+    if (i < npieces) {
+      const int h = i / lpr, piece = i % lpr, bh = b * H + h;
+      if (s_keep[h] && len_r[c] < cap_r[c]) {
+        const size_t dst = ((size_t)slab_r[c] + len_r[c]) * lpr + piece;
+        Kp[dst] = (w > 0) ? k_old[c] : k_in[c];
+        Vp[dst] = (w > 0) ? v_old[c] : v_in[c];
+      }
+      if (w > 0) {
+        const size_t ring_at = ((size_t)bh * w + slot) * lpr + piece;
+        Kr[ring_at] = k_in[c];
+        Vr[ring_at] = v_in[c];
+      }
+      // ---- 4. bookkeeping, by the thread that owns piece 0 of the head ----
+      if (piece == 0) {
+        if (s_keep[h]) {
+          if (len_r[c] < cap_r[c]) {
+            a.prefix_pos[(size_t)slab_r[c] + len_r[c]] = q;
+            a.lengths[bh] = len_r[c] + 1;
+          } else if (a.error_flag) {
+            *a.error_flag = 1;
+          }
+        }
+        if (w > 0) a.score_ring[(size_t)bh * w + slot] = s_new[h];
       }
     }
-    if (w > 0) a.score_ring[(size_t)bh * w + slot] = s_new[tid];
   }
   if (tid == 0) a.seq_pos[b] = p + 1;
 }
