@@ -10,7 +10,12 @@
 //   A (16 x 32)  = W rows (heads) from LDS, staged once per block
 //   B (32 x 16)  = 16 tokens x 32 inputs, loaded straight from global memory in
 //                  the instruction's operand layout (lane = token + 16*k-group,
-//                  16 bytes per lane), no LDS round trip for the streamed data
+//                  16 bytes per lane), no LDS round trip for the streamed data.
+//                  Ordinary (cached) loads on purpose: a 128-byte line is
+//                  consumed by two consecutive load instructions of the same
+//                  wavefront, and with the non-temporal hint the second one
+//                  fetched the line again (5.1 instead of 6.0 TB/s measured;
+//                  a pure read stream reaches 6.0-6.4 TB/s on this part)
 //   C (16 x 16)  = fp32 accumulators, heads 0..15 x 16 tokens
 // Each wavefront owns groups of 16 consecutive tokens and walks the whole D_h.
 #include "kvzap_internal.h"
@@ -18,14 +23,14 @@
 namespace kvzap {
 namespace {
 
-constexpr int kThreads = 1024;         // 16 wavefronts share one copy of W in LDS
-constexpr int kWaves = kThreads / 64;
 constexpr int kUnroll = 8;             // independent 16-byte loads in flight per lane
 
+template <int kThreads>                // wavefronts of a block share one copy of W in LDS
 __global__ __launch_bounds__(kThreads) void score_linear_kernel(
     const unsigned short* __restrict__ hidden, const unsigned short* __restrict__ W,
     const unsigned short* __restrict__ bias, float* __restrict__ scores,
     long long rows, int T, int Dh, int H, int groups_per_block) {
+  constexpr int kWaves = kThreads / 64;
   extern __shared__ __align__(16) unsigned char smem[];
   // W as [H][Dh/8 + 4] 16-byte pieces: the 64-byte pad per row spreads the 16
   // (head, k-group) pieces one ds_read_b128 touches over distinct banks
@@ -62,7 +67,7 @@ __global__ __launch_bounds__(kThreads) void score_linear_kernel(
       u32x4 b[kUnroll];
 #pragma unroll
       for (int u = 0; u < kUnroll; ++u)
-        b[u] = __builtin_nontemporal_load(hrow + (size_t)(i0 + u) * 4);
+        b[u] = hrow[(size_t)(i0 + u) * 4];
 #pragma unroll
       for (int u = 0; u < kUnroll; ++u) {
         const u32x4 a = head_ok ? sWrow[(size_t)(i0 + u) * 4] : zero4;
@@ -71,7 +76,7 @@ __global__ __launch_bounds__(kThreads) void score_linear_kernel(
       }
     }
     for (int i = steps_main; i < steps; ++i) {
-      const u32x4 b = __builtin_nontemporal_load(hrow + (size_t)i * 4);
+      const u32x4 b = hrow[(size_t)i * 4];
       const u32x4 a = head_ok ? sWrow[(size_t)i * 4] : zero4;
       acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
           __builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
@@ -92,29 +97,38 @@ __global__ __launch_bounds__(kThreads) void score_linear_kernel(
   }
 }
 
+template <int kThreads>
+int launch_linear(const void* hidden, const void* W, const void* b, float* scores, long long rows,
+                  int T, int Dh, int H, long long want_blocks, hipStream_t stream) {
+  constexpr int kWaves = kThreads / 64;
+  const long long ngroups = (rows + 15) / 16;
+  long long gpb = (ngroups + want_blocks - 1) / want_blocks;
+  if (gpb < kWaves) gpb = kWaves;                     // at least one group per wavefront
+  const long long blocks = (ngroups + gpb - 1) / gpb;
+  const size_t lds = (size_t)H * ((size_t)Dh * 2 + 64);   // validated <= 160 KB by the caller
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(score_linear_kernel<kThreads>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+      return KVZAP_ERR_RUNTIME;
+    attr_set = true;
+  }
+  score_linear_kernel<kThreads><<<dim3((unsigned)blocks), kThreads, lds, stream>>>(
+      static_cast<const unsigned short*>(hidden), static_cast<const unsigned short*>(W),
+      static_cast<const unsigned short*>(b), scores, rows, T, Dh, H, (int)gpb);
+  return hipGetLastError() == hipSuccess ? KVZAP_OK : KVZAP_ERR_RUNTIME;
+}
+
 }  // namespace
 
 int launch_score_linear(const void* hidden, const void* W, const void* b, float* scores,
                         int B, int T, int Dh, int H, hipStream_t stream) {
   const long long rows = (long long)B * T;
   const long long ngroups = (rows + 15) / 16;
-  // about four blocks per CU's worth of work units, at least one group per wavefront
-  long long blocks = 256 * 2;
-  long long gpb = (ngroups + blocks - 1) / blocks;
-  if (gpb < kWaves) gpb = kWaves;
-  blocks = (ngroups + gpb - 1) / gpb;
-  const size_t lds = (size_t)H * ((size_t)Dh * 2 + 64);   // validated <= 160 KB by the caller
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(score_linear_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-      return KVZAP_ERR_RUNTIME;
-    attr_set = true;
-  }
-  score_linear_kernel<<<dim3((unsigned)blocks), kThreads, lds, stream>>>(
-      static_cast<const unsigned short*>(hidden), static_cast<const unsigned short*>(W),
-      static_cast<const unsigned short*>(b), scores, rows, T, Dh, H, (int)gpb);
-  return hipGetLastError() == hipSuccess ? KVZAP_OK : KVZAP_ERR_RUNTIME;
+  // long inputs: 16-wavefront blocks, ~4 per CU (W is staged into LDS once per block);
+  // short inputs: 4-wavefront blocks so that more CUs take part
+  if (ngroups >= 16 * 1024) return launch_linear<1024>(hidden, W, b, scores, rows, T, Dh, H, 1024, stream);
+  return launch_linear<256>(hidden, W, b, scores, rows, T, Dh, H, 1024, stream);
 }
 
 }  // namespace kvzap
