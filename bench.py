@@ -26,6 +26,13 @@ from paper_2601_07891_amd import binding, synth  # noqa: E402
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a plain
+# streaming kernel of known size; see profiles/c3_hbm_traffic.txt): (workload, kernel) -> bytes
+MEASURED_HBM_TRAFFIC = {
+    ("c3_qwen8b_128k_mlp", "score_mlp_frag_kernel"): 1209.2e6 + 4.2e6,
+    ("c3_qwen8b_128k_mlp", "compact_kernel"): 146.5e6 + 143.3e6,
+}
+
 
 def _oracle_sample(wl, layer0, sample_tokens):
     """Run the float64 oracle on the first `sample_tokens` tokens of every sequence
@@ -279,9 +286,17 @@ def main() -> int:
                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "traffic": None}
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
     roofline["avg_launch_ms"] = score_ms
+    roofline["algorithmic_flops_per_launch" if M else "algorithmic_bytes_per_launch"] = (
+        score_flops if M else B * T * (2 * Dh + 4 * H))
+    if L == wl.L:
+        roofline["traffic"] = MEASURED_HBM_TRAFFIC.get((wl.name, roofline["kernel"]))
+        compact_traffic = MEASURED_HBM_TRAFFIC.get((wl.name, "compact_kernel"))
+    else:
+        compact_traffic = None
     compact_roof = {"kernel": "compact_kernel", "bound": "hbm",
                     "achieved": compact_bytes / (compact_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
-                    "unit": "GB/s", "traffic": None, "avg_launch_ms": compact_ms}
+                    "unit": "GB/s", "traffic": compact_traffic, "avg_launch_ms": compact_ms,
+                    "algorithmic_bytes_per_launch": compact_bytes}
     compact_roof["frac"] = compact_roof["achieved"] / compact_roof["peak"]
 
     out = {

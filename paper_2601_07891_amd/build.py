@@ -11,6 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libkvzap.so")
+CEILINGS_PATH = os.path.join(HERE, "kvzap_ceilings")
 SOURCES = ["api.hip", "mask.hip", "compact.hip", "score_linear.hip", "score_mlp.hip",
            "decode.hip"]
 
@@ -40,8 +41,13 @@ def build(verbose: bool = True) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
+    # stand-alone calibration program (practical MFMA / HBM ceilings of the GPU it runs on)
+    cmd = [HIPCC, *FLAGS, os.path.join(CSRC, "ceilings.hip"), "-o", CEILINGS_PATH]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed for ceilings.hip:\n{r.stdout}\n{r.stderr}")
     if verbose:
-        print(f"built {LIB_PATH}")
+        print(f"built {LIB_PATH} and {CEILINGS_PATH}")
     return LIB_PATH
 
 
