@@ -28,7 +28,7 @@
  *     launched and no output is written.  No call throws or aborts.
  *   - Supported shapes: H (KV heads) in [1, 16]; D (head dim) a multiple of 8
  *     with D <= 512 (rows are moved in 16-byte pieces); D_h a multiple of 64;
- *     the MLP width M a multiple of 128 with M <= 1024.  Anything else returns
+ *     the MLP width M a multiple of 128 with M <= 640.  Anything else returns
  *     KVZAP_ERR_UNSUPPORTED; there is no fallback path.
  *   - Weight storage is output-major, the way a PyTorch linear module stores
  *     it: the paper's W1 in R^{D_h x M} (App. B) is passed as its transpose
@@ -74,6 +74,8 @@ const char* kvzap_version(void);
  * Minimum workspace size in bytes for one call.  For KVZAP_CALL_DECODE_EVICT
  * pass T = 1 (one new token per sequence).  Returns 0 for calls that need no
  * workspace and for invalid arguments.  Pure host function.
+ * KVZAP_CALL_SCORE with M > 0 needs M*Dh*2 bytes: every call copies W1 there in
+ * the order the matrix-core loads want it (a few microseconds).
  */
 size_t kvzap_workspace_bytes(int which_call, int B, int T, int Dh, int M, int H);
 
@@ -82,7 +84,8 @@ size_t kvzap_workspace_bytes(int which_call, int B, int T, int Dh, int M, int H)
  *
  *   M == 0 : KVzap-Linear   scores[b,h,t] = sum_k hidden[b,t,k] * W1[h,k] + b1[h]
  *   M  > 0 : KVzap-MLP      z = hidden[b,t,:] . W1[m,:] + b1[m]        (m < M)
- *                           g = GELU(z)  (exact erf form, fp32)
+ *                           g = GELU(z) = z * Phi(z)  (erf form, not the tanh one; fp32, erf
+ *                               evaluated to 1.5e-7 absolute)
  *                           scores[b,h,t] = sum_m g[m] * W2[h,m] + b2[h]
  *
  *   hidden  bf16 [B, T, Dh]
@@ -92,6 +95,9 @@ size_t kvzap_workspace_bytes(int which_call, int B, int T, int Dh, int M, int H)
  *   b2      bf16 [H]; NULL = zero; must be NULL if M == 0
  *   scores  fp32 [B, H, T]  (positions on the last axis, as Algorithm 1 indexes
  *           them); fully overwritten.
+ *
+ * workspace: see kvzap_workspace_bytes(KVZAP_CALL_SCORE, ...); may be NULL when
+ * that is 0 (linear surrogate).  KVZAP_ERR_WORKSPACE if missing, misaligned or small.
  *
  * Arithmetic: bf16 products accumulated in fp32 on the matrix cores; GELU in
  * fp32; the GELU output enters the second projection as a bf16 pair (high part
