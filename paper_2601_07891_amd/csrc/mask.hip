@@ -1,13 +1,16 @@
 // Threshold + sliding-window mask and per-head index lists (Sec. 3.3, Algorithm 1).
 //
-// Three small launches over scores [B*H, T] (4 bytes per flag, so the whole
-// stage moves ~1 % of the bytes of the K/V compaction that follows):
+// Small launches over scores [B*H, T] (4 bytes per flag, so the whole stage moves
+// ~1 % of the bytes of the K/V compaction that follows; it is bound by the ~4 us
+// floor of a kernel launch, so the number of launches is what matters):
 //   1. count : one block per 1024-token chunk of one (b,h) row counts its kept flags
-//   2. scan  : a single block turns the chunk counts into exclusive prefixes and
-//              writes lengths[B,H] and offsets[B*H+1]
-//   3. emit  : every chunk recomputes its flags (scores are L2-resident by now),
-//              ranks them with a wave ballot + LDS scan and writes the ascending
-//              kept positions at its prefix
+//   2. emit  : every chunk recomputes its flags (scores are L2-resident by now),
+//              ranks them with a wave shuffle scan + LDS and writes the ascending
+//              kept positions at its prefix.  With up to kFusedMaxChunks chunks each
+//              block derives its own prefix by summing the counts of all chunks
+//              before it (a few KB from L2), and the first chunk of every head
+//              also writes lengths and offsets; beyond that a single-block scan
+//              kernel runs between the two.
 // No block waits for another, so there is nothing that can spin.
 #include "kvzap_internal.h"
 
@@ -109,11 +112,50 @@ __global__ __launch_bounds__(kScanThreads) void mask_scan_kernel(
   }
 }
 
+constexpr int kFusedMaxChunks = 8192;
+
+// block-wide sum of a 64-bit value (all threads get the result)
+__device__ __forceinline__ long long block_sum_i64(long long v, long long* lds_scratch) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) lds_scratch[threadIdx.x >> 6] = v;
+  __syncthreads();
+  long long s = 0;
+#pragma unroll
+  for (int w = 0; w < kThreads / 64; ++w) s += lds_scratch[w];
+  return s;
+}
+
+template <bool kFused>
 __global__ __launch_bounds__(kThreads) void mask_emit_kernel(
     const float* __restrict__ scores, float tau, int window,
     const int32_t* __restrict__ seq_lens, int H, int T, int nchunks,
-    const int64_t* __restrict__ chunk_prefix, int32_t* __restrict__ keep_idx) {
+    const int64_t* __restrict__ chunk_prefix, const int32_t* __restrict__ chunk_counts,
+    int32_t* __restrict__ keep_idx, int32_t* __restrict__ lengths,
+    int64_t* __restrict__ offsets) {
   const int chunk = blockIdx.x, bh = blockIdx.y;
+  long long my_prefix;
+  if (kFused) {
+    __shared__ long long scratch[kThreads / 64];
+    const int BH = gridDim.y;
+    const int mine = bh * nchunks + chunk;               // chunks are ordered (b,h)-major
+    long long before = 0;
+    for (int i = threadIdx.x; i < mine; i += kThreads) before += chunk_counts[i];
+    my_prefix = block_sum_i64(before, scratch);
+    if (chunk == 0) {                                    // this head's length and start
+      long long own = 0;
+      for (int i = threadIdx.x; i < nchunks; i += kThreads) own += chunk_counts[mine + i];
+      const long long head_total = block_sum_i64(own, scratch);
+      if (threadIdx.x == 0) {
+        offsets[bh] = my_prefix;
+        lengths[bh] = (int32_t)head_total;
+        if (bh == BH - 1) offsets[BH] = my_prefix + head_total;
+      }
+    }
+  } else {
+    my_prefix = chunk_prefix[(size_t)bh * nchunks + chunk];
+  }
   const int Tb = seq_lens ? seq_lens[bh / H] : T;
   const float* row = scores + (size_t)bh * T;
   const bool vec_ok = (T % 4) == 0;
@@ -134,7 +176,7 @@ __global__ __launch_bounds__(kThreads) void mask_emit_kernel(
   int before = 0;
 #pragma unroll
   for (int w = 0; w < kThreads / 64; ++w) before += (w < wid) ? wave_tot[w] : 0;
-  int64_t pos = chunk_prefix[(size_t)bh * nchunks + chunk] + before + incl - c;
+  int64_t pos = my_prefix + before + incl - c;
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
     if (bits & (1u << e)) keep_idx[pos++] = t0 + e;
@@ -154,10 +196,17 @@ int launch_mask(const float* scores, float tau, int window, const int32_t* seq_l
   const dim3 grid(nchunks, BH);
   mask_count_kernel<<<grid, kThreads, 0, stream>>>(scores, tau, window, seq_lens, H, T,
                                                    nchunks, chunk_counts);
-  mask_scan_kernel<<<1, kScanThreads, 0, stream>>>(chunk_counts, chunk_prefix, BH, nchunks,
-                                                   lengths, offsets);
-  mask_emit_kernel<<<grid, kThreads, 0, stream>>>(scores, tau, window, seq_lens, H, T,
-                                                  nchunks, chunk_prefix, keep_idx);
+  if ((long long)BH * nchunks <= kFusedMaxChunks) {
+    mask_emit_kernel<true><<<grid, kThreads, 0, stream>>>(scores, tau, window, seq_lens, H, T,
+                                                          nchunks, chunk_prefix, chunk_counts,
+                                                          keep_idx, lengths, offsets);
+  } else {
+    mask_scan_kernel<<<1, kScanThreads, 0, stream>>>(chunk_counts, chunk_prefix, BH, nchunks,
+                                                     lengths, offsets);
+    mask_emit_kernel<false><<<grid, kThreads, 0, stream>>>(scores, tau, window, seq_lens, H, T,
+                                                           nchunks, chunk_prefix, chunk_counts,
+                                                           keep_idx, lengths, offsets);
+  }
   return hipGetLastError() == hipSuccess ? KVZAP_OK : KVZAP_ERR_RUNTIME;
 }
 

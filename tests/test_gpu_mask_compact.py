@@ -45,6 +45,8 @@ CASES = [
     (1, 16, 2049, 8, 1, 0.0),             # smallest row, H = 16
     (1, 8, 4100, 48, 128, 0.0),           # D not a power of two -> generic path
     (4, 8, 16384, 128, 128, 0.67),
+    (64, 16, 9000, 8, 128, 0.3),          # > 8192 chunks: the path with the separate scan kernel
+    (8, 8, 131072, 8, 128, 1.0),          # exactly 8192 chunks: the largest fused case
 ]
 
 
