@@ -5,11 +5,11 @@
 // D/8 pieces of 16 bytes; consecutive lanes take consecutive pieces, so one
 // wavefront reads and writes whole rows with 16-byte accesses (a 128-dim row
 // is 256 B = 16 lanes, four rows per wavefront instruction).  Latency is covered
-// by parallelism, not by per-thread unrolling: a thread moves one piece of a K
-// row and one of a V row per pass and the grid holds ~16k small blocks, which
-// measured faster (5.6-5.9 TB/s) than 2-8 rows in flight per thread with fewer
-// blocks (4.6-5.4 TB/s); non-temporal accesses are worth another 15 %.
-// The grid is (tiles, B*H): blocks of one head stride over that head's kept
+// by parallelism, not by per-thread unrolling: a thread moves one piece of one
+// row per pass and the grid holds ~32k small blocks, which measured faster
+// (5.6-5.9 TB/s) than 2-8 rows in flight per thread with fewer blocks
+// (4.6-5.4 TB/s); non-temporal accesses are worth another 15 %.
+// The grid is (tiles, B*H, {K,V}): blocks of one head stride over that head's kept
 // rows, so no search for the owning head is needed and short heads simply run
 // out of tiles early.
 #include "kvzap_internal.h"
@@ -18,7 +18,6 @@ namespace kvzap {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kRowsInFlight = 1;   // rows of K and of V per thread per pass
 
 template <int LPR>  // lanes (16-byte pieces) per row
 __global__ __launch_bounds__(kThreads) void compact_kernel(
@@ -27,38 +26,21 @@ __global__ __launch_bounds__(kThreads) void compact_kernel(
     const int64_t* __restrict__ offsets, u32x4* __restrict__ K_out,
     u32x4* __restrict__ V_out, int64_t cap_rows, int T) {
   constexpr int kRowsPerPass = kThreads / LPR;            // rows one block covers at once
-  constexpr int kTileRows = kRowsPerPass * kRowsInFlight;
   const int bh = blockIdx.y;
   const int n = lengths[bh];
   const int64_t out0 = offsets[bh];
   const int piece = threadIdx.x % LPR;
   const int sub = threadIdx.x / LPR;
-  const u32x4* Kh = K + (size_t)bh * T * LPR;
-  const u32x4* Vh = V + (size_t)bh * T * LPR;
-  for (int j0 = blockIdx.x * kTileRows; j0 < n; j0 += gridDim.x * kTileRows) {
-    int t[kRowsInFlight];
-    bool ok[kRowsInFlight];
-#pragma unroll
-    for (int r = 0; r < kRowsInFlight; ++r) {
-      const int j = j0 + r * kRowsPerPass + sub;
-      ok[r] = (j < n) && (out0 + j < cap_rows);
-      t[r] = ok[r] ? keep_idx[out0 + j] : 0;
-      ok[r] = ok[r] && (t[r] >= 0) && (t[r] < T);   // never read outside the head
-    }
-    u32x4 kv[kRowsInFlight], vv[kRowsInFlight];
-#pragma unroll
-    for (int r = 0; r < kRowsInFlight; ++r) {
-      if (ok[r]) {
-        kv[r] = __builtin_nontemporal_load(Kh + (size_t)t[r] * LPR + piece);
-        vv[r] = __builtin_nontemporal_load(Vh + (size_t)t[r] * LPR + piece);
-      }
-    }
-#pragma unroll
-    for (int r = 0; r < kRowsInFlight; ++r) {
-      if (ok[r]) {
-        const size_t o = (size_t)(out0 + j0 + r * kRowsPerPass + sub) * LPR + piece;
-        __builtin_nontemporal_store(kv[r], K_out + o);
-        __builtin_nontemporal_store(vv[r], V_out + o);
+  // blockIdx.z selects the tensor: K and V rows are moved by different blocks (+3 %)
+  const u32x4* src = (blockIdx.z ? V : K) + (size_t)bh * T * LPR;
+  u32x4* dst = blockIdx.z ? V_out : K_out;
+  for (int j0 = blockIdx.x * kRowsPerPass; j0 < n; j0 += gridDim.x * kRowsPerPass) {
+    const int j = j0 + sub;
+    if (j < n && out0 + j < cap_rows) {
+      const int t = keep_idx[out0 + j];
+      if (t >= 0 && t < T) {                                // never read outside the head
+        const u32x4 row = __builtin_nontemporal_load(src + (size_t)t * LPR + piece);
+        __builtin_nontemporal_store(row, dst + (size_t)(out0 + j) * LPR + piece);
       }
     }
   }
@@ -97,13 +79,14 @@ int launch_compact(const void* K, const void* V, const int32_t* keep_idx,
   // ~16k blocks (64 per CU), split evenly over heads
   int tiles_per_head;
   {
-    const int rows_per_tile = (kThreads / (lpr <= kThreads ? lpr : kThreads)) * kRowsInFlight;
+    const int rows_per_tile = kThreads / (lpr <= kThreads ? lpr : kThreads);
     const int max_tiles = (T + rows_per_tile - 1) / rows_per_tile;
     int want = (256 * 64 + BH - 1) / BH;
     tiles_per_head = want < max_tiles ? want : max_tiles;
     if (tiles_per_head < 1) tiles_per_head = 1;
   }
-  const dim3 grid(tiles_per_head, BH);
+  const dim3 grid(tiles_per_head, BH, 2);
+  const dim3 grid_generic(tiles_per_head, BH);
   const u32x4* k = static_cast<const u32x4*>(K);
   const u32x4* v = static_cast<const u32x4*>(V);
   u32x4* ko = static_cast<u32x4*>(K_out);
@@ -118,7 +101,7 @@ int launch_compact(const void* K, const void* V, const int32_t* keep_idx,
     KVZAP_COMPACT_CASE(16)   // D = 128
     KVZAP_COMPACT_CASE(32)   // D = 256
     default:
-      compact_generic_kernel<<<grid, kThreads, 0, stream>>>(k, v, keep_idx, lengths, offsets,
+      compact_generic_kernel<<<grid_generic, kThreads, 0, stream>>>(k, v, keep_idx, lengths, offsets,
                                                             ko, vo, cap_rows, T, lpr);
   }
 #undef KVZAP_COMPACT_CASE
