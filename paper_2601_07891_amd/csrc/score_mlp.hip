@@ -235,7 +235,6 @@ __global__ __launch_bounds__(kThreads) void score_mlp_kernel(
 // ---------------------------------------------------------------------------
 constexpr int kPD = 3;                       // hidden tiles in flight
 constexpr int kNS = kPD + 1;                 // LDS stages
-constexpr int kHStage = kTok * 128;          // bytes per stage
 
 // Wait until at most N vector-memory operations of this wavefront are outstanding
 // (they complete in issue order).  Written as asm with a memory clobber so that the
@@ -286,26 +285,29 @@ __global__ __launch_bounds__(256) void arrange_w1_kernel(const u32x4* __restrict
   }
 }
 
-template <int UB>
+template <int UB, int TB>   // UB 32-unit blocks per wavefront, TB 32-token blocks per block
 __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
     const unsigned short* hidden, const unsigned char* W1f,   // not __restrict__: their loads must stay ordered w.r.t. the waits
     const unsigned short* __restrict__ b1, const unsigned short* __restrict__ W2,
     const unsigned short* __restrict__ b2, float* __restrict__ scores,
     long long rows, int T, int Dh, int H) {
   constexpr int U = 128 * UB;
+  constexpr int TOK = 32 * TB;               // tokens per block
+  constexpr int STAGE = TOK * 128;           // bytes per LDS stage (TOK rows of one K tile)
+  constexpr int NDJ = TB;                    // load-to-LDS instructions per wavefront per tile
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, kg = lane >> 5;
-  const long long row0 = (long long)blockIdx.x * kTok;
-  const int rows_here = (rows - row0 < kTok) ? (int)(rows - row0) : kTok;
+  const long long row0 = (long long)blockIdx.x * TOK;
+  const int rows_here = (rows - row0 < TOK) ? (int)(rows - row0) : TOK;
 
   // hidden load-to-LDS: instruction j (0..3) of wavefront w fills LDS chunk j*4+w of a
   // stage = rows (j*4+w)*8 + lane/8, physical piece lane%8 <- logical piece (lane%8) ^ (row%8)
   const unsigned char* hb = reinterpret_cast<const unsigned char*>(hidden + (size_t)row0 * Dh);
-  unsigned h_off[4];
+  unsigned h_off[NDJ];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
+  for (int j = 0; j < NDJ; ++j) {
     int r = (j * 4 + wid) * 8 + (lane >> 3);
     const int p = (lane & 7) ^ (r & 7);
     if (r > rows_here - 1) r = rows_here - 1;            // clamp: in bounds, result discarded
@@ -314,7 +316,7 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
   const unsigned lds0 = lds_address(smem);
   auto dma = [&](int j, int tile) {
     load_to_lds_b128(hb + (size_t)tile * (kBK * 2) + h_off[j],
-                     lds0 + (unsigned)((tile % kNS) * kHStage + (j * 4 + wid) * 1024));
+                     lds0 + (unsigned)((tile % kNS) * STAGE + (j * 4 + wid) * 1024));
   };
   // A fragments of this wavefront: unit blocks rb = wid*UB + ub
   const unsigned char* abase = W1f + ((size_t)wid * UB * 4) * 1024 + lane * 16;
@@ -322,22 +324,22 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
     return *reinterpret_cast<const bf16x8*>(abase + ((size_t)(tile * (U / 32) + ub) * 4 + kk) * 1024);
   };
 
-  floatx16 acc[UB][4];
+  floatx16 acc[UB][TB];
 #pragma unroll
   for (int ub = 0; ub < UB; ++ub)
 #pragma unroll
-    for (int tb = 0; tb < 4; ++tb)
+    for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[ub][tb][e] = 0.0f;
 
   const int nk = Dh / kBK;                 // >= kPD + 1 (checked by the launcher)
   bf16x8 a[4][UB];                         // a[kk]: step kk of the current tile, then of the next
-  bf16x8 b[2][4];
+  bf16x8 b[2][TB];
   // ---- prologue: hidden tiles 0..kPD-1 in flight, A fragments of tile 0 ----
 #pragma unroll
   for (int d = 0; d < kPD; ++d)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) dma(j, d);
+    for (int j = 0; j < NDJ; ++j) dma(j, d);
   // same issue order as in the main loop (the compiler sizes its own waits on the A
   // fragments by their position in the load stream, on both paths into the loop)
 #pragma unroll
@@ -349,14 +351,14 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
     }
   // hidden tile 0 = the four oldest operations; everything younger may stay in flight
   __builtin_amdgcn_sched_barrier(0);
-  wait_vmcnt<4 * (kPD - 1) + 4 * UB>();
+  wait_vmcnt<NDJ * (kPD - 1) + 4 * UB>();
   block_barrier_no_drain();
   auto read_b = [&](int buf, int tile, int kk, int tb) {
     b[buf][tb] = *reinterpret_cast<const bf16x8*>(
-        smem + (tile % kNS) * kHStage + lds_off(32 * tb + l32, kk * 2 + kg));
+        smem + (tile % kNS) * STAGE + lds_off(32 * tb + l32, kk * 2 + kg));
   };
 #pragma unroll
-  for (int tb = 0; tb < 4; ++tb) read_b(0, 0, 0, tb);
+  for (int tb = 0; tb < TB; ++tb) read_b(0, 0, 0, tb);
 
   // One K tile.  MORE: tile t+1 exists; MORE_PD: tile t+kPD exists.  Both are compile-time
   // so that the body is a single basic block whose instruction order is the source order.
@@ -370,12 +372,12 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
         // A fragment with the next tile's data
         if (kk < 3) {
 #pragma unroll
-          for (int tb = 0; tb < 4; ++tb)
-            if (tb * UB / 4 == ub) read_b((kk + 1) & 1, t, kk + 1, tb);
+          for (int tb = 0; tb < TB; ++tb)
+            if (tb * UB / TB == ub) read_b((kk + 1) & 1, t, kk + 1, tb);
         }
-        if (more_pd && ub == 0) dma(kk, t + kPD);
+        if (more_pd && ub == 0 && kk < NDJ) dma(kk, t + kPD);
 #pragma unroll
-        for (int tb = 0; tb < 4; ++tb)
+        for (int tb = 0; tb < TB; ++tb)
           acc[ub][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk][ub], b[kk & 1][tb],
                                                                 acc[ub][tb], 0, 0, 0);
         if (more) a[kk][ub] = aload(t + 1, ub, kk);
@@ -390,7 +392,7 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
       wait_vmcnt<UB + (kPD - 1) * 4 * UB>();
       block_barrier_no_drain();
 #pragma unroll
-      for (int tb = 0; tb < 4; ++tb) read_b(0, t + 1, 0, tb);
+      for (int tb = 0; tb < TB; ++tb) read_b(0, t + 1, 0, tb);
     }
   };
   int t = 0;
@@ -401,9 +403,9 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
 
   // ---- epilogue: bias + GELU, then the M -> H projection as a second MFMA ----
   const int ubase = wid * (32 * UB);
-  floatx16 acc2[4];
+  floatx16 acc2[TB];
 #pragma unroll
-  for (int tb = 0; tb < 4; ++tb)
+  for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc2[tb][e] = 0.0f;
 #pragma unroll
@@ -422,7 +424,7 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
       for (int e = 0; e < 8; ++e)
         bias[e] = b1 ? bf16_bits_to_float(b1[u0 + 8 * (e / 4) + (e % 4)]) : 0.0f;
 #pragma unroll
-      for (int tb = 0; tb < 4; ++tb) {
+      for (int tb = 0; tb < TB; ++tb) {
         unsigned hi[4], lo[4];
 #pragma unroll
         for (int e2 = 0; e2 < 4; ++e2) {
@@ -446,23 +448,23 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
       }
     }
   }
-  float* red = reinterpret_cast<float*>(smem);     // [4][H][128]
+  float* red = reinterpret_cast<float*>(smem);     // [4][H][TOK]
 #pragma unroll
-  for (int tb = 0; tb < 4; ++tb)
+  for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int head = 8 * (r / 4) + 4 * kg + (r % 4);
-      if (head < H) red[(wid * H + head) * kTok + 32 * tb + l32] = acc2[tb][r];
+      if (head < H) red[(wid * H + head) * TOK + 32 * tb + l32] = acc2[tb][r];
     }
   __syncthreads();
-  for (int i = tid; i < H * kTok; i += 256) {
-    const int head = i / kTok, tok = i % kTok;
+  for (int i = tid; i < H * TOK; i += 256) {
+    const int head = i / TOK, tok = i % TOK;
     const long long r = row0 + tok;
     if (r < rows) {
-      float s = red[(0 * H + head) * kTok + tok];
-      s += red[(1 * H + head) * kTok + tok];
-      s += red[(2 * H + head) * kTok + tok];
-      s += red[(3 * H + head) * kTok + tok];
+      float s = red[(0 * H + head) * TOK + tok];
+      s += red[(1 * H + head) * TOK + tok];
+      s += red[(2 * H + head) * TOK + tok];
+      s += red[(3 * H + head) * TOK + tok];
       if (b2) s += bf16_bits_to_float(b2[head]);
       const long long bidx = r / T, t = r - bidx * T;
       scores[((size_t)bidx * H + head) * T + t] = s;
@@ -470,14 +472,16 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
   }
 }
 
-template <int UB>
+template <int UB, int TB>
 int launch_frag(const void* hidden, const void* W1, const void* b1, const void* W2,
                 const void* b2, float* scores, long long rows, int T, int Dh, int H,
                 void* workspace, hipStream_t stream) {
-  constexpr size_t lds = (size_t)kNS * kHStage;
+  constexpr int TOK = 32 * TB;
+  constexpr size_t lds = (size_t)kNS * TOK * 128;
+  static_assert(lds >= (size_t)4 * 16 * TOK * sizeof(float), "reduction buffer fits");
   static bool attr_set = false;
   if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(score_mlp_frag_kernel<UB>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(score_mlp_frag_kernel<UB, TB>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
       return KVZAP_ERR_RUNTIME;
     attr_set = true;
@@ -485,8 +489,8 @@ int launch_frag(const void* hidden, const void* W1, const void* b1, const void* 
   const int M = 128 * UB;
   arrange_w1_kernel<<<512, 256, 0, stream>>>(static_cast<const u32x4*>(W1),
                                              static_cast<u32x4*>(workspace), M, Dh);
-  const long long blocks = (rows + kTok - 1) / kTok;
-  score_mlp_frag_kernel<UB><<<dim3((unsigned)blocks), 256, lds, stream>>>(
+  const long long blocks = (rows + TOK - 1) / TOK;
+  score_mlp_frag_kernel<UB, TB><<<dim3((unsigned)blocks), 256, lds, stream>>>(
       static_cast<const unsigned short*>(hidden), static_cast<const unsigned char*>(workspace),
       static_cast<const unsigned short*>(b1), static_cast<const unsigned short*>(W2),
       static_cast<const unsigned short*>(b2), scores, rows, T, Dh, H);
@@ -522,16 +526,15 @@ int launch_score_mlp(const void* hidden, const void* W1, const void* b1, const v
   const bool frag = (Dh / kBK) >= kPD + 1;     // the main variant needs at least kPD+1 K tiles
 #define KVZAP_MLP_CASE(UBV)                                                                     \
   case UBV:                                                                                     \
-    return frag ? launch_frag<UBV>(hidden, W1, b1, W2, b2, scores, rows, T, Dh, H, workspace,   \
-                                   stream)                                                      \
+    return frag ? launch_frag<UBV, (UBV <= 4 ? 4 : 3)>(hidden, W1, b1, W2, b2, scores, rows, T, \
+                                                       Dh, H, workspace, stream)                \
                 : launch_one<UBV>(hidden, W1, b1, W2, b2, scores, rows, T, Dh, H, stream);
   switch (M / 128) {
     KVZAP_MLP_CASE(1)
     KVZAP_MLP_CASE(2)
     KVZAP_MLP_CASE(3)
     KVZAP_MLP_CASE(4)
-    case 5:   // 320 accumulator registers do not fit beside the fragment ring: staged variant
-      return launch_one<5>(hidden, W1, b1, W2, b2, scores, rows, T, Dh, H, stream);
+    KVZAP_MLP_CASE(5)   // M = 640: 96-token blocks so that the 5 x 3 accumulator blocks fit (240 registers)
     default: return KVZAP_ERR_UNSUPPORTED;
   }
 #undef KVZAP_MLP_CASE
