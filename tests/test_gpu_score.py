@@ -68,7 +68,8 @@ def test_linear_one_hot_weights_pick_columns():
 
 MLP_SHAPES = [(1, 300, 256, 128, 8), (2, 129, 1024, 128, 8), (1, 1000, 4096, 512, 8),
               (1, 257, 5120, 640, 8), (1, 64, 2048, 256, 3), (1, 1, 3072, 384, 16),
-              (3, 50, 4096, 512, 8)]
+              (3, 50, 4096, 512, 8), (1, 200, 448, 128, 8), (2, 70, 320, 256, 4),   # odd K-tile counts
+              (1, 97, 256, 640, 8), (1, 500, 192, 512, 8)]                          # 4 tiles; D_h < 256
 
 
 @pytest.mark.parametrize("B,T,Dh,M,H", MLP_SHAPES)
