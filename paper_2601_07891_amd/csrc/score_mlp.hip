@@ -33,16 +33,18 @@ constexpr int kBK = 64;       // K per LDS tile
 // ten FMA-class operations per element instead of the ~40 of a library erff, which matters
 // because the epilogue's vector ALU work is not overlapped with matrix-core work.
 __device__ __forceinline__ float gelu_exact(float z) {
-  const float x = fabsf(z) * 0.70710678118654752f;
-  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
-  float p = fmaf(t, 1.061405429f, -1.453152027f);
-  p = fmaf(t, p, 1.421413741f);
-  p = fmaf(t, p, -0.284496736f);
-  p = fmaf(t, p, 0.254829592f);
-  // exp(-x^2) = 2^(-x^2 * log2(e))
-  const float e = __builtin_amdgcn_exp2f(x * x * -1.4426950408889634f);
-  const float half_erfc = 0.5f * (t * p) * e;          // 0.5 * erfc(|z| / sqrt 2)
-  const float phi = (z >= 0.0f) ? (1.0f - half_erfc) : half_erfc;
+  const float x = fabsf(z);
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f * 0.70710678118654752f, x, 1.0f));
+  // 0.5 * (a1 t + ... + a5 t^5): the 0.5 of Phi is folded into the coefficients
+  float p = fmaf(t, 0.5f * 1.061405429f, 0.5f * -1.453152027f);
+  p = fmaf(t, p, 0.5f * 1.421413741f);
+  p = fmaf(t, p, 0.5f * -0.284496736f);
+  p = fmaf(t, p, 0.5f * 0.254829592f);
+  // exp(-z^2 / 2) = 2^(-z^2 * log2(e) / 2)
+  const float e = __builtin_amdgcn_exp2f(z * z * (-0.5f * 1.4426950408889634f));
+  const float half_erfc = (t * p) * e;                 // 0.5 * erfc(|z| / sqrt 2) = Phi(-|z|)
+  // Phi(z) = 0.5 + copysign(0.5 - Phi(-|z|), z)
+  const float phi = 0.5f + copysignf(0.5f - half_erfc, z);
   return z * phi;
 }
 
@@ -164,26 +166,19 @@ __global__ __launch_bounds__(kThreads) void score_mlp_kernel(
       }
 #pragma unroll
       for (int tb = 0; tb < 2; ++tb) {
-        unsigned hi[4], lo[4];
+        // GELU output as a bf16 pair: ghi = round(g), glo = round(g - ghi) (hardware RNE
+        // conversions, two values per instruction)
+        bf16x8 ghi, glo;
 #pragma unroll
-        for (int e2 = 0; e2 < 4; ++e2) {
-          unsigned short h16[2], l16[2];
-#pragma unroll
-          for (int q = 0; q < 2; ++q) {
-            const int e = 2 * e2 + q;
-            const float g = gelu_exact(acc[ub][tb][8 * s + e] + bias[e]);
-            h16[q] = float_to_bf16_bits(g);
-            l16[q] = float_to_bf16_bits(g - bf16_bits_to_float(h16[q]));
-          }
-          hi[e2] = (unsigned)h16[0] | ((unsigned)h16[1] << 16);
-          lo[e2] = (unsigned)l16[0] | ((unsigned)l16[1] << 16);
+        for (int e = 0; e < 8; ++e) {
+          const float g = gelu_exact(acc[ub][tb][8 * s + e] + bias[e]);
+          ghi[e] = (__bf16)g;
+          glo[e] = (__bf16)(g - (float)ghi[e]);
         }
-        const u32x4 ghi = {hi[0], hi[1], hi[2], hi[3]};
-        const u32x4 glo = {lo[0], lo[1], lo[2], lo[3]};
-        acc2[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-            __builtin_bit_cast(bf16x8, w2), __builtin_bit_cast(bf16x8, ghi), acc2[tb], 0, 0, 0);
-        acc2[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-            __builtin_bit_cast(bf16x8, w2), __builtin_bit_cast(bf16x8, glo), acc2[tb], 0, 0, 0);
+        acc2[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w2), ghi,
+                                                           acc2[tb], 0, 0, 0);
+        acc2[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w2), glo,
+                                                           acc2[tb], 0, 0, 0);
       }
     }
   }
@@ -425,26 +420,19 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
         bias[e] = b1 ? bf16_bits_to_float(b1[u0 + 8 * (e / 4) + (e % 4)]) : 0.0f;
 #pragma unroll
       for (int tb = 0; tb < TB; ++tb) {
-        unsigned hi[4], lo[4];
+        // GELU output as a bf16 pair: ghi = round(g), glo = round(g - ghi) (hardware RNE
+        // conversions, two values per instruction)
+        bf16x8 ghi, glo;
 #pragma unroll
-        for (int e2 = 0; e2 < 4; ++e2) {
-          unsigned short h16[2], l16[2];
-#pragma unroll
-          for (int q = 0; q < 2; ++q) {
-            const int e = 2 * e2 + q;
-            const float g = gelu_exact(acc[ub][tb][8 * s + e] + bias[e]);
-            h16[q] = float_to_bf16_bits(g);
-            l16[q] = float_to_bf16_bits(g - bf16_bits_to_float(h16[q]));
-          }
-          hi[e2] = (unsigned)h16[0] | ((unsigned)h16[1] << 16);
-          lo[e2] = (unsigned)l16[0] | ((unsigned)l16[1] << 16);
+        for (int e = 0; e < 8; ++e) {
+          const float g = gelu_exact(acc[ub][tb][8 * s + e] + bias[e]);
+          ghi[e] = (__bf16)g;
+          glo[e] = (__bf16)(g - (float)ghi[e]);
         }
-        const u32x4 ghi = {hi[0], hi[1], hi[2], hi[3]};
-        const u32x4 glo = {lo[0], lo[1], lo[2], lo[3]};
-        acc2[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-            __builtin_bit_cast(bf16x8, w2), __builtin_bit_cast(bf16x8, ghi), acc2[tb], 0, 0, 0);
-        acc2[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-            __builtin_bit_cast(bf16x8, w2), __builtin_bit_cast(bf16x8, glo), acc2[tb], 0, 0, 0);
+        acc2[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w2), ghi,
+                                                           acc2[tb], 0, 0, 0);
+        acc2[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w2), glo,
+                                                           acc2[tb], 0, 0, 0);
       }
     }
   }
