@@ -338,3 +338,35 @@ def param_count(kind: str, L: int, D_h: int, H: int, biases: bool = False) -> in
     else:
         raise ValueError(kind)
     return L * per
+
+
+# --------------------------------------------------------------------------
+# consumer of the ragged cache: one decoding step of attention over per-head
+# caches of different lengths (Sec. 5 names such a kernel as the engineering
+# that turns the compression into savings; the weights are the a_ji of Eq. 2)
+# --------------------------------------------------------------------------
+def attend_decode(q: np.ndarray, caches, scale: float) -> np.ndarray:
+    """Softmax attention of one new query per (sequence, query head) over the
+    kept KV pairs of its KV head (grouped-query attention: query head g uses KV
+    head g // (H_Q // H), as in the models of App. B).
+
+    q       float64 [B, H_Q, D]
+    caches  caches[b][h] = (K [n_bh, D], V [n_bh, D]) float64, n_bh >= 1, in any
+            row order (the result does not depend on it)
+    Returns float64 [B, H_Q, D]:  out = sum_i softmax_i(scale * q . K_i) V_i.
+    """
+    q = np.asarray(q, dtype=np.float64)
+    B, HQ, D = q.shape
+    H = len(caches[0])
+    G = HQ // H
+    assert G * H == HQ
+    out = np.zeros((B, HQ, D))
+    for b in range(B):
+        for g in range(HQ):
+            K, V = caches[b][g // G]
+            s = (np.asarray(K, dtype=np.float64) @ q[b, g]) * scale
+            s = s - s.max()
+            p = np.exp(s)
+            p = p / p.sum()
+            out[b, g] = p @ np.asarray(V, dtype=np.float64)
+    return out
