@@ -61,7 +61,8 @@ typedef enum kvzap_call {
   KVZAP_CALL_SCORE = 0,
   KVZAP_CALL_MASK = 1,
   KVZAP_CALL_COMPACT = 2,
-  KVZAP_CALL_DECODE_EVICT = 3
+  KVZAP_CALL_DECODE_EVICT = 3,
+  KVZAP_CALL_ATTEND_DECODE = 4   /* pass T = max_rows, Dh = HQ, M = window */
 } kvzap_call;
 
 /* Text for a status code (host pointer to a static string, never NULL). */
@@ -198,6 +199,49 @@ int kvzap_decode_evict(const void* hidden_new, const void* W1, const void* b1,
                        float tau, int window, int B, int H, int D,
                        int32_t* error_flag,
                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * kvzap_attend_decode -- one decoding step of attention over the ragged cache the
+ * prune step produces (Sec. 5: the non-uniform per-head lengths need an attention
+ * kernel that handles them; the weights are the a_ji of Sec. 3.2, Eq. 2).
+ *
+ * For sequence b and query head g (grouped-query attention, KV head h = g / (HQ/H)):
+ *   out[b,g,:] = sum_i softmax_i( scale * q[b,g,:] . K_i ) * V_i
+ * over the rows i of head (b,h): its lengths[b,h] packed rows followed, when
+ * window > 0, by the min(seq_pos[b], window) pairs still inside the window ring.
+ * The two parts are exactly the state kvzap_decode_evict maintains (call it first,
+ * then attend: seq_pos counts the new token, which sits in the ring).  A prefill
+ * result of kvzap_compact is attended to with window = 0, row_offsets = offsets,
+ * lengths = lengths (its window tokens are among the packed rows).
+ *
+ *   q            bf16 [B, HQ, D]
+ *   K_rows, V_rows  bf16 [total_rows, D]; head (b,h) owns rows
+ *                row_offsets[b*H+h] .. + lengths[b,h].  The kernel never reads
+ *                outside [0, total_rows): a head whose offset is out of range is
+ *                treated as empty and a length is cut at total_rows.
+ *   row_offsets  int64 [B*H];  lengths int32 [B, H]
+ *   K_ring, V_ring  bf16 [B, H, window, D], seq_pos int32 [B]; all three NULL iff window == 0
+ *   max_rows     host-side upper bound on lengths[b,h] (e.g. the slab capacity or the
+ *                prompt length).  It only sizes the launch and the workspace; a head
+ *                longer than the bound is still attended to in full, only slower.
+ *   scale        usually 1/sqrt(D)
+ *   out          bf16 [B, HQ, D], fully overwritten.  A head with no row yields zeros.
+ *   workspace    kvzap_workspace_bytes(KVZAP_CALL_ATTEND_DECODE, B, T = max_rows,
+ *                Dh = HQ, M = window, H)
+ *
+ * Supported: D = 128, HQ a multiple of H with HQ/H <= 16.  Arithmetic: bf16 products
+ * accumulated in fp32 on the matrix cores; the softmax weights enter the second
+ * product rounded to bf16 and the denominator sums those rounded weights, so the
+ * output is a convex combination of the V rows up to fp32 rounding, then rounded to
+ * bf16.  Fixed combination order (run-to-run deterministic); the result does not
+ * depend on the order of the rows beyond rounding.
+ */
+int kvzap_attend_decode(const void* q, const void* K_rows, const void* V_rows,
+                        int64_t total_rows, const int64_t* row_offsets,
+                        const int32_t* lengths, const void* K_ring, const void* V_ring,
+                        const int32_t* seq_pos, int window, int max_rows, float scale,
+                        void* out, int B, int H, int HQ, int D,
+                        void* workspace, size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

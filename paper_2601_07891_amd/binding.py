@@ -17,7 +17,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libkvzap.so")
 
-CALL_SCORE, CALL_MASK, CALL_COMPACT, CALL_DECODE_EVICT = 0, 1, 2, 3
+CALL_SCORE, CALL_MASK, CALL_COMPACT, CALL_DECODE_EVICT, CALL_ATTEND_DECODE = 0, 1, 2, 3, 4
 
 _c_void_p, _c_int, _c_float, _c_size_t, _c_int64 = (
     ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t, ctypes.c_int64)
@@ -34,6 +34,9 @@ SIGNATURES = {
     "kvzap_decode_evict": (_c_int, [_c_void_p] * 5 + [_c_int, _c_int] + [_c_void_p] * 12 +
                            [_c_float] + [_c_int] * 4 + [_c_void_p, _c_void_p, _c_size_t,
                                                         _c_void_p]),
+    "kvzap_attend_decode": (_c_int, [_c_void_p] * 3 + [_c_int64] + [_c_void_p] * 5 +
+                            [_c_int, _c_int, _c_float, _c_void_p] + [_c_int] * 4 +
+                            [_c_void_p, _c_size_t, _c_void_p]),
 }
 
 
@@ -250,3 +253,52 @@ def kvzap_decode_evict(hidden_new: torch.Tensor, W1: torch.Tensor, b1, W2, b2,
         _ptr(ws), ws_bytes, _stream(stream))
     if rc != 0:
         raise KvzapError(rc, "kvzap_decode_evict")
+
+
+def kvzap_attend_decode(q: torch.Tensor, K_rows: torch.Tensor, V_rows: torch.Tensor,
+                        row_offsets: torch.Tensor, lengths: torch.Tensor,
+                        K_ring: Optional[torch.Tensor], V_ring: Optional[torch.Tensor],
+                        seq_pos: Optional[torch.Tensor], window: int, max_rows: int,
+                        scale: float, out: Optional[torch.Tensor] = None,
+                        workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """q bf16 [B,HQ,D]; K_rows/V_rows bf16 [total_rows,D]; row_offsets int64 [B*H];
+    lengths int32 [B,H]; ring tensors bf16 [B,H,window,D] and seq_pos int32 [B] (None when
+    window == 0).  Returns out bf16 [B,HQ,D]."""
+    bf = torch.bfloat16
+    _check(q, bf, "q"); _check(K_rows, bf, "K_rows"); _check(V_rows, bf, "V_rows")
+    _check(row_offsets, torch.int64, "row_offsets"); _check(lengths, torch.int32, "lengths")
+    B, HQ, D = q.shape
+    if lengths.dim() != 2 or lengths.shape[0] != B:
+        raise ValueError("lengths must be [B,H]")
+    H = lengths.shape[1]
+    if row_offsets.numel() != B * H:
+        raise ValueError("row_offsets must have B*H entries")
+    if K_rows.dim() != 2 or K_rows.shape[1] != D or K_rows.shape != V_rows.shape:
+        raise ValueError("K_rows and V_rows must both be [total_rows, D]")
+    if window > 0:
+        _check(K_ring, bf, "K_ring"); _check(V_ring, bf, "V_ring")
+        _check(seq_pos, torch.int32, "seq_pos")
+        if tuple(K_ring.shape) != (B, H, window, D) or K_ring.shape != V_ring.shape:
+            raise ValueError("K_ring and V_ring must be [B,H,window,D]")
+        if seq_pos.numel() != B:
+            raise ValueError("seq_pos must have B entries")
+    if out is None:
+        out = torch.empty((B, HQ, D), dtype=bf, device=q.device)
+    else:
+        _check(out, bf, "out")
+        if out.shape != q.shape:
+            raise ValueError("out must be [B,HQ,D]")
+    ws, ws_bytes = _workspace(
+        kvzap_workspace_bytes(CALL_ATTEND_DECODE, B, int(max_rows), HQ, int(window), H),
+        q.device, workspace)
+    ring = window > 0
+    total_rows = K_rows.shape[0]
+    rc = lib().kvzap_attend_decode(
+        _ptr(q), _ptr(K_rows) if total_rows else None, _ptr(V_rows) if total_rows else None,
+        total_rows, _ptr(row_offsets), _ptr(lengths),
+        _ptr(K_ring) if ring else None, _ptr(V_ring) if ring else None,
+        _ptr(seq_pos) if ring else None, int(window), int(max_rows), float(scale), _ptr(out),
+        B, H, HQ, D, _ptr(ws), ws_bytes, _stream(stream))
+    if rc != 0:
+        raise KvzapError(rc, "kvzap_attend_decode")
+    return out

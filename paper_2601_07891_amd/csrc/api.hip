@@ -16,6 +16,13 @@ constexpr int kMaxM = 640;
 constexpr size_t kLdsBytes = 160 * 1024;
 
 // shape rules shared by kvzap_score and kvzap_decode_evict
+int check_attend_shape(int B, int H, int HQ, int max_rows, int window) {
+  if (B <= 0 || H <= 0 || HQ <= 0 || max_rows < 0 || window < 0) return KVZAP_ERR_SHAPE;
+  if (HQ % H != 0) return KVZAP_ERR_SHAPE;
+  if (HQ / H > 16 || (long long)B * H > 65535) return KVZAP_ERR_UNSUPPORTED;
+  return KVZAP_OK;
+}
+
 int check_scorer_shape(int Dh, int M, int H) {
   if (Dh <= 0 || M < 0 || H <= 0) return KVZAP_ERR_SHAPE;
   if (H > kMaxH || Dh % 64 != 0) return KVZAP_ERR_UNSUPPORTED;
@@ -53,7 +60,8 @@ const char* kvzap_status_string(int status) {
 const char* kvzap_version(void) { return "0.1.0"; }
 
 size_t kvzap_workspace_bytes(int which_call, int B, int T, int Dh, int M, int H) {
-  if (B <= 0 || T <= 0 || H <= 0) return 0;
+  if (B <= 0 || H <= 0) return 0;
+  if (T <= 0 && which_call != KVZAP_CALL_ATTEND_DECODE) return 0;
   switch (which_call) {
     case KVZAP_CALL_MASK:
       if ((long long)B * H > 65535) return 0;
@@ -64,6 +72,9 @@ size_t kvzap_workspace_bytes(int which_call, int B, int T, int Dh, int M, int H)
     case KVZAP_CALL_SCORE:
       if (check_scorer_shape(Dh, M, H) != KVZAP_OK) return 0;
       return M > 0 ? kvzap::align_up((size_t)M * Dh * 2, 256) : 0;   // W1 in fragment order
+    case KVZAP_CALL_ATTEND_DECODE:   // T = max_rows, Dh = HQ, M = window
+      if (check_attend_shape(B, H, Dh, T, M) != KVZAP_OK) return 0;
+      return kvzap::attend_workspace_bytes(B, H, Dh, T, M);
     case KVZAP_CALL_COMPACT:
     default:
       return 0;
@@ -168,6 +179,29 @@ int kvzap_decode_evict(const void* hidden_new, const void* W1, const void* b1, c
   a.lengths = lengths; a.seq_pos = seq_pos; a.tau = tau; a.window = window;
   a.B = B; a.H = H; a.D = D; a.error_flag = error_flag; a.workspace = workspace;
   return kvzap::launch_decode_evict(a, static_cast<hipStream_t>(stream));
+}
+
+int kvzap_attend_decode(const void* q, const void* K_rows, const void* V_rows,
+                        int64_t total_rows, const int64_t* row_offsets, const int32_t* lengths,
+                        const void* K_ring, const void* V_ring, const int32_t* seq_pos,
+                        int window, int max_rows, float scale, void* out, int B, int H, int HQ,
+                        int D, void* workspace, size_t workspace_bytes, void* stream) {
+  if (D <= 0 || total_rows < 0) return KVZAP_ERR_SHAPE;
+  const int rc = check_attend_shape(B, H, HQ, max_rows, window);
+  if (rc != KVZAP_OK) return rc;
+  if (D != 128) return KVZAP_ERR_UNSUPPORTED;
+  if (scale != scale) return KVZAP_ERR_SHAPE;
+  if (!q || !row_offsets || !lengths || !out) return KVZAP_ERR_NULL;
+  if (total_rows > 0 && (!K_rows || !V_rows)) return KVZAP_ERR_NULL;
+  if (window > 0 && (!K_ring || !V_ring || !seq_pos)) return KVZAP_ERR_NULL;
+  const void* ptrs[] = {q, K_rows, V_rows, row_offsets, lengths, K_ring, V_ring, seq_pos, out};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return KVZAP_ERR_ALIGN;
+  const size_t need = kvzap::attend_workspace_bytes(B, H, HQ, max_rows, window);
+  if (!workspace || !aligned256(workspace) || workspace_bytes < need) return KVZAP_ERR_WORKSPACE;
+  return kvzap::launch_attend_decode(q, K_rows, V_rows, total_rows, row_offsets, lengths, K_ring,
+                                     V_ring, seq_pos, window, max_rows, scale, out, B, H, HQ,
+                                     workspace, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

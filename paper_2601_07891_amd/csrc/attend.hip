@@ -1,0 +1,324 @@
+// Decode-step attention over the ragged per-head cache (Sec. 5; weights of Sec. 3.2
+// Eq. 2): for every KV head, its G = HQ/H query heads attend to the head's packed
+// rows and to the rows still inside the window ring.
+//
+// The kernel is bound by reading K and V once (512 bytes per row against 4*G*128
+// flops), so the design is about streaming rows with as few vector-ALU instructions
+// per byte as possible; both contractions run on v_mfma_f32_16x16x32_bf16 straight
+// from the registers the global loads fill, with no LDS and no barrier:
+//
+//   one wave = one split of one KV head, 32-row chunks, the next chunk's loads in
+//   flight while the current one is consumed.
+//
+//   S^T = K q^T      A = K   lane (i = l%16, kg = l/16) loads 16 bytes of row rho(i) at
+//                            byte 64*kk + 16*kg for kk = 0..3 (the k-slices an MFMA
+//                            step wants); two 16-row sets per chunk
+//                    B = q   lane (g = l%16, kg) holds q[g][32kk + 8kg ..+8], zero for
+//                            g >= G
+//                    C       lane (g, s = l/16), register r: row i = 4s + r of the set
+//   with rho(t, i) = 16t + 4(i%4) + i/4, so lane (g, s) ends up with the scores of the
+//   chunk rows 4j + s, j = 4t + r = 0..7: exactly the eight k-slots of B in
+//
+//   O^T = V^T P^T    A = V^T lane (c = l%16, s = l/16) loads piece c (8 values,
+//                            d = 8c..8c+7) of the rows 4j + s, j = 0..7, fully
+//                            coalesced (a load instruction covers 4 whole rows); one
+//                            v_perm per register pairs rows (2j', 2j'+1) of one d,
+//                            which is the k-pair layout of the A operand for the
+//                            d-tile {8c + e : c = 0..15}
+//                    B = P^T the exponentiated scores of lane (g, s), packed to bf16
+//                    C       lane (g, s), tile e, register r: d = 32s + 8r + e
+//   plus one more MFMA with A = ones whose result is the softmax denominator (the sum of
+//   the bf16-rounded weights, already reduced over all 32 rows).
+//
+// The softmax reference m is lazy: scores are exponentiated relative to a per-head
+// reference that is only raised (with a rescale of the accumulators) when some score
+// exceeds it by more than 2^16; fp32 and bf16 carry that range without loss, so the
+// common chunk needs no cross-lane traffic at all.
+//
+// A second small kernel combines the splits of each head and writes bf16.
+#include "kvzap_internal.h"
+
+namespace kvzap {
+namespace {
+
+constexpr int kD = 128;                 // head dimension (elements)
+constexpr int kChunkRows = 32;
+constexpr int kSplitChunks = 16;        // chunks per split: 512 rows = 256 KB of K and V
+constexpr float kLazyMargin = 16.0f;    // log2 units
+
+// Rows of one head: packed prefix [0, n_p) at row offset `off`, ring [0, n_r).
+struct HeadExtent {
+  int64_t off;
+  int n_p, n_r;
+};
+
+__device__ __forceinline__ HeadExtent head_extent(const int64_t* row_offsets,
+                                                  const int32_t* lengths,
+                                                  const int32_t* seq_pos, int window,
+                                                  int64_t total_rows, int bh, int b) {
+  HeadExtent e;
+  e.off = row_offsets[bh];
+  int64_t n = lengths[bh];
+  if (e.off < 0 || e.off > total_rows) { e.off = 0; n = 0; }
+  if (n < 0) n = 0;
+  if (n > total_rows - e.off) n = total_rows - e.off;
+  e.n_p = (int)n;
+  int r = 0;
+  if (window > 0) {
+    r = seq_pos[b];
+    r = r < 0 ? 0 : (r > window ? window : r);
+  }
+  e.n_r = r;
+  return e;
+}
+
+__device__ __forceinline__ int chunks_of(int rows) { return (rows + kChunkRows - 1) / kChunkRows; }
+
+struct Chunk {
+  u32x4 k[2][4];   // [set][k-step]
+  u32x4 v[8];      // [row group j]
+};
+
+// Loads chunk `vc` of the head's chunk list (prefix chunks, then ring chunks).  Rows past
+// the end of the segment are read from its last row (their weights are forced to zero).
+__device__ __forceinline__ void load_chunk(Chunk& c, int vc, int cp, const HeadExtent& e,
+                                           const u32x4* Kp, const u32x4* Vp,
+                                           const u32x4* Kr, const u32x4* Vr, int li, int lg,
+                                           int& row0, int& n_seg) {
+  const bool ring = vc >= cp;
+  const u32x4* Kb = ring ? Kr : Kp;
+  const u32x4* Vb = ring ? Vr : Vp;
+  n_seg = ring ? e.n_r : e.n_p;
+  row0 = (ring ? vc - cp : vc) * kChunkRows;
+  constexpr int kRowVec = kD * 2 / 16;   // 16 u32x4 per row
+  if (row0 + kChunkRows <= n_seg) {
+    const u32x4* kp = Kb + (size_t)(row0 + 4 * (li & 3) + (li >> 2)) * kRowVec + lg;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) c.k[t][kk] = kp[t * 16 * kRowVec + kk * 4];
+    const u32x4* vp = Vb + (size_t)(row0 + lg) * kRowVec + li;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) c.v[j] = vp[j * 4 * kRowVec];
+  } else {
+    const int last = n_seg - 1;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      int r = row0 + 16 * t + 4 * (li & 3) + (li >> 2);
+      r = r < last ? r : last;
+      const u32x4* kp = Kb + (size_t)r * kRowVec + lg;
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) c.k[t][kk] = kp[kk * 4];
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      int r = row0 + 4 * j + lg;
+      r = r < last ? r : last;
+      c.v[j] = Vb[(size_t)r * kRowVec + li];
+    }
+  }
+}
+
+struct Accum {
+  floatx4 o[8];    // [d-tile e][r]: d = 32s + 8r + e
+  floatx4 l;       // every register: sum of the weights of head g
+  float m;         // reference exponent of head g (scaled log2 units)
+};
+
+__device__ __forceinline__ float shfl_xor_f(float x, int mask) {
+  return __shfl_xor(x, mask, 64);
+}
+
+__device__ __forceinline__ void consume_chunk(const Chunk& c, const u32x4 (&qb)[4], Accum& a,
+                                              int row0, int n_seg, int lg, float cscale) {
+  floatx4 s[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    s[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+      s[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, c.k[t][kk]),
+                                                     __builtin_bit_cast(bf16x8, qb[kk]), s[t],
+                                                     0, 0, 0);
+  }
+  float x[8];
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) x[4 * t + r] = s[t][r] * cscale;
+  if (row0 + kChunkRows > n_seg) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (row0 + 4 * j + lg >= n_seg) x[j] = -INFINITY;
+  }
+  float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
+                   fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+  if (__any(mx > a.m + kLazyMargin)) {
+    // raise the reference to the exact running maximum of each head and rescale
+    float mn = fmaxf(mx, shfl_xor_f(mx, 16));
+    mn = fmaxf(mn, shfl_xor_f(mn, 32));
+    mn = fmaxf(mn, a.m);
+    const float alpha = __builtin_amdgcn_exp2f(a.m - mn);   // 0 when a.m = -inf
+#pragma unroll
+    for (int e = 0; e < 8; ++e) a.o[e] *= alpha;
+    a.l *= alpha;
+    a.m = mn;
+  }
+  bf16x8 p;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) p[j] = (__bf16)__builtin_amdgcn_exp2f(x[j] - a.m);
+
+  constexpr unsigned kSelLo = 0x05040100u, kSelHi = 0x07060302u;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    u32x4 vt;
+#pragma unroll
+    for (int jp = 0; jp < 4; ++jp)
+      vt[jp] = __builtin_amdgcn_perm(c.v[2 * jp + 1][e >> 1], c.v[2 * jp][e >> 1],
+                                     (e & 1) ? kSelHi : kSelLo);
+    a.o[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vt), p, a.o[e],
+                                                     0, 0, 0);
+  }
+  const u32x4 ones = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+  a.l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ones), p, a.l, 0, 0, 0);
+}
+
+// grid (NS, B*H), 64 threads.  part: [B*H][NS][G][128] fp32, ml: [B*H][NS][G][2] fp32.
+__global__ __launch_bounds__(64, 2) void attend_partial_kernel(
+    const u32x4* q, const u32x4* K_rows, const u32x4* V_rows, int64_t total_rows,
+    const int64_t* row_offsets, const int32_t* lengths, const u32x4* K_ring,
+    const u32x4* V_ring, const int32_t* seq_pos, int window, float cscale, int H, int G,
+    float* part, float* ml) {
+  const int bh = blockIdx.y, split = blockIdx.x, NS = gridDim.x;
+  const int b = bh / H;
+  const HeadExtent e = head_extent(row_offsets, lengths, seq_pos, window, total_rows, bh, b);
+  const int cp = chunks_of(e.n_p), ct = cp + chunks_of(e.n_r);
+  const int c0 = split * kSplitChunks;
+  // the last split runs to the end of the list, so a head longer than the host's bound
+  // is still covered
+  const int c1 = (split == NS - 1) ? ct : (c0 + kSplitChunks < ct ? c0 + kSplitChunks : ct);
+  if (c0 >= c1) return;
+
+  const int lane = threadIdx.x, li = lane & 15, lg = lane >> 4;
+  constexpr int kRowVec = kD * 2 / 16;
+  const u32x4* Kp = K_rows + (size_t)e.off * kRowVec;
+  const u32x4* Vp = V_rows + (size_t)e.off * kRowVec;
+  const u32x4* Kr = K_ring + (size_t)bh * (window > 0 ? window : 0) * kRowVec;
+  const u32x4* Vr = V_ring + (size_t)bh * (window > 0 ? window : 0) * kRowVec;
+
+  // q as the B operand: lane (g = li, kg = lg), k-step kk: q[g][32kk + 8kg ..+8]
+  u32x4 qb[4];
+  {
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    const u32x4* qp = q + ((size_t)bh * G + (li < G ? li : 0)) * kRowVec + lg;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) qb[kk] = li < G ? qp[kk * 4] : zero;
+  }
+
+  Accum acc;
+#pragma unroll
+  for (int t = 0; t < 8; ++t) acc.o[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+  acc.l = floatx4{0.f, 0.f, 0.f, 0.f};
+  acc.m = -INFINITY;
+
+  // Two chunk buffers; the steady-state loop has no branch around a load, so the
+  // compiler's wait counts let the loads of one buffer fly while the other is consumed.
+  Chunk ca, cb;
+  int row0a, nsega, row0b, nsegb;
+  load_chunk(ca, c0, cp, e, Kp, Vp, Kr, Vr, li, lg, row0a, nsega);
+  int vc = c0;
+  while (vc + 2 < c1) {
+    load_chunk(cb, vc + 1, cp, e, Kp, Vp, Kr, Vr, li, lg, row0b, nsegb);
+    consume_chunk(ca, qb, acc, row0a, nsega, lg, cscale);
+    load_chunk(ca, vc + 2, cp, e, Kp, Vp, Kr, Vr, li, lg, row0a, nsega);
+    consume_chunk(cb, qb, acc, row0b, nsegb, lg, cscale);
+    vc += 2;
+  }
+  if (vc + 1 < c1) {
+    load_chunk(cb, vc + 1, cp, e, Kp, Vp, Kr, Vr, li, lg, row0b, nsegb);
+    consume_chunk(ca, qb, acc, row0a, nsega, lg, cscale);
+    consume_chunk(cb, qb, acc, row0b, nsegb, lg, cscale);
+  } else {
+    consume_chunk(ca, qb, acc, row0a, nsega, lg, cscale);
+  }
+
+  if (li < G) {
+    const size_t slot = ((size_t)bh * NS + split) * G + li;
+    float* dst = part + slot * kD + 32 * lg;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      floatx4 lo = {acc.o[0][r], acc.o[1][r], acc.o[2][r], acc.o[3][r]};
+      floatx4 hi = {acc.o[4][r], acc.o[5][r], acc.o[6][r], acc.o[7][r]};
+      *reinterpret_cast<floatx4*>(dst + 8 * r) = lo;
+      *reinterpret_cast<floatx4*>(dst + 8 * r + 4) = hi;
+    }
+    if (lg == 0) {
+      ml[slot * 2] = acc.m;
+      ml[slot * 2 + 1] = acc.l[0];
+    }
+  }
+}
+
+// grid B*H*G, 128 threads (one per output element).
+__global__ __launch_bounds__(128) void attend_combine_kernel(
+    const float* part, const float* ml, int64_t total_rows, const int64_t* row_offsets,
+    const int32_t* lengths, const int32_t* seq_pos, int window, int H, int G, int NS,
+    unsigned short* out) {
+  const int bh = blockIdx.x / G, g = blockIdx.x % G, d = threadIdx.x;
+  const HeadExtent e = head_extent(row_offsets, lengths, seq_pos, window, total_rows, bh, bh / H);
+  const int ct = chunks_of(e.n_p) + chunks_of(e.n_r);
+  int ns = (ct + kSplitChunks - 1) / kSplitChunks;
+  ns = ns < NS ? ns : NS;
+  float mmax = -INFINITY;
+  for (int s = 0; s < ns; ++s) mmax = fmaxf(mmax, ml[(((size_t)bh * NS + s) * G + g) * 2]);
+  float num = 0.f, den = 0.f;
+  for (int s = 0; s < ns; ++s) {
+    const size_t slot = ((size_t)bh * NS + s) * G + g;
+    const float w = __builtin_amdgcn_exp2f(ml[slot * 2] - mmax);
+    num += w * part[slot * kD + d];
+    den += w * ml[slot * 2 + 1];
+  }
+  out[(size_t)blockIdx.x * kD + d] = float_to_bf16_bits(ns > 0 ? num / den : 0.f);
+}
+
+}  // namespace
+
+int attend_splits(int max_rows, int window) {
+  const int ct = (max_rows + kChunkRows - 1) / kChunkRows +
+                 ((window > 0 ? window : 0) + kChunkRows - 1) / kChunkRows;
+  const int ns = (ct + kSplitChunks - 1) / kSplitChunks;
+  return ns > 0 ? ns : 1;
+}
+
+size_t attend_workspace_bytes(int B, int H, int HQ, int max_rows, int window) {
+  const size_t slots = (size_t)B * H * attend_splits(max_rows, window) * (HQ / H);
+  return align_up(slots * kD * sizeof(float), 256) + align_up(slots * 2 * sizeof(float), 256);
+}
+
+int launch_attend_decode(const void* q, const void* K_rows, const void* V_rows,
+                         int64_t total_rows, const int64_t* row_offsets,
+                         const int32_t* lengths, const void* K_ring, const void* V_ring,
+                         const int32_t* seq_pos, int window, int max_rows, float scale,
+                         void* out, int B, int H, int HQ, void* workspace,
+                         hipStream_t stream) {
+  const int G = HQ / H, BH = B * H;
+  const int NS = attend_splits(max_rows, window);
+  const size_t slots = (size_t)BH * NS * G;
+  float* part = static_cast<float*>(workspace);
+  float* ml = reinterpret_cast<float*>(static_cast<char*>(workspace) +
+                                       align_up(slots * kD * sizeof(float), 256));
+  const float cscale = scale * 1.4426950408889634f;
+  hipLaunchKernelGGL(attend_partial_kernel, dim3(NS, BH), dim3(64), 0, stream,
+                     static_cast<const u32x4*>(q), static_cast<const u32x4*>(K_rows),
+                     static_cast<const u32x4*>(V_rows), total_rows, row_offsets, lengths,
+                     static_cast<const u32x4*>(K_ring), static_cast<const u32x4*>(V_ring),
+                     seq_pos, window, cscale, H, G, part, ml);
+  if (hipGetLastError() != hipSuccess) return KVZAP_ERR_RUNTIME;
+  hipLaunchKernelGGL(attend_combine_kernel, dim3(BH * G), dim3(128), 0, stream, part, ml,
+                     total_rows, row_offsets, lengths, seq_pos, window, H, G, NS,
+                     static_cast<unsigned short*>(out));
+  if (hipGetLastError() != hipSuccess) return KVZAP_ERR_RUNTIME;
+  return KVZAP_OK;
+}
+
+}  // namespace kvzap

@@ -64,4 +64,12 @@ struct DecodeArgs {
 int launch_decode_evict(const DecodeArgs& a, hipStream_t stream);
 size_t decode_workspace_bytes(int B, int Dh, int M, int H);
 
+int launch_attend_decode(const void* q, const void* K_rows, const void* V_rows,
+                         int64_t total_rows, const int64_t* row_offsets,
+                         const int32_t* lengths, const void* K_ring, const void* V_ring,
+                         const int32_t* seq_pos, int window, int max_rows, float scale,
+                         void* out, int B, int H, int HQ, void* workspace,
+                         hipStream_t stream);
+size_t attend_workspace_bytes(int B, int H, int HQ, int max_rows, int window);
+
 }  // namespace kvzap

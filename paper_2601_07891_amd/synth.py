@@ -125,6 +125,21 @@ def make_kv(wl: Workload, layer: int = 0, device="cpu",
     return K, V
 
 
+def make_attend_inputs(B: int, H: int, HQ: int, D: int, total_rows: int, window: int,
+                       seed: int, device="cpu", q_gain: float = 1.0):
+    """Inputs of one decode-attention step: q bf16 [B,HQ,D] ~ q_gain*N(0,1), row store
+    K_rows/V_rows bf16 [total_rows,D] ~ N(0,1) and ring K/V bf16 [B,H,max(window,1),D]
+    ~ N(0,1).  With scale = 1/sqrt(D) the logits are ~ N(0, q_gain^2): q_gain = 1 gives
+    a spread softmax, larger gains a peaked one."""
+    g = _gen(device, seed * 13 + 5)
+    q = _randn_bf16((B, HQ, D), g, device, q_gain)
+    K_rows = _randn_bf16((max(total_rows, 1), D), g, device)
+    V_rows = _randn_bf16((max(total_rows, 1), D), g, device)
+    K_ring = _randn_bf16((B, H, max(window, 1), D), g, device)
+    V_ring = _randn_bf16((B, H, max(window, 1), D), g, device)
+    return q, K_rows, V_rows, K_ring, V_ring
+
+
 def make_exact_case(T: int, Dh: int, H: int, M: int, seed: int, device="cpu"):
     """Inputs on which every partial sum of the linear surrogate (M == 0) is an
     exactly representable small integer in fp32, in any summation order:
