@@ -259,26 +259,59 @@ __global__ __launch_bounds__(64, 2) void attend_partial_kernel(
   }
 }
 
-// grid B*H*G, 128 threads (one per output element).
-__global__ __launch_bounds__(128) void attend_combine_kernel(
+// grid B*H*G, 256 threads: thread (c = tid%32, sg = tid/32) folds the splits sg, sg+8, ...
+// of output elements 4c..4c+3 with a running reference, then the 8 groups meet in LDS.
+constexpr int kCombineGroups = 8;
+
+__global__ __launch_bounds__(256) void attend_combine_kernel(
     const float* part, const float* ml, int64_t total_rows, const int64_t* row_offsets,
     const int32_t* lengths, const int32_t* seq_pos, int window, int H, int G, int NS,
     unsigned short* out) {
-  const int bh = blockIdx.x / G, g = blockIdx.x % G, d = threadIdx.x;
+  __shared__ floatx4 s_num[kCombineGroups][32];
+  __shared__ float s_m[kCombineGroups], s_den[kCombineGroups];
+  const int bh = blockIdx.x / G, g = blockIdx.x % G;
+  const int c = threadIdx.x & 31, sg = threadIdx.x >> 5;
   const HeadExtent e = head_extent(row_offsets, lengths, seq_pos, window, total_rows, bh, bh / H);
   const int ct = chunks_of(e.n_p) + chunks_of(e.n_r);
   int ns = (ct + kSplitChunks - 1) / kSplitChunks;
   ns = ns < NS ? ns : NS;
-  float mmax = -INFINITY;
-  for (int s = 0; s < ns; ++s) mmax = fmaxf(mmax, ml[(((size_t)bh * NS + s) * G + g) * 2]);
-  float num = 0.f, den = 0.f;
-  for (int s = 0; s < ns; ++s) {
+  float m = -INFINITY, den = 0.f;
+  floatx4 num = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+  for (int s = sg; s < ns; s += kCombineGroups) {
     const size_t slot = ((size_t)bh * NS + s) * G + g;
-    const float w = __builtin_amdgcn_exp2f(ml[slot * 2] - mmax);
-    num += w * part[slot * kD + d];
-    den += w * ml[slot * 2 + 1];
+    const float ms = ml[slot * 2], ls = ml[slot * 2 + 1];
+    const floatx4 a = *reinterpret_cast<const floatx4*>(part + slot * kD + 4 * c);
+    const float mn = fmaxf(m, ms);
+    const float w_old = __builtin_amdgcn_exp2f(m - mn), w_new = __builtin_amdgcn_exp2f(ms - mn);
+    num = num * w_old + a * w_new;
+    den = den * w_old + ls * w_new;
+    m = mn;
   }
-  out[(size_t)blockIdx.x * kD + d] = float_to_bf16_bits(ns > 0 ? num / den : 0.f);
+  s_num[sg][c] = num;
+  if (c == 0) { s_m[sg] = m; s_den[sg] = den; }
+  __syncthreads();
+  if (sg == 0) {
+    float mm = s_m[0];
+#pragma unroll
+    for (int k = 1; k < kCombineGroups; ++k) mm = fmaxf(mm, s_m[k]);
+    floatx4 n = {0.f, 0.f, 0.f, 0.f};
+    float dsum = 0.f;
+#pragma unroll
+    for (int k = 0; k < kCombineGroups; ++k) {
+      // a group that saw no split has m = -inf and zero sums; exp2(-inf - mm) = 0 unless
+      // mm is -inf too (no split at all), which the ns > 0 test below covers
+      const float w = (s_m[k] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(s_m[k] - mm);
+      n += s_num[k][c] * w;
+      dsum += s_den[k] * w;
+    }
+    unsigned short* o = out + (size_t)blockIdx.x * kD + 4 * c;
+    typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
+    u16x4 r;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) r[k] = float_to_bf16_bits(ns > 0 ? n[k] / dsum : 0.f);
+    *reinterpret_cast<u16x4*>(o) = r;
+  }
 }
 
 }  // namespace
@@ -314,7 +347,7 @@ int launch_attend_decode(const void* q, const void* K_rows, const void* V_rows,
                      static_cast<const u32x4*>(K_ring), static_cast<const u32x4*>(V_ring),
                      seq_pos, window, cscale, H, G, part, ml);
   if (hipGetLastError() != hipSuccess) return KVZAP_ERR_RUNTIME;
-  hipLaunchKernelGGL(attend_combine_kernel, dim3(BH * G), dim3(128), 0, stream, part, ml,
+  hipLaunchKernelGGL(attend_combine_kernel, dim3(BH * G), dim3(256), 0, stream, part, ml,
                      total_rows, row_offsets, lengths, seq_pos, window, H, G, NS,
                      static_cast<unsigned short*>(out));
   if (hipGetLastError() != hipSuccess) return KVZAP_ERR_RUNTIME;
