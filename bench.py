@@ -31,6 +31,8 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 MEASURED_HBM_TRAFFIC = {
     ("c3_qwen8b_128k_mlp", "score_mlp_frag_kernel"): 1209.2e6 + 4.2e6,
     ("c3_qwen8b_128k_mlp", "compact_kernel"): 146.5e6 + 143.3e6,
+    # profiles/c5_attend_hbm_traffic.txt (default rows-per-head range, 32 query heads)
+    ("c5_qwen8b_decode+attend", "attend_partial_kernel"): 4926.1e6 + 10.4e6,
 }
 
 
@@ -212,7 +214,9 @@ def bench_attend(wl, args) -> int:
                    "rows_per_head": [lo, hi], "cache_rows_per_layer": rows},
         "ms_per_call": ms_call,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                     "frac": achieved / PEAK_HBM_GBS, "traffic": None,
+                     "frac": achieved / PEAK_HBM_GBS,
+                     "traffic": (MEASURED_HBM_TRAFFIC.get((wl.name + "+attend", "attend_partial_kernel"))
+                                 if (lo, hi, HQ, B) == (4096, 32768, 32, 64) else None),
                      "kernel": "attend_partial_kernel (+ attend_combine_kernel in the same interval)",
                      "bytes_per_launch": bytes_call},
         "cpu_baseline": {"value": sample_rows / (c1 - c0), "unit": "cache rows/s",
