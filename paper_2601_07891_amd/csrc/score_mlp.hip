@@ -297,6 +297,27 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
   const long long row0 = (long long)blockIdx.x * TOK;
   const int rows_here = (rows - row0 < TOK) ? (int)(rows - row0) : TOK;
 
+  // The epilogue's operands (W2 and b1, a few KB) are staged in LDS behind the ring: read
+  // from global memory there, every one of its 64 small loads would expose a full memory
+  // round trip with nothing to overlap it.  The loads are issued here, ahead of the
+  // prologue's traffic, and written to LDS once the prologue has waited for hidden tile 0
+  // (vector-memory operations complete in issue order).
+  constexpr int kW2Pieces = U / 128;                    // 16-byte pieces of W2 per thread (H <= 16)
+  unsigned char* const sW2 = smem + kNS * STAGE;        // [H][U] bf16
+  float* const sB1 = reinterpret_cast<float*>(sW2 + 16 * U * 2);   // [U] fp32
+  u32x4 w2_stage[kW2Pieces];
+  unsigned short b1_stage[U / 256 + 1];
+#pragma unroll
+  for (int i = 0; i < kW2Pieces; ++i) {
+    const int piece = i * 256 + tid;
+    w2_stage[i] = piece < H * (U / 8) ? reinterpret_cast<const u32x4*>(W2)[piece] : u32x4{0u, 0u, 0u, 0u};
+  }
+#pragma unroll
+  for (int i = 0; i < U / 256 + 1; ++i) {
+    const int u = i * 256 + tid;
+    b1_stage[i] = (b1 && u < U) ? b1[u] : (unsigned short)0;
+  }
+
   // hidden load-to-LDS: instruction j (0..3) of wavefront w fills LDS chunk j*4+w of a
   // stage = rows (j*4+w)*8 + lane/8, physical piece lane%8 <- logical piece (lane%8) ^ (row%8)
   const unsigned char* hb = reinterpret_cast<const unsigned char*>(hidden + (size_t)row0 * Dh);
@@ -348,6 +369,16 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
   __builtin_amdgcn_sched_barrier(0);
   wait_vmcnt<NDJ * (kPD - 1) + 4 * UB>();
   block_barrier_no_drain();
+#pragma unroll
+  for (int i = 0; i < kW2Pieces; ++i) {
+    const int piece = i * 256 + tid;
+    if (piece < H * (U / 8)) reinterpret_cast<u32x4*>(sW2)[piece] = w2_stage[i];
+  }
+#pragma unroll
+  for (int i = 0; i < U / 256 + 1; ++i) {
+    const int u = i * 256 + tid;
+    if (u < U) sB1[u] = bf16_bits_to_float(b1_stage[i]);
+  }
   auto read_b = [&](int buf, int tile, int kk, int tb) {
     b[buf][tb] = *reinterpret_cast<const bf16x8*>(
         smem + (tile % kNS) * STAGE + lds_off(32 * tb + l32, kk * 2 + kg));
@@ -357,37 +388,60 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
 
   // One K tile.  MORE: tile t+1 exists; MORE_PD: tile t+kPD exists.  Both are compile-time
   // so that the body is a single basic block whose instruction order is the source order.
+  //
+  // The hand-over to tile t+1 sits in the MIDDLE of tile t (before k-step 2), not at its
+  // end: after that barrier the B reads of (t+1, step 0) are spread over k-step 3 like any
+  // other step's, so no LDS latency is exposed between tiles, and the load-to-LDS of tile
+  // t+kPD (which overwrites the stage of tile t-1, read for the last time before every
+  // wavefront's arrival at this barrier) is issued during k-steps 2 and 3.
   auto tile_body = [&](int t, auto more_tag, auto more_pd_tag) {
     constexpr bool more = decltype(more_tag)::value, more_pd = decltype(more_pd_tag)::value;
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
+      if (more && kk == 2) {
+        // hidden tile t+1 must have landed.  Its load-to-LDS operations are followed in this
+        // wavefront's in-order vector-memory stream by at least one whole tile of A-fragment
+        // loads (4*UB) plus the 2*UB-1 issued so far in this tile (for tile 1: by the
+        // prologue's 4*UB and these), so allowing that many operations to stay outstanding
+        // is always sufficient.
+        wait_vmcnt<6 * UB - 1>();
+        block_barrier_no_drain();
+      }
 #pragma unroll
       for (int ub = 0; ub < UB; ++ub) {
-        // B reads for the next step, (one hidden load-to-LDS), 4 MFMAs, then re-load this
+        // B reads for the next step, (one hidden load-to-LDS), 4 MFMAs, then re-load an
         // A fragment with the next tile's data
-        if (kk < 3) {
+        if (kk < 3 || more) {
 #pragma unroll
           for (int tb = 0; tb < TB; ++tb)
-            if (tb * UB / TB == ub) read_b((kk + 1) & 1, t, kk + 1, tb);
+            if (tb * UB / TB == ub) {
+              if (kk < 3) read_b((kk + 1) & 1, t, kk + 1, tb);
+              else read_b(0, t + 1, 0, tb);
+            }
         }
-        if (more_pd && ub == 0 && kk < NDJ) dma(kk, t + kPD);
+        if (more_pd && kk >= 2) {
+          // the NDJ load-to-LDS instructions of tile t+kPD, spread over the 2*UB groups of
+          // k-steps 2 and 3
+#pragma unroll
+          for (int j = 0; j < NDJ; ++j)
+            if (j * 2 * UB / NDJ == (kk - 2) * UB + ub) dma(j, t + kPD);
+        }
 #pragma unroll
         for (int tb = 0; tb < TB; ++tb)
           acc[ub][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk][ub], b[kk & 1][tb],
                                                                 acc[ub][tb], 0, 0, 0);
-        if (more) a[kk][ub] = aload(t + 1, ub, kk);
+        // re-load the fragment of the PREVIOUS group: a load issued right behind the MFMAs
+        // that still read its destination registers costs extra issue cycles
+        if (more) {
+          if (ub > 0) a[kk][ub - 1] = aload(t + 1, ub - 1, kk);
+          else if (kk > 0) a[kk - 1][UB - 1] = aload(t + 1, UB - 1, kk - 1);
+        }
         __builtin_amdgcn_sched_barrier(0);
       }
     }
     if (more) {
-      // hidden tile t+1 must have landed.  Its load-to-LDS operations are followed in this
-      // wavefront's in-order vector-memory stream by at least UB + (kPD-1)*4*UB A-fragment
-      // loads (the rest of their own tile, then two whole tiles), so allowing that many
-      // operations to stay outstanding is always sufficient.
-      wait_vmcnt<UB + (kPD - 1) * 4 * UB>();
-      block_barrier_no_drain();
-#pragma unroll
-      for (int tb = 0; tb < TB; ++tb) read_b(0, t + 1, 0, tb);
+      a[3][UB - 1] = aload(t + 1, UB - 1, 3);
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
   int t = 0;
@@ -410,14 +464,15 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
       const int u0 = ubase + 32 * ub + 16 * s + 4 * kg;
       u32x4 w2 = {0u, 0u, 0u, 0u};
       if (l32 < H) {
-        const uint2 p0 = *reinterpret_cast<const uint2*>(W2 + (size_t)l32 * U + u0);
-        const uint2 p1 = *reinterpret_cast<const uint2*>(W2 + (size_t)l32 * U + u0 + 8);
+        const uint2 p0 = *reinterpret_cast<const uint2*>(sW2 + ((size_t)l32 * U + u0) * 2);
+        const uint2 p1 = *reinterpret_cast<const uint2*>(sW2 + ((size_t)l32 * U + u0 + 8) * 2);
         w2.x = p0.x; w2.y = p0.y; w2.z = p1.x; w2.w = p1.y;
       }
+      const floatx4 bias_lo = *reinterpret_cast<const floatx4*>(sB1 + u0);
+      const floatx4 bias_hi = *reinterpret_cast<const floatx4*>(sB1 + u0 + 8);
       float bias[8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e)
-        bias[e] = b1 ? bf16_bits_to_float(b1[u0 + 8 * (e / 4) + (e % 4)]) : 0.0f;
+      for (int e = 0; e < 8; ++e) bias[e] = e < 4 ? bias_lo[e] : bias_hi[e - 4];
 #pragma unroll
       for (int tb = 0; tb < TB; ++tb) {
         // GELU output as a bf16 pair: ghi = round(g), glo = round(g - ghi) (hardware RNE
@@ -445,16 +500,21 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
       if (head < H) red[(wid * H + head) * TOK + 32 * tb + l32] = acc2[tb][r];
     }
   __syncthreads();
+  // sequence and position of the block's first token: one 64-bit division per block, the
+  // elements then only step over sequence ends
+  const long long b_first = row0 / T;
+  const int t_first = (int)(row0 - b_first * T);
   for (int i = tid; i < H * TOK; i += 256) {
     const int head = i / TOK, tok = i % TOK;
-    const long long r = row0 + tok;
-    if (r < rows) {
+    if (tok < rows_here) {
       float s = red[(0 * H + head) * TOK + tok];
       s += red[(1 * H + head) * TOK + tok];
       s += red[(2 * H + head) * TOK + tok];
       s += red[(3 * H + head) * TOK + tok];
       if (b2) s += bf16_bits_to_float(b2[head]);
-      const long long bidx = r / T, t = r - bidx * T;
+      long long bidx = b_first;
+      long long t = (long long)t_first + tok;
+      while (t >= T) { t -= T; ++bidx; }
       scores[((size_t)bidx * H + head) * T + t] = s;
     }
   }
@@ -465,8 +525,9 @@ int launch_frag(const void* hidden, const void* W1, const void* b1, const void* 
                 const void* b2, float* scores, long long rows, int T, int Dh, int H,
                 void* workspace, hipStream_t stream) {
   constexpr int TOK = 32 * TB;
-  constexpr size_t lds = (size_t)kNS * TOK * 128;
-  static_assert(lds >= (size_t)4 * 16 * TOK * sizeof(float), "reduction buffer fits");
+  constexpr size_t ring = (size_t)kNS * TOK * 128;
+  static_assert(ring >= (size_t)4 * 16 * TOK * sizeof(float), "reduction buffer fits");
+  constexpr size_t lds = ring + (size_t)16 * (128 * UB) * 2 + (size_t)(128 * UB) * 4;   // + W2, b1
   static bool attr_set = false;
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(score_mlp_frag_kernel<UB, TB>),
