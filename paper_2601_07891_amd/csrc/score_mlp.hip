@@ -492,12 +492,22 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
     }
   }
   float* red = reinterpret_cast<float*>(smem);     // [4][H][TOK]
+  // acc2[tb][r] is head 8*(r/4) + 4*kg + r%4 of token 32*tb + l32
 #pragma unroll
   for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int head = 8 * (r / 4) + 4 * kg + (r % 4);
-      if (head < H) red[(wid * H + head) * TOK + 32 * tb + l32] = acc2[tb][r];
+    for (int q = 0; q < 4; ++q) {
+      if (8 * q + 8 <= H) {                        // uniform: all eight heads of this group exist
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          red[(wid * H + 8 * q + 4 * kg + e) * TOK + 32 * tb + l32] = acc2[tb][4 * q + e];
+      } else if (8 * q < H) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int head = 8 * q + 4 * kg + e;
+          if (head < H) red[(wid * H + head) * TOK + 32 * tb + l32] = acc2[tb][4 * q + e];
+        }
+      }
     }
   __syncthreads();
   // sequence and position of the block's first token: one 64-bit division per block, the
