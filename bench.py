@@ -119,6 +119,35 @@ def bench_decode(wl, args) -> int:
     ms_per_step = (t1 - t0) * 1e3 / steps
     grown = float(torch.stack([st.lengths.float().mean() for st, _ in layers]).mean()
                   - len0.float().mean())
+
+    # second figure: the same L calls captured once in a HIP graph and replayed (inputs are
+    # copied into fixed buffers before every replay, as a model's previous layer would write
+    # them); the slabs have room for exactly `steps` more tokens
+    graph_ms = None
+    if args.graph:
+        h_in, k_in, v_in = (torch.empty_like(hid[0]), torch.empty_like(kv[0][0]),
+                            torch.empty_like(kv[0][1]))
+
+        def gstep():
+            for st, wt in layers:
+                binding.kvzap_decode_evict(h_in, wt["W1"], wt["b1"], wt["W2"], wt["b2"], k_in, v_in,
+                                           st, tau, ws)
+
+        for st, _ in layers:                     # back to the initial lengths: capacity for the replays
+            st.lengths.copy_(len0.to(torch.int32))
+        torch.cuda.synchronize()
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr):
+            gstep()
+        torch.cuda.synchronize()
+        reps = max(1, min(steps, warm + steps - 1))
+        g0 = time.perf_counter()
+        for i in range(reps):
+            h, (k, v) = hid[i % n_in], kv[i % n_in]
+            h_in.copy_(h); k_in.copy_(k); v_in.copy_(v)
+            gr.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - g0) * 1e3 / reps
     out = {"metric": "decode-evict tokens/sec (all layers per token)", "value": B / (ms_per_step * 1e-3),
            "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warm,
            "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
@@ -127,6 +156,9 @@ def bench_decode(wl, args) -> int:
                       "kv_heads": H, "head_dim": D, "window": w, "tau": tau,
                       "kept_per_step_fraction": grown / (steps + warm)},
            "us_per_layer_step": ms_per_step * 1e3 / L,
+           "hip_graph": (None if graph_ms is None else
+                         {"ms_per_step": graph_ms, "us_per_layer_step": graph_ms * 1e3 / L,
+                          "tokens_per_s": B / (graph_ms * 1e-3)}),
            "roofline": None, "cpu_baseline": None,
            "note": "latency-bound: ~5.5 MB per layer-step; one library call per layer per step, eager"}
     print(json.dumps(out))
@@ -243,6 +275,8 @@ def main() -> int:
                          "default is one stream, which keeps per-kernel timings clean")
     ap.add_argument("--decode-cache-rows", type=int, nargs=2, default=[4096, 32768],
                     help="decode workload: range of rows already kept per (sequence, head)")
+    ap.add_argument("--graph", action="store_true",
+                    help="decode workload: also time the step replayed from a HIP graph")
     ap.add_argument("--stage", default="evict", choices=["evict", "attend"],
                     help="decode workload: time the eviction step (default) or the attention "
                          "over the ragged cache it maintains")

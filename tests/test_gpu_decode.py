@@ -159,3 +159,87 @@ def test_decode_full_slab_sets_error_flag():
     torch.cuda.synchronize()
     assert int(st.error_flag[0]) == 1
     assert (parity.to_np(st.lengths) == 2).all()                  # never beyond capacity
+
+
+def _clone_state(st):
+    c = binding.DecodeState(st.B, st.H, st.D, st.window, st.slab_capacity.cpu().reshape(st.B, st.H), DEV)
+    for name in ("K_prefix", "V_prefix", "prefix_pos", "K_ring", "V_ring", "score_ring", "lengths",
+                 "seq_pos", "error_flag"):
+        getattr(c, name).copy_(getattr(st, name))
+    return c
+
+
+def test_decode_and_attention_replayed_from_a_hip_graph_match_eager():
+    """One decode step of three layers (evict + attention each) captured in a HIP graph and
+    replayed several times, with eager work and synchronisation between the replays; after
+    every replay the states and the attention outputs equal the eager run's bit for bit."""
+    wl = synth.with_size(synth.CONFIGS["c5_qwen8b_decode"], B=4, Dh=1024)
+    B, H, D, w, L, steps, tau = 4, wl.H, 128, 16, 3, 6, 0.0
+    HQ = 4 * H
+    cap = np.full((B, H), steps + 40)
+    wts = [synth.make_weights(wl, l, DEV) for l in range(L)]
+    eager = [binding.DecodeState(B, H, D, w, cap, DEV) for _ in range(L)]
+    for l, st in enumerate(eager):                       # some history before the captured steps
+        for i in range(30):
+            hid = synth.make_hidden(wl, 500 + i, DEV, B=1, T=B)[0].contiguous()
+            k, v = synth.make_kv(wl, 600 + i + l, DEV, B=B, T=1)
+            binding.kvzap_decode_evict(hid, wts[l]["W1"], wts[l]["b1"], wts[l]["W2"], wts[l]["b2"],
+                                       k[:, :, 0].contiguous(), v[:, :, 0].contiguous(), st, tau)
+    torch.cuda.synchronize()
+    graphed = [_clone_state(st) for st in eager]
+
+    h_in = torch.zeros((B, wl.Dh), dtype=torch.bfloat16, device=DEV)
+    k_in = torch.zeros((B, H, D), dtype=torch.bfloat16, device=DEV)
+    v_in = torch.zeros_like(k_in)
+    q_in = torch.zeros((B, HQ, D), dtype=torch.bfloat16, device=DEV)
+    outs = {"eager": [torch.zeros_like(q_in) for _ in range(L)],
+            "graph": [torch.zeros_like(q_in) for _ in range(L)]}
+    ws_e = torch.empty(binding.kvzap_workspace_bytes(binding.CALL_DECODE_EVICT, B, 1, wl.Dh, wl.M, H),
+                       dtype=torch.uint8, device=DEV)
+    ws_a = torch.empty(binding.kvzap_workspace_bytes(binding.CALL_ATTEND_DECODE, B, steps + 40, HQ, w, H),
+                       dtype=torch.uint8, device=DEV)
+
+    def step(states, out_list):
+        for l, st in enumerate(states):
+            binding.kvzap_decode_evict(h_in, wts[l]["W1"], wts[l]["b1"], wts[l]["W2"], wts[l]["b2"],
+                                       k_in, v_in, st, tau, ws_e)
+            binding.kvzap_attend_decode(q_in, st.K_prefix, st.V_prefix, st.slab_offsets, st.lengths,
+                                        st.K_ring, st.V_ring, st.seq_pos, w, steps + 40, D ** -0.5,
+                                        out=out_list[l], workspace=ws_a)
+
+    def set_inputs(i):
+        h_in.copy_(synth.make_hidden(wl, 700 + i, DEV, B=1, T=B)[0])
+        k, v = synth.make_kv(wl, 800 + i, DEV, B=B, T=1)
+        k_in.copy_(k[:, :, 0]); v_in.copy_(v[:, :, 0])
+        q_in.copy_(synth.make_attend_inputs(B, H, HQ, D, 1, 0, 900 + i, DEV)[0])
+
+    # capture on a scratch copy so that capturing changes neither state
+    scratch = [_clone_state(st) for st in eager]
+    set_inputs(0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step(scratch, outs["graph"])                     # warm-up outside capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step(graphed, outs["graph"])
+    torch.cuda.synchronize()
+    # capture launches nothing: graphed states still equal the eager ones
+    for i in range(steps):
+        set_inputs(i)
+        step(eager, outs["eager"])
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        (outs["eager"][0].float() * 2).sum().item()      # eager work between replays
+        for l in range(L):
+            for name in ("K_prefix", "V_prefix", "prefix_pos", "K_ring", "V_ring", "score_ring",
+                         "lengths", "seq_pos"):
+                a, b = getattr(eager[l], name), getattr(graphed[l], name)
+                assert torch.equal(a.view(torch.uint8).reshape(-1), b.view(torch.uint8).reshape(-1)), \
+                    f"replay {i}, layer {l}: {name} differs"
+            assert torch.equal(outs["eager"][l].view(torch.int16), outs["graph"][l].view(torch.int16)), \
+                f"replay {i}, layer {l}: attention output differs"
+    assert int(eager[0].seq_pos[0]) == 30 + steps

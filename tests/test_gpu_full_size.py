@@ -98,3 +98,38 @@ def test_config4_full_layer_mlp():
 
 def test_config4_full_layer_linear():
     _full_size_case("c4_qwen32b_4x64k_linear", n_random=600)
+
+
+def test_decode_attention_at_the_benchmark_shape():
+    """kvzap_attend_decode at the decode workload's cache shape (64 sequences x 8 KV heads of
+    4096..32768 rows + a full 128-row ring, 32 query heads), as bench.py launches it; the
+    oracle recomputes a sample of heads one by one: the shortest, the longest, the first, the
+    last and a few random ones."""
+    wl = synth.CONFIGS["c5_qwen8b_decode"]
+    B, H, D, w, HQ = wl.B, wl.H, wl.D, wl.window, 32
+    G = HQ // H
+    g = torch.Generator().manual_seed(wl.seed)
+    lens = torch.randint(4096, 32768 + 1, (B, H), generator=g).to(torch.int32)
+    off = torch.zeros(B * H, dtype=torch.int64)
+    off[1:] = torch.cumsum(lens.reshape(-1).to(torch.int64), 0)[:-1]
+    total = int(lens.sum())
+    q, Kr, Vr, Kg, Vg = synth.make_attend_inputs(B, H, HQ, D, total, w, wl.seed, DEV)
+    sp = torch.full((B,), 40000, dtype=torch.int32, device=DEV)
+    scale = D ** -0.5
+    out = binding.kvzap_attend_decode(q, Kr, Vr, off.to(DEV), lens.to(DEV), Kg, Vg, sp, w, 32768,
+                                      scale)
+    torch.cuda.synchronize()
+    flat = lens.reshape(-1)
+    rng = np.random.default_rng(3)
+    heads = {0, B * H - 1, int(flat.argmin()), int(flat.argmax())}
+    heads.update(int(x) for x in rng.integers(0, B * H, 6))
+    for bh in sorted(heads):
+        b, h = divmod(bh, H)
+        o, n = int(off[bh]), int(flat[bh])
+        K = synth.f64(torch.cat([Kr[o:o + n], Kg[b, h]]))
+        V = synth.f64(torch.cat([Vr[o:o + n], Vg[b, h]]))
+        ref = O.attend_decode(synth.f64(q[b:b + 1, h * G:(h + 1) * G]), [[(K, V)]], scale)[0]
+        got = out[b, h * G:(h + 1) * G].to(torch.float64).cpu().numpy()
+        err = np.abs(got - ref)
+        assert err.max() <= 2.0 ** -7 * max(1.0, float(np.abs(V).max())), (bh, err.max())
+        assert np.sqrt((err ** 2).mean()) <= 2e-3 * np.sqrt((ref ** 2).mean()) + 1e-3, bh
