@@ -370,3 +370,54 @@ def attend_decode(q: np.ndarray, caches, scale: float) -> np.ndarray:
             p = p / p.sum()
             out[b, g] = p @ np.asarray(V, dtype=np.float64)
     return out
+
+
+# --------------------------------------------------------------------------
+# paged layout of the ragged cache (Sec. 1, criterion 3: compatibility with
+# paged attention; Sec. 5: heads of different lengths need pages per head)
+# --------------------------------------------------------------------------
+def pages_needed(n_rows: int, page_rows: int, reserve_rows: int = 0) -> int:
+    """Pages of `page_rows` rows that hold n_rows + reserve_rows rows (0 for 0)."""
+    total = int(n_rows) + int(reserve_rows)
+    return 0 if total <= 0 else (total + page_rows - 1) // page_rows
+
+
+def assign_pages(lengths: np.ndarray, page_rows: int, free_pages: Sequence[int],
+                 max_pages: int, reserve_rows: int = 0):
+    """Give every head, in (sequence, head) order, the next pages of the free
+    list.  Reading (the paper fixes no allocator): first-fit in list order, so
+    the result is unique.  Returns (block_table [B*H, max_pages] int32 with -1
+    in unused entries, pages_used, ok); when the free list is too short or a
+    head needs more than max_pages, nothing is assigned and ok is False."""
+    n = np.asarray(lengths, dtype=np.int64).reshape(-1)
+    need = [pages_needed(int(x), page_rows, reserve_rows) for x in n]
+    table = np.full((n.size, max_pages), -1, dtype=np.int32)
+    if sum(need) > len(free_pages) or (need and max(need) > max_pages):
+        return table, 0, False
+    pos = 0
+    for bh, c in enumerate(need):
+        for i in range(c):
+            table[bh, i] = int(free_pages[pos])
+            pos += 1
+    return table, pos, True
+
+
+def scatter_to_pages(rows_per_head: Sequence[np.ndarray], table: np.ndarray,
+                     page_rows: int, num_pages: int, D: int) -> np.ndarray:
+    """Write row j of head bh to row j % page_rows of page table[bh, j // page_rows].
+    rows_per_head[bh] is uint16 [n_bh, D].  Returns the pool uint16
+    [num_pages, page_rows, D], zero where nothing was written."""
+    pool = np.zeros((num_pages, page_rows, D), dtype=np.uint16)
+    for bh, rows in enumerate(rows_per_head):
+        for j in range(rows.shape[0]):
+            pool[table[bh, j // page_rows], j % page_rows] = rows[j]
+    return pool
+
+
+def gather_from_pages(pool: np.ndarray, table_row: np.ndarray, n_rows: int,
+                      page_rows: int) -> np.ndarray:
+    """The first n_rows rows of one head, read back through its block table."""
+    out = np.zeros((n_rows, pool.shape[2]), dtype=pool.dtype)
+    for j in range(n_rows):
+        out[j] = pool[table_row[j // page_rows], j % page_rows]
+    return out
