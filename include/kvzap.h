@@ -62,7 +62,8 @@ typedef enum kvzap_call {
   KVZAP_CALL_MASK = 1,
   KVZAP_CALL_COMPACT = 2,
   KVZAP_CALL_DECODE_EVICT = 3,
-  KVZAP_CALL_ATTEND_DECODE = 4   /* pass T = max_rows, Dh = HQ, M = window */
+  KVZAP_CALL_ATTEND_DECODE = 4,  /* pass T = max_rows, Dh = HQ, M = window (also for the paged form) */
+  KVZAP_CALL_ASSIGN_PAGES = 5    /* only B and H matter (pass T = 1) */
 } kvzap_call;
 
 /* Text for a status code (host pointer to a static string, never NULL). */
@@ -242,6 +243,60 @@ int kvzap_attend_decode(const void* q, const void* K_rows, const void* V_rows,
                         const int32_t* seq_pos, int window, int max_rows, float scale,
                         void* out, int B, int H, int HQ, int D,
                         void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Paged layout of the ragged cache (Sec. 1, third criterion: a pruning method has to work
+ * with paged attention; Sec. 5: per-head lengths need pages per head).  The kept rows of
+ * head (b,h) live in pages of page_rows rows taken from one pool:
+ *
+ *   K_pool, V_pool  bf16 [num_pages, page_rows, D]
+ *   block_table     int32 [B*H, max_pages]: row j of head (b,h) is row j % page_rows of
+ *                   page block_table[b*H+h][j / page_rows]; unused entries are -1
+ *   page_rows       a power of two >= 16
+ *
+ * kvzap_assign_pages -- fills the block table from the lengths kvzap_mask produced: head
+ * (b,h), in (b,h) order, takes the next ceil((lengths[b,h] + reserve_rows) / page_rows)
+ * entries of free_pages (first fit in list order; reserve_rows leaves room for tokens
+ * appended later).  result (device int32 [2]): [0] = entries of free_pages consumed,
+ * [1] = 0 on success, 1 if the free list is too short, 2 if a head needs more than
+ * max_pages; on failure every table entry is -1 and nothing is consumed.  The library
+ * never reads the pool here and keeps no allocator state: the caller removes the first
+ * result[0] entries from its free list.
+ *   lengths int32 [B,H]; free_pages int32 [n_free]; block_table fully overwritten.
+ *   workspace: kvzap_workspace_bytes(KVZAP_CALL_ASSIGN_PAGES, B, 1, 0, 0, H).
+ */
+int kvzap_assign_pages(const int32_t* lengths, int B, int H, int page_rows, int reserve_rows,
+                       const int32_t* free_pages, int n_free, int32_t* block_table,
+                       int max_pages, int32_t* result,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * kvzap_compact_paged -- the gather of kvzap_compact written through a block table
+ * (Algorithm 1, last line, into the layout above).  keep_idx, lengths and offsets are
+ * kvzap_mask's outputs (offsets only locates each head's slice of keep_idx).  A kept row
+ * whose page slot is beyond max_pages or whose table entry is not in [0, num_pages) is
+ * skipped; rows of a page beyond the head's length are left untouched.  K, V must not
+ * overlap the pools.  D in {64, 128, 256}.
+ */
+int kvzap_compact_paged(const void* K, const void* V, const int32_t* keep_idx,
+                        const int32_t* lengths, const int64_t* offsets,
+                        const int32_t* block_table, int max_pages, int page_rows,
+                        void* K_pool, void* V_pool, int num_pages,
+                        int B, int H, int T, int D, void* stream);
+
+/*
+ * kvzap_attend_decode_paged -- kvzap_attend_decode over the paged layout: the packed rows
+ * of head (b,h) are its first lengths[b,h] rows in block-table order, the window ring is
+ * as before.  A table entry outside [0, num_pages) is clamped into the pool (the call never
+ * reads outside it; the result for that head is then meaningless), lengths are cut at
+ * max_pages * page_rows.  Same arithmetic, workspace and limits as kvzap_attend_decode.
+ */
+int kvzap_attend_decode_paged(const void* q, const void* K_pool, const void* V_pool,
+                              int num_pages, const int32_t* block_table, int max_pages,
+                              int page_rows, const int32_t* lengths, const void* K_ring,
+                              const void* V_ring, const int32_t* seq_pos, int window,
+                              int max_rows, float scale, void* out, int B, int H, int HQ,
+                              int D, void* workspace, size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -18,6 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libkvzap.so")
 
 CALL_SCORE, CALL_MASK, CALL_COMPACT, CALL_DECODE_EVICT, CALL_ATTEND_DECODE = 0, 1, 2, 3, 4
+CALL_ASSIGN_PAGES = 5
 
 _c_void_p, _c_int, _c_float, _c_size_t, _c_int64 = (
     ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t, ctypes.c_int64)
@@ -37,6 +38,13 @@ SIGNATURES = {
     "kvzap_attend_decode": (_c_int, [_c_void_p] * 3 + [_c_int64] + [_c_void_p] * 5 +
                             [_c_int, _c_int, _c_float, _c_void_p] + [_c_int] * 4 +
                             [_c_void_p, _c_size_t, _c_void_p]),
+    "kvzap_assign_pages": (_c_int, [_c_void_p, _c_int, _c_int, _c_int, _c_int, _c_void_p, _c_int,
+                                    _c_void_p, _c_int, _c_void_p, _c_void_p, _c_size_t, _c_void_p]),
+    "kvzap_compact_paged": (_c_int, [_c_void_p] * 6 + [_c_int, _c_int, _c_void_p, _c_void_p] +
+                            [_c_int] * 5 + [_c_void_p]),
+    "kvzap_attend_decode_paged": (_c_int, [_c_void_p] * 3 + [_c_int, _c_void_p, _c_int, _c_int] +
+                                  [_c_void_p] * 4 + [_c_int, _c_int, _c_float, _c_void_p] +
+                                  [_c_int] * 4 + [_c_void_p, _c_size_t, _c_void_p]),
 }
 
 
@@ -301,4 +309,105 @@ def kvzap_attend_decode(q: torch.Tensor, K_rows: torch.Tensor, V_rows: torch.Ten
         B, H, HQ, D, _ptr(ws), ws_bytes, _stream(stream))
     if rc != 0:
         raise KvzapError(rc, "kvzap_attend_decode")
+    return out
+
+
+def kvzap_assign_pages(lengths: torch.Tensor, page_rows: int, free_pages: torch.Tensor,
+                       max_pages: int, reserve_rows: int = 0,
+                       block_table: Optional[torch.Tensor] = None,
+                       result: Optional[torch.Tensor] = None,
+                       workspace: Optional[torch.Tensor] = None, stream=None):
+    """lengths int32 [B,H]; free_pages int32 [n_free].  Returns (block_table int32
+    [B*H, max_pages], result int32 [2] = (pages taken, status)), both on the device."""
+    _check(lengths, torch.int32, "lengths"); _check(free_pages, torch.int32, "free_pages")
+    B, H = lengths.shape
+    if block_table is None:
+        block_table = torch.empty((B * H, max_pages), dtype=torch.int32, device=lengths.device)
+    else:
+        _check(block_table, torch.int32, "block_table")
+        if tuple(block_table.shape) != (B * H, max_pages):
+            raise ValueError("block_table must be [B*H, max_pages]")
+    if result is None:
+        result = torch.empty(4, dtype=torch.int32, device=lengths.device)
+    else:
+        _check(result, torch.int32, "result")
+    ws, ws_bytes = _workspace(kvzap_workspace_bytes(CALL_ASSIGN_PAGES, B, 1, 0, 0, H),
+                              lengths.device, workspace)
+    n_free = free_pages.numel()
+    rc = lib().kvzap_assign_pages(_ptr(lengths), B, H, int(page_rows), int(reserve_rows),
+                                  _ptr(free_pages) if n_free else None, n_free,
+                                  _ptr(block_table), int(max_pages), _ptr(result),
+                                  _ptr(ws), ws_bytes, _stream(stream))
+    if rc != 0:
+        raise KvzapError(rc, "kvzap_assign_pages")
+    return block_table, result
+
+
+def kvzap_compact_paged(K: torch.Tensor, V: torch.Tensor, keep_idx: torch.Tensor,
+                        lengths: torch.Tensor, offsets: torch.Tensor,
+                        block_table: torch.Tensor, page_rows: int, K_pool: torch.Tensor,
+                        V_pool: torch.Tensor, stream=None) -> None:
+    """K, V bf16 [B,H,T,D]; pools bf16 [num_pages, page_rows, D], written in place."""
+    bf = torch.bfloat16
+    _check(K, bf, "K"); _check(V, bf, "V"); _check(K_pool, bf, "K_pool"); _check(V_pool, bf, "V_pool")
+    _check(keep_idx, torch.int32, "keep_idx"); _check(lengths, torch.int32, "lengths")
+    _check(offsets, torch.int64, "offsets"); _check(block_table, torch.int32, "block_table")
+    B, H, T, D = K.shape
+    if V.shape != K.shape or K_pool.shape != V_pool.shape:
+        raise ValueError("K/V and the two pools must have matching shapes")
+    if K_pool.dim() != 3 or K_pool.shape[1] != page_rows or K_pool.shape[2] != D:
+        raise ValueError("pools must be [num_pages, page_rows, D]")
+    if block_table.dim() != 2 or block_table.shape[0] != B * H:
+        raise ValueError("block_table must be [B*H, max_pages]")
+    num_pages = K_pool.shape[0]
+    rc = lib().kvzap_compact_paged(_ptr(K), _ptr(V), _ptr(keep_idx), _ptr(lengths), _ptr(offsets),
+                                   _ptr(block_table), block_table.shape[1], int(page_rows),
+                                   _ptr(K_pool) if num_pages else None,
+                                   _ptr(V_pool) if num_pages else None, num_pages,
+                                   B, H, T, D, _stream(stream))
+    if rc != 0:
+        raise KvzapError(rc, "kvzap_compact_paged")
+
+
+def kvzap_attend_decode_paged(q: torch.Tensor, K_pool: torch.Tensor, V_pool: torch.Tensor,
+                              block_table: torch.Tensor, page_rows: int, lengths: torch.Tensor,
+                              K_ring: Optional[torch.Tensor], V_ring: Optional[torch.Tensor],
+                              seq_pos: Optional[torch.Tensor], window: int, max_rows: int,
+                              scale: float, out: Optional[torch.Tensor] = None,
+                              workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """kvzap_attend_decode over pools bf16 [num_pages, page_rows, D] and a block table int32
+    [B*H, max_pages]."""
+    bf = torch.bfloat16
+    _check(q, bf, "q"); _check(K_pool, bf, "K_pool"); _check(V_pool, bf, "V_pool")
+    _check(block_table, torch.int32, "block_table"); _check(lengths, torch.int32, "lengths")
+    B, HQ, D = q.shape
+    if lengths.dim() != 2 or lengths.shape[0] != B:
+        raise ValueError("lengths must be [B,H]")
+    H = lengths.shape[1]
+    if K_pool.dim() != 3 or K_pool.shape[1:] != (page_rows, D) or K_pool.shape != V_pool.shape:
+        raise ValueError("pools must both be [num_pages, page_rows, D]")
+    if block_table.dim() != 2 or block_table.shape[0] != B * H:
+        raise ValueError("block_table must be [B*H, max_pages]")
+    if window > 0:
+        _check(K_ring, bf, "K_ring"); _check(V_ring, bf, "V_ring")
+        _check(seq_pos, torch.int32, "seq_pos")
+        if tuple(K_ring.shape) != (B, H, window, D) or K_ring.shape != V_ring.shape:
+            raise ValueError("K_ring and V_ring must be [B,H,window,D]")
+    if out is None:
+        out = torch.empty((B, HQ, D), dtype=bf, device=q.device)
+    else:
+        _check(out, bf, "out")
+    ws, ws_bytes = _workspace(
+        kvzap_workspace_bytes(CALL_ATTEND_DECODE, B, int(max_rows), HQ, int(window), H),
+        q.device, workspace)
+    ring = window > 0
+    num_pages = K_pool.shape[0]
+    rc = lib().kvzap_attend_decode_paged(
+        _ptr(q), _ptr(K_pool) if num_pages else None, _ptr(V_pool) if num_pages else None,
+        num_pages, _ptr(block_table), block_table.shape[1], int(page_rows), _ptr(lengths),
+        _ptr(K_ring) if ring else None, _ptr(V_ring) if ring else None,
+        _ptr(seq_pos) if ring else None, int(window), int(max_rows), float(scale), _ptr(out),
+        B, H, HQ, D, _ptr(ws), ws_bytes, _stream(stream))
+    if rc != 0:
+        raise KvzapError(rc, "kvzap_attend_decode_paged")
     return out

@@ -75,6 +75,9 @@ size_t kvzap_workspace_bytes(int which_call, int B, int T, int Dh, int M, int H)
     case KVZAP_CALL_ATTEND_DECODE:   // T = max_rows, Dh = HQ, M = window
       if (check_attend_shape(B, H, Dh, T, M) != KVZAP_OK) return 0;
       return kvzap::attend_workspace_bytes(B, H, Dh, T, M);
+    case KVZAP_CALL_ASSIGN_PAGES:
+      if ((long long)B * H > 65535) return 0;
+      return kvzap::assign_pages_workspace_bytes(B * H);
     case KVZAP_CALL_COMPACT:
     default:
       return 0;
@@ -199,9 +202,90 @@ int kvzap_attend_decode(const void* q, const void* K_rows, const void* V_rows,
     if (!aligned16(p)) return KVZAP_ERR_ALIGN;
   const size_t need = kvzap::attend_workspace_bytes(B, H, HQ, max_rows, window);
   if (!workspace || !aligned256(workspace) || workspace_bytes < need) return KVZAP_ERR_WORKSPACE;
-  return kvzap::launch_attend_decode(q, K_rows, V_rows, total_rows, row_offsets, lengths, K_ring,
-                                     V_ring, seq_pos, window, max_rows, scale, out, B, H, HQ,
-                                     workspace, static_cast<hipStream_t>(stream));
+  return kvzap::launch_attend_decode(q, K_rows, V_rows, total_rows, row_offsets, nullptr, 0, 0, 0,
+                                     lengths, K_ring, V_ring, seq_pos, window, max_rows, scale,
+                                     out, B, H, HQ, workspace, static_cast<hipStream_t>(stream));
+}
+
+namespace {
+bool valid_page_rows(int page_rows) {
+  return page_rows >= 16 && page_rows <= (1 << 20) && (page_rows & (page_rows - 1)) == 0;
+}
+}  // namespace
+
+int kvzap_assign_pages(const int32_t* lengths, int B, int H, int page_rows, int reserve_rows,
+                       const int32_t* free_pages, int n_free, int32_t* block_table,
+                       int max_pages, int32_t* result, void* workspace, size_t workspace_bytes,
+                       void* stream) {
+  if (B <= 0 || H <= 0 || reserve_rows < 0 || n_free < 0 || max_pages <= 0) return KVZAP_ERR_SHAPE;
+  if (!valid_page_rows(page_rows)) return KVZAP_ERR_SHAPE;
+  if ((long long)B * H > 65535) return KVZAP_ERR_UNSUPPORTED;
+  if (!lengths || !block_table || !result || (n_free > 0 && !free_pages)) return KVZAP_ERR_NULL;
+  if (!aligned16(lengths) || !aligned16(free_pages) || !aligned16(block_table) || !aligned16(result))
+    return KVZAP_ERR_ALIGN;
+  if (!workspace || !aligned256(workspace) ||
+      workspace_bytes < kvzap::assign_pages_workspace_bytes(B * H))
+    return KVZAP_ERR_WORKSPACE;
+  return kvzap::launch_assign_pages(lengths, B * H, page_rows, reserve_rows, free_pages, n_free,
+                                    block_table, max_pages, result, workspace,
+                                    static_cast<hipStream_t>(stream));
+}
+
+int kvzap_compact_paged(const void* K, const void* V, const int32_t* keep_idx,
+                        const int32_t* lengths, const int64_t* offsets,
+                        const int32_t* block_table, int max_pages, int page_rows, void* K_pool,
+                        void* V_pool, int num_pages, int B, int H, int T, int D, void* stream) {
+  if (B <= 0 || H <= 0 || T <= 0 || D <= 0 || max_pages <= 0 || num_pages < 0) return KVZAP_ERR_SHAPE;
+  if (!valid_page_rows(page_rows)) return KVZAP_ERR_SHAPE;
+  if ((D != 64 && D != 128 && D != 256) || (long long)B * H > 65535) return KVZAP_ERR_UNSUPPORTED;
+  if (!K || !V || !keep_idx || !lengths || !offsets || !block_table) return KVZAP_ERR_NULL;
+  if (num_pages > 0 && (!K_pool || !V_pool)) return KVZAP_ERR_NULL;
+  const void* ptrs[] = {K, V, keep_idx, lengths, offsets, block_table, K_pool, V_pool};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return KVZAP_ERR_ALIGN;
+  {  // the gather is not an in-place operation
+    const size_t in_bytes = (size_t)B * H * T * D * 2;
+    const size_t pool_bytes = (size_t)num_pages * page_rows * D * 2;
+    auto overlaps = [](const void* a, size_t na, const void* b, size_t nb) {
+      const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+      return na > 0 && nb > 0 && x < y + nb && y < x + na;
+    };
+    if (overlaps(K, in_bytes, K_pool, pool_bytes) || overlaps(V, in_bytes, K_pool, pool_bytes) ||
+        overlaps(K, in_bytes, V_pool, pool_bytes) || overlaps(V, in_bytes, V_pool, pool_bytes) ||
+        overlaps(K_pool, pool_bytes, V_pool, pool_bytes))
+      return KVZAP_ERR_SHAPE;
+  }
+  if (num_pages == 0) return KVZAP_OK;                   // nothing can be written
+  return kvzap::launch_compact_paged(K, V, keep_idx, lengths, offsets, block_table, max_pages,
+                                     page_rows, K_pool, V_pool, num_pages, B * H, T, D,
+                                     static_cast<hipStream_t>(stream));
+}
+
+int kvzap_attend_decode_paged(const void* q, const void* K_pool, const void* V_pool,
+                              int num_pages, const int32_t* block_table, int max_pages,
+                              int page_rows, const int32_t* lengths, const void* K_ring,
+                              const void* V_ring, const int32_t* seq_pos, int window,
+                              int max_rows, float scale, void* out, int B, int H, int HQ, int D,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+  if (D <= 0 || num_pages < 0 || max_pages <= 0) return KVZAP_ERR_SHAPE;
+  if (!valid_page_rows(page_rows)) return KVZAP_ERR_SHAPE;
+  const int rc = check_attend_shape(B, H, HQ, max_rows, window);
+  if (rc != KVZAP_OK) return rc;
+  if (D != 128) return KVZAP_ERR_UNSUPPORTED;
+  if (scale != scale) return KVZAP_ERR_SHAPE;
+  if ((long long)max_pages * page_rows > INT_MAX) return KVZAP_ERR_SHAPE;
+  if (!q || !block_table || !lengths || !out) return KVZAP_ERR_NULL;
+  if (num_pages > 0 && (!K_pool || !V_pool)) return KVZAP_ERR_NULL;
+  if (window > 0 && (!K_ring || !V_ring || !seq_pos)) return KVZAP_ERR_NULL;
+  const void* ptrs[] = {q, K_pool, V_pool, block_table, lengths, K_ring, V_ring, seq_pos, out};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return KVZAP_ERR_ALIGN;
+  const size_t need = kvzap::attend_workspace_bytes(B, H, HQ, max_rows, window);
+  if (!workspace || !aligned256(workspace) || workspace_bytes < need) return KVZAP_ERR_WORKSPACE;
+  return kvzap::launch_attend_decode(q, K_pool, V_pool, 0, nullptr, block_table, max_pages,
+                                     page_rows, num_pages, lengths, K_ring, V_ring, seq_pos, window,
+                                     max_rows, scale, out, B, H, HQ, workspace,
+                                     static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

@@ -51,16 +51,19 @@ struct HeadExtent {
   int n_p, n_r;
 };
 
+// Contiguous layout: head bh owns rows row_offsets[bh] .. of a store of cap_rows rows.
+// Paged layout (row_offsets == nullptr): its rows are addressed through its block table and
+// cap_rows is what the table can address (max_pages * page_rows, 0 for an empty pool).
 __device__ __forceinline__ HeadExtent head_extent(const int64_t* row_offsets,
                                                   const int32_t* lengths,
                                                   const int32_t* seq_pos, int window,
-                                                  int64_t total_rows, int bh, int b) {
+                                                  int64_t cap_rows, int bh, int b) {
   HeadExtent e;
-  e.off = row_offsets[bh];
+  e.off = row_offsets ? row_offsets[bh] : 0;
   int64_t n = lengths[bh];
-  if (e.off < 0 || e.off > total_rows) { e.off = 0; n = 0; }
+  if (e.off < 0 || e.off > cap_rows) { e.off = 0; n = 0; }
   if (n < 0) n = 0;
-  if (n > total_rows - e.off) n = total_rows - e.off;
+  if (n > cap_rows - e.off) n = cap_rows - e.off;
   e.n_p = (int)n;
   int r = 0;
   if (window > 0) {
@@ -78,34 +81,70 @@ struct Chunk {
   u32x4 v[8];      // [row group j]
 };
 
+// Where the rows of one head live.
+struct Source {
+  const u32x4* K;            // packed rows of this head (contiguous) or the page pool (paged)
+  const u32x4* V;
+  const u32x4* Kr;           // ring rows of this head
+  const u32x4* Vr;
+  const int32_t* pages;      // paged: this head's block-table row
+  int log_page, max_pages, num_pages;
+  int n_p, n_r;
+};
+
+constexpr int kRowVec = kD * 2 / 16;   // 16-byte pieces per row
+
+// Offset (in 16-byte pieces) of packed row r of the head from Source::K / Source::V.  Paged:
+// row r is row r % page_rows of page pages[r / page_rows]; a table entry outside the pool is
+// clamped into it, so nothing outside the pool is ever read.
+template <bool kPaged>
+__device__ __forceinline__ size_t prefix_offset(const Source& s, int r) {
+  if (!kPaged) return (size_t)r * kRowVec;
+  int slot = r >> s.log_page;
+  slot = slot < s.max_pages - 1 ? slot : s.max_pages - 1;
+  int page = s.pages[slot];
+  page = page < 0 ? 0 : (page < s.num_pages ? page : s.num_pages - 1);
+  return (((size_t)page << s.log_page) + (size_t)(r & ((1 << s.log_page) - 1))) * kRowVec;
+}
+
 // Loads chunk `vc` of the head's chunk list (prefix chunks, then ring chunks).  Rows past
 // the end of the segment are read from its last row (their weights are forced to zero).
-__device__ __forceinline__ void load_chunk(Chunk& c, int vc, int cp, const HeadExtent& e,
-                                           const u32x4* Kp, const u32x4* Vp,
-                                           const u32x4* Kr, const u32x4* Vr, int li, int lg,
-                                           int& row0, int& n_seg) {
+// A page holds a multiple of 16 rows, so each 16-row half of a chunk is contiguous.
+template <bool kPaged>
+__device__ __forceinline__ void load_chunk(Chunk& c, int vc, int cp, const Source& s, int li,
+                                           int lg, int& row0, int& n_seg) {
   const bool ring = vc >= cp;
-  const u32x4* Kb = ring ? Kr : Kp;
-  const u32x4* Vb = ring ? Vr : Vp;
-  n_seg = ring ? e.n_r : e.n_p;
+  const u32x4* Kb = ring ? s.Kr : s.K;
+  const u32x4* Vb = ring ? s.Vr : s.V;
+  n_seg = ring ? s.n_r : s.n_p;
   row0 = (ring ? vc - cp : vc) * kChunkRows;
-  constexpr int kRowVec = kD * 2 / 16;   // 16 u32x4 per row
+  const int klocal = 4 * (li & 3) + (li >> 2);          // row of this lane inside a 16-row set
   if (row0 + kChunkRows <= n_seg) {
-    const u32x4* kp = Kb + (size_t)(row0 + 4 * (li & 3) + (li >> 2)) * kRowVec + lg;
+    size_t half[2];
+    if (kPaged && !ring) {
+      half[0] = prefix_offset<kPaged>(s, row0);
+      half[1] = prefix_offset<kPaged>(s, row0 + 16);
+    } else {
+      half[0] = (size_t)row0 * kRowVec;
+      half[1] = half[0] + 16 * kRowVec;
+    }
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int t = 0; t < 2; ++t) {
+      const u32x4* kp = Kb + half[t] + klocal * kRowVec + lg;
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) c.k[t][kk] = kp[t * 16 * kRowVec + kk * 4];
-    const u32x4* vp = Vb + (size_t)(row0 + lg) * kRowVec + li;
+      for (int kk = 0; kk < 4; ++kk) c.k[t][kk] = kp[kk * 4];
+    }
 #pragma unroll
-    for (int j = 0; j < 8; ++j) c.v[j] = vp[j * 4 * kRowVec];
+    for (int j = 0; j < 8; ++j)
+      c.v[j] = Vb[half[j >> 2] + (size_t)(4 * (j & 3) + lg) * kRowVec + li];
   } else {
     const int last = n_seg - 1;
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
-      int r = row0 + 16 * t + 4 * (li & 3) + (li >> 2);
+      int r = row0 + 16 * t + klocal;
       r = r < last ? r : last;
-      const u32x4* kp = Kb + (size_t)r * kRowVec + lg;
+      const size_t o = (kPaged && !ring) ? prefix_offset<kPaged>(s, r) : (size_t)r * kRowVec;
+      const u32x4* kp = Kb + o + lg;
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) c.k[t][kk] = kp[kk * 4];
     }
@@ -113,7 +152,8 @@ __device__ __forceinline__ void load_chunk(Chunk& c, int vc, int cp, const HeadE
     for (int j = 0; j < 8; ++j) {
       int r = row0 + 4 * j + lg;
       r = r < last ? r : last;
-      c.v[j] = Vb[(size_t)r * kRowVec + li];
+      const size_t o = (kPaged && !ring) ? prefix_offset<kPaged>(s, r) : (size_t)r * kRowVec;
+      c.v[j] = Vb[o + li];
     }
   }
 }
@@ -183,14 +223,18 @@ __device__ __forceinline__ void consume_chunk(const Chunk& c, const u32x4 (&qb)[
 }
 
 // grid (NS, B*H), 64 threads.  part: [B*H][NS][G][128] fp32, ml: [B*H][NS][G][2] fp32.
+// Contiguous layout: K_rows/V_rows are the row store, row_offsets the heads' first rows.
+// Paged layout: K_rows/V_rows are the page pool, row_offsets is null, block_table given.
+template <bool kPaged>
 __global__ __launch_bounds__(64, 2) void attend_partial_kernel(
-    const u32x4* q, const u32x4* K_rows, const u32x4* V_rows, int64_t total_rows,
-    const int64_t* row_offsets, const int32_t* lengths, const u32x4* K_ring,
-    const u32x4* V_ring, const int32_t* seq_pos, int window, float cscale, int H, int G,
-    int spc, float* part, float* ml) {
+    const u32x4* q, const u32x4* K_rows, const u32x4* V_rows, int64_t cap_rows,
+    const int64_t* row_offsets, const int32_t* block_table, int max_pages, int log_page,
+    int num_pages, const int32_t* lengths, const u32x4* K_ring, const u32x4* V_ring,
+    const int32_t* seq_pos, int window, float cscale, int H, int G, int spc, float* part,
+    float* ml) {
   const int bh = blockIdx.y, split = blockIdx.x, NS = gridDim.x;
   const int b = bh / H;
-  const HeadExtent e = head_extent(row_offsets, lengths, seq_pos, window, total_rows, bh, b);
+  const HeadExtent e = head_extent(row_offsets, lengths, seq_pos, window, cap_rows, bh, b);
   const int cp = chunks_of(e.n_p), ct = cp + chunks_of(e.n_r);
   const int c0 = split * spc;
   // the last split runs to the end of the list, so a head longer than the host's bound
@@ -199,11 +243,14 @@ __global__ __launch_bounds__(64, 2) void attend_partial_kernel(
   if (c0 >= c1) return;
 
   const int lane = threadIdx.x, li = lane & 15, lg = lane >> 4;
-  constexpr int kRowVec = kD * 2 / 16;
-  const u32x4* Kp = K_rows + (size_t)e.off * kRowVec;
-  const u32x4* Vp = V_rows + (size_t)e.off * kRowVec;
-  const u32x4* Kr = K_ring + (size_t)bh * (window > 0 ? window : 0) * kRowVec;
-  const u32x4* Vr = V_ring + (size_t)bh * (window > 0 ? window : 0) * kRowVec;
+  Source src;
+  src.K = K_rows + (size_t)e.off * kRowVec;
+  src.V = V_rows + (size_t)e.off * kRowVec;
+  src.Kr = K_ring + (size_t)bh * (window > 0 ? window : 0) * kRowVec;
+  src.Vr = V_ring + (size_t)bh * (window > 0 ? window : 0) * kRowVec;
+  src.pages = kPaged ? block_table + (size_t)bh * max_pages : nullptr;
+  src.log_page = log_page; src.max_pages = max_pages; src.num_pages = num_pages;
+  src.n_p = e.n_p; src.n_r = e.n_r;
 
   // q as the B operand: lane (g = li, kg = lg), k-step kk: q[g][32kk + 8kg ..+8]
   u32x4 qb[4];
@@ -224,17 +271,17 @@ __global__ __launch_bounds__(64, 2) void attend_partial_kernel(
   // compiler's wait counts let the loads of one buffer fly while the other is consumed.
   Chunk ca, cb;
   int row0a, nsega, row0b, nsegb;
-  load_chunk(ca, c0, cp, e, Kp, Vp, Kr, Vr, li, lg, row0a, nsega);
+  load_chunk<kPaged>(ca, c0, cp, src, li, lg, row0a, nsega);
   int vc = c0;
   while (vc + 2 < c1) {
-    load_chunk(cb, vc + 1, cp, e, Kp, Vp, Kr, Vr, li, lg, row0b, nsegb);
+    load_chunk<kPaged>(cb, vc + 1, cp, src, li, lg, row0b, nsegb);
     consume_chunk(ca, qb, acc, row0a, nsega, lg, cscale);
-    load_chunk(ca, vc + 2, cp, e, Kp, Vp, Kr, Vr, li, lg, row0a, nsega);
+    load_chunk<kPaged>(ca, vc + 2, cp, src, li, lg, row0a, nsega);
     consume_chunk(cb, qb, acc, row0b, nsegb, lg, cscale);
     vc += 2;
   }
   if (vc + 1 < c1) {
-    load_chunk(cb, vc + 1, cp, e, Kp, Vp, Kr, Vr, li, lg, row0b, nsegb);
+    load_chunk<kPaged>(cb, vc + 1, cp, src, li, lg, row0b, nsegb);
     consume_chunk(ca, qb, acc, row0a, nsega, lg, cscale);
     consume_chunk(cb, qb, acc, row0b, nsegb, lg, cscale);
   } else {
@@ -344,6 +391,7 @@ size_t attend_workspace_bytes(int B, int H, int HQ, int max_rows, int window) {
 
 int launch_attend_decode(const void* q, const void* K_rows, const void* V_rows,
                          int64_t total_rows, const int64_t* row_offsets,
+                         const int32_t* block_table, int max_pages, int page_rows, int num_pages,
                          const int32_t* lengths, const void* K_ring, const void* V_ring,
                          const int32_t* seq_pos, int window, int max_rows, float scale,
                          void* out, int B, int H, int HQ, void* workspace,
@@ -356,15 +404,28 @@ int launch_attend_decode(const void* q, const void* K_rows, const void* V_rows,
   float* ml = reinterpret_cast<float*>(static_cast<char*>(workspace) +
                                        align_up(slots * kD * sizeof(float), 256));
   const float cscale = scale * 1.4426950408889634f;
-  hipLaunchKernelGGL(attend_partial_kernel, dim3(NS, BH), dim3(64), 0, stream,
-                     static_cast<const u32x4*>(q), static_cast<const u32x4*>(K_rows),
-                     static_cast<const u32x4*>(V_rows), total_rows, row_offsets, lengths,
-                     static_cast<const u32x4*>(K_ring), static_cast<const u32x4*>(V_ring),
-                     seq_pos, window, cscale, H, G, spc, part, ml);
+  const bool paged = block_table != nullptr;
+  int log_page = 0;
+  while ((1 << log_page) < page_rows) ++log_page;
+  // rows a head can address: the whole store, or what its block-table row covers
+  const int64_t cap_rows = paged ? (num_pages > 0 ? (int64_t)max_pages * page_rows : 0) : total_rows;
+  const auto* qv = static_cast<const u32x4*>(q);
+  const auto* kv = static_cast<const u32x4*>(K_rows);
+  const auto* vv = static_cast<const u32x4*>(V_rows);
+  const auto* kr = static_cast<const u32x4*>(K_ring);
+  const auto* vr = static_cast<const u32x4*>(V_ring);
+  if (paged)
+    hipLaunchKernelGGL(attend_partial_kernel<true>, dim3(NS, BH), dim3(64), 0, stream, qv, kv, vv,
+                       cap_rows, nullptr, block_table, max_pages, log_page, num_pages, lengths, kr,
+                       vr, seq_pos, window, cscale, H, G, spc, part, ml);
+  else
+    hipLaunchKernelGGL(attend_partial_kernel<false>, dim3(NS, BH), dim3(64), 0, stream, qv, kv, vv,
+                       cap_rows, row_offsets, nullptr, 0, 0, 0, lengths, kr, vr, seq_pos, window,
+                       cscale, H, G, spc, part, ml);
   if (hipGetLastError() != hipSuccess) return KVZAP_ERR_RUNTIME;
   hipLaunchKernelGGL(attend_combine_kernel, dim3(BH * G), dim3(256), 0, stream, part, ml,
-                     total_rows, row_offsets, lengths, seq_pos, window, H, G, NS, spc,
-                     static_cast<unsigned short*>(out));
+                     cap_rows, paged ? nullptr : row_offsets, lengths, seq_pos, window, H, G, NS,
+                     spc, static_cast<unsigned short*>(out));
   if (hipGetLastError() != hipSuccess) return KVZAP_ERR_RUNTIME;
   return KVZAP_OK;
 }

@@ -66,10 +66,19 @@ size_t decode_workspace_bytes(int B, int Dh, int M, int H);
 
 int launch_attend_decode(const void* q, const void* K_rows, const void* V_rows,
                          int64_t total_rows, const int64_t* row_offsets,
+                         const int32_t* block_table, int max_pages, int page_rows, int num_pages,
                          const int32_t* lengths, const void* K_ring, const void* V_ring,
                          const int32_t* seq_pos, int window, int max_rows, float scale,
                          void* out, int B, int H, int HQ, void* workspace,
                          hipStream_t stream);
+int launch_assign_pages(const int32_t* lengths, int BH, int page_rows, int reserve_rows,
+                        const int32_t* free_pages, int n_free, int32_t* block_table,
+                        int max_pages, int32_t* result, void* workspace, hipStream_t stream);
+size_t assign_pages_workspace_bytes(int BH);
+int launch_compact_paged(const void* K, const void* V, const int32_t* keep_idx,
+                         const int32_t* lengths, const int64_t* offsets,
+                         const int32_t* block_table, int max_pages, int page_rows, void* K_pool,
+                         void* V_pool, int num_pages, int BH, int T, int D, hipStream_t stream);
 size_t attend_workspace_bytes(int B, int H, int HQ, int max_rows, int window);
 
 }  // namespace kvzap
