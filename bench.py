@@ -181,9 +181,24 @@ def bench_attend(wl, args) -> int:
     off = torch.zeros(B * H, dtype=torch.int64)
     off[1:] = torch.cumsum(lens.reshape(-1).to(torch.int64), 0)[:-1]
     total = int(lens.sum())
+    P = args.page_rows
     layers = []
+    table = None
+    if P:       # every head's pages scattered over the pool by a random permutation
+        pages_per_head = (lens.reshape(-1).to(torch.int64) + P - 1) // P
+        num_pages = int(pages_per_head.sum())
+        perm = torch.randperm(num_pages, generator=g).to(torch.int32)
+        table = torch.full((B * H, int(pages_per_head.max())), -1, dtype=torch.int32)
+        pos = 0
+        for i, c in enumerate(pages_per_head.tolist()):
+            table[i, :c] = perm[pos:pos + c]
+            pos += c
+        table = table.to(dev)
+        total = num_pages * P
     for l in range(L):
         q, Kr, Vr, Kg, Vg = synth.make_attend_inputs(B, H, HQ, D, total, w, wl.seed + l, dev)
+        if P:
+            Kr, Vr = Kr.view(-1, P, D), Vr.view(-1, P, D)
         layers.append((q, Kr, Vr, Kg, Vg))
     lens_d, off_d = lens.to(dev), off.to(dev)
     sp = torch.full((B,), 40000, dtype=torch.int32, device=dev)
@@ -192,10 +207,16 @@ def bench_attend(wl, args) -> int:
                      dtype=torch.uint8, device=dev)
     scale = D ** -0.5
 
+    def attend(q, Kr, Vr, Kg, Vg, out_):
+        if P:
+            return binding.kvzap_attend_decode_paged(q, Kr, Vr, table, P, lens_d, Kg, Vg, sp, w, hi,
+                                                     scale, out=out_, workspace=ws)
+        return binding.kvzap_attend_decode(q, Kr, Vr, off_d, lens_d, Kg, Vg, sp, w, hi, scale,
+                                           out=out_, workspace=ws)
+
     def step():
         for q, Kr, Vr, Kg, Vg in layers:
-            binding.kvzap_attend_decode(q, Kr, Vr, off_d, lens_d, Kg, Vg, sp, w, hi, scale,
-                                        out=out, workspace=ws)
+            attend(q, Kr, Vr, Kg, Vg, out)
 
     for _ in range(warm):
         step()
@@ -210,7 +231,7 @@ def bench_attend(wl, args) -> int:
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / steps
     ms_call = ev0.elapsed_time(ev1) / (steps * L)          # both kernels of one call
-    rows = total + B * H * w
+    rows = int(lens.sum()) + B * H * w
     bytes_call = rows * 2 * D * 2                          # K and V rows, read once
     achieved = bytes_call / (ms_call * 1e-3) / 1e9
 
@@ -221,14 +242,18 @@ def bench_attend(wl, args) -> int:
     caches = []
     for h in range(H):
         o, n = int(off[h]), int(lens[0, h])
-        caches.append((synth.f64(torch.cat([Kr[o:o + n], Kg[0, h]])),
-                       synth.f64(torch.cat([Vr[o:o + n], Vg[0, h]]))))
+        if P:       # rows of head (0,h) in block-table order
+            pg = table[h, :(n + P - 1) // P].long()
+            kh, vh = Kr[pg].reshape(-1, D)[:n], Vr[pg].reshape(-1, D)[:n]
+        else:
+            kh, vh = Kr[o:o + n], Vr[o:o + n]
+        caches.append((synth.f64(torch.cat([kh, Kg[0, h]])), synth.f64(torch.cat([vh, Vg[0, h]]))))
     q0 = synth.f64(q[:1])
     c0 = time.perf_counter()
     ref = O.attend_decode(q0, [caches], scale)
     c1 = time.perf_counter()
     got = out  # last layer's output; recompute layer 0 for the check
-    got = binding.kvzap_attend_decode(q, Kr, Vr, off_d, lens_d, Kg, Vg, sp, w, hi, scale)
+    got = attend(q, Kr, Vr, Kg, Vg, None)
     err = float(np.abs(got[:1].to(torch.float64).cpu().numpy() - ref).max())
     sample_rows = sum(c[0].shape[0] for c in caches)
     try:
@@ -243,12 +268,13 @@ def bench_attend(wl, args) -> int:
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name + "+attend", "layers": L, "batch": B, "kv_heads": H,
                    "query_heads": HQ, "head_dim": D, "window": w,
-                   "rows_per_head": [lo, hi], "cache_rows_per_layer": rows},
+                   "rows_per_head": [lo, hi], "cache_rows_per_layer": rows,
+                   "layout": f"paged, {P} rows per page, pages shuffled" if P else "contiguous slabs"},
         "ms_per_call": ms_call,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                      "frac": achieved / PEAK_HBM_GBS,
                      "traffic": (MEASURED_HBM_TRAFFIC.get((wl.name + "+attend", "attend_partial_kernel"))
-                                 if (lo, hi, HQ, B) == (4096, 32768, 32, 64) else None),
+                                 if (lo, hi, HQ, B, P) == (4096, 32768, 32, 64, 0) else None),
                      "kernel": "attend_partial_kernel (+ attend_combine_kernel in the same interval)",
                      "bytes_per_launch": bytes_call},
         "cpu_baseline": {"value": sample_rows / (c1 - c0), "unit": "cache rows/s",
@@ -275,6 +301,10 @@ def main() -> int:
                          "default is one stream, which keeps per-kernel timings clean")
     ap.add_argument("--decode-cache-rows", type=int, nargs=2, default=[4096, 32768],
                     help="decode workload: range of rows already kept per (sequence, head)")
+    ap.add_argument("--page-rows", type=int, default=0,
+                    help="0 (default): packed contiguous output; a power of two >= 16: paged output "
+                         "(kvzap_assign_pages + kvzap_compact_paged) and, for --stage attend, the "
+                         "paged attention over a shuffled page pool")
     ap.add_argument("--graph", action="store_true",
                     help="decode workload: also time the step replayed from a HIP graph")
     ap.add_argument("--stage", default="evict", choices=["evict", "attend"],
@@ -301,6 +331,7 @@ def main() -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     B, T, H, D, Dh, M = wl.B, wl.T, wl.H, wl.D, wl.Dh, wl.M
+    P = args.page_rows
 
     # ---- resident inputs and preallocated outputs for every layer ----
     layers = []
@@ -315,8 +346,16 @@ def main() -> int:
             idx=torch.empty(cap, dtype=torch.int32, device=dev),
             n=torch.empty((B, H), dtype=torch.int32, device=dev),
             off=torch.empty(B * H + 1, dtype=torch.int64, device=dev),
-            K_out=torch.empty((cap, D), dtype=torch.bfloat16, device=dev),
-            V_out=torch.empty((cap, D), dtype=torch.bfloat16, device=dev)))
+            K_out=None if P else torch.empty((cap, D), dtype=torch.bfloat16, device=dev),
+            V_out=None if P else torch.empty((cap, D), dtype=torch.bfloat16, device=dev)))
+        if P:       # paged layout: room for 55 % of the rows (the configs keep 25-50 %)
+            num_pages = int(cap * 0.55) // P + B * H
+            layers[-1].update(
+                K_pool=torch.empty((num_pages, P, D), dtype=torch.bfloat16, device=dev),
+                V_pool=torch.empty((num_pages, P, D), dtype=torch.bfloat16, device=dev),
+                free=torch.arange(num_pages, dtype=torch.int32, device=dev),
+                table=torch.empty((B * H, T // P + 1), dtype=torch.int32, device=dev),
+                pages=torch.zeros(4, dtype=torch.int32, device=dev))
     ws = torch.empty(max(binding.kvzap_workspace_bytes(binding.CALL_MASK, B, T, 0, 0, H), 256),
                      dtype=torch.uint8, device=dev)
     ws_score = torch.empty(max(binding.kvzap_workspace_bytes(binding.CALL_SCORE, B, T, Dh, M, H), 256),
@@ -343,9 +382,21 @@ def main() -> int:
     def mask(ly):
         binding.kvzap_mask(ly["scores"], tau, wl.window, None, ly["idx"], ly["n"], ly["off"], ws)
 
+    ws_pages = torch.empty(max(binding.kvzap_workspace_bytes(binding.CALL_ASSIGN_PAGES, B, 1, 0, 0, H), 256),
+                           dtype=torch.uint8, device=dev)
+
+    def assign(ly):
+        binding.kvzap_assign_pages(ly["n"], P, ly["free"], ly["table"].shape[1], 0, ly["table"],
+                                   ly["pages"], ws_pages)
+
     def compact(ly):
-        binding.kvzap_compact(ly["K"], ly["V"], ly["idx"], ly["n"], ly["off"], ly["K_out"],
-                              ly["V_out"], B * H * T)
+        if P:
+            assign(ly)
+            binding.kvzap_compact_paged(ly["K"], ly["V"], ly["idx"], ly["n"], ly["off"], ly["table"],
+                                        P, ly["K_pool"], ly["V_pool"])
+        else:
+            binding.kvzap_compact(ly["K"], ly["V"], ly["idx"], ly["n"], ly["off"], ly["K_out"],
+                                  ly["V_out"], B * H * T)
 
     # Layers are independent in the prune step, so the scorer of layer l+1 may run while the
     # HBM-bound mask + compact of layer l run on a second stream (--two-streams, default priority).
@@ -405,6 +456,13 @@ def main() -> int:
 
     mask_ms = time_stage(mask)
     compact_ms = time_stage(compact)
+    assign_ms = None
+    if P:
+        if any(int(ly["pages"][1]) != 0 for ly in layers):
+            print("bench.py: the page pool was too small for this workload", file=sys.stderr)
+            return 1
+        assign_ms = time_stage(assign)
+        compact_ms -= assign_ms                   # the gather alone, for the HBM figure
     kept_rows = float(np.mean([int(ly["off"][-1]) for ly in layers]))
     kept_fraction = kept_rows / (B * H * T)
 
@@ -426,10 +484,10 @@ def main() -> int:
         score_flops if M else B * T * (2 * Dh + 4 * H))
     if L == wl.L:
         roofline["traffic"] = MEASURED_HBM_TRAFFIC.get((wl.name, roofline["kernel"]))
-        compact_traffic = MEASURED_HBM_TRAFFIC.get((wl.name, "compact_kernel"))
+        compact_traffic = None if P else MEASURED_HBM_TRAFFIC.get((wl.name, "compact_kernel"))
     else:
         compact_traffic = None
-    compact_roof = {"kernel": "compact_kernel", "bound": "hbm",
+    compact_roof = {"kernel": "compact_paged_kernel" if P else "compact_kernel", "bound": "hbm",
                     "achieved": compact_bytes / (compact_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
                     "unit": "GB/s", "traffic": compact_traffic, "avg_launch_ms": compact_ms,
                     "algorithmic_bytes_per_launch": compact_bytes}
@@ -444,11 +502,13 @@ def main() -> int:
                    "mlp_width": M, "kv_heads": H, "head_dim": D, "window": wl.window,
                    "keep_fraction_target": wl.keep_fraction, "tau": tau,
                    "kept_fraction_measured": kept_fraction, "scorer": wl.scorer,
+                   "output_layout": f"paged, {P} rows per page" if P else "packed contiguous",
                    "generator": f"torch {torch.__version__} cuda philox, seeds per layer"},
         "roofline": roofline,
         "roofline_compact": compact_roof,
         "stages_ms_per_layer": {"score": score_ms, "mask": mask_ms, "compact": compact_ms,
-                                "sum": score_ms + mask_ms + compact_ms,
+                                "assign_pages": assign_ms,
+                                "sum": score_ms + mask_ms + compact_ms + (assign_ms or 0.0),
                                 "wall": ms_per_step / L,
                                 "streams": 2 if args.two_streams else 1,
                                 "note": "score timed inside the step; mask and compact timed "

@@ -61,13 +61,13 @@ __global__ __launch_bounds__(kScanThreads) void assign_scan_kernel(
   }
 }
 
-// grid B*H: block bh writes its block-table row (-1 beyond its pages)
+// grid (tiles, B*H): the blocks of head bh write its block-table row (-1 beyond its pages)
 __global__ __launch_bounds__(256) void assign_fill_kernel(
     const int32_t* __restrict__ start, const int32_t* __restrict__ free_pages,
     int32_t* __restrict__ block_table, int max_pages) {
-  const int bh = blockIdx.x;
+  const int bh = blockIdx.y;
   const int s = start[bh], c = start[bh + 1] - s;
-  for (int i = threadIdx.x; i < max_pages; i += blockDim.x)
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < max_pages; i += gridDim.x * blockDim.x)
     block_table[(size_t)bh * max_pages + i] = i < c ? free_pages[s + i] : -1;
 }
 
@@ -119,7 +119,9 @@ int launch_assign_pages(const int32_t* lengths, int BH, int page_rows, int reser
   assign_scan_kernel<<<1, kScanThreads, 0, stream>>>(lengths, BH, log_page, reserve_rows, n_free,
                                                      max_pages, start, result);
   if (hipGetLastError() != hipSuccess) return KVZAP_ERR_RUNTIME;
-  assign_fill_kernel<<<BH, 256, 0, stream>>>(start, free_pages, block_table, max_pages);
+  int tiles = (max_pages + 255) / 256;
+  tiles = tiles < 64 ? tiles : 64;
+  assign_fill_kernel<<<dim3(tiles, BH), 256, 0, stream>>>(start, free_pages, block_table, max_pages);
   return hipGetLastError() == hipSuccess ? KVZAP_OK : KVZAP_ERR_RUNTIME;
 }
 
