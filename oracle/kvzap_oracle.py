@@ -421,3 +421,28 @@ def gather_from_pages(pool: np.ndarray, table_row: np.ndarray, n_rows: int,
     for j in range(n_rows):
         out[j] = pool[table_row[j // page_rows], j % page_rows]
     return out
+
+
+def extend_pages(lengths: np.ndarray, page_counts: np.ndarray, table: np.ndarray,
+                 page_rows: int, free_pages: Sequence[int], reserve_rows: int = 0):
+    """Bring every head up to pages_needed(length, reserve) pages by appending the next
+    entries of the free list behind the page_counts[bh] entries it already owns, heads in
+    (sequence, head) order.  Returns (new table, new page_counts, pages_used, ok); when the
+    list is too short or a head would exceed the table width, nothing changes and ok is
+    False.  assign_pages is the case page_counts == 0 on an all -1 table."""
+    n = np.asarray(lengths, dtype=np.int64).reshape(-1)
+    have = np.asarray(page_counts, dtype=np.int64).reshape(-1)
+    table = np.array(table, dtype=np.int32, copy=True)
+    max_pages = table.shape[1]
+    add = [max(0, pages_needed(int(n[i]), page_rows, reserve_rows) - int(have[i]))
+           for i in range(n.size)]
+    if sum(add) > len(free_pages) or any(int(have[i]) + add[i] > max_pages for i in range(n.size)):
+        return table, np.array(have, dtype=np.int32), 0, False
+    pos = 0
+    new_counts = np.array(have, dtype=np.int32)
+    for bh, c in enumerate(add):
+        for i in range(c):
+            table[bh, int(have[bh]) + i] = int(free_pages[pos])
+            pos += 1
+        new_counts[bh] += c
+    return table, new_counts, pos, True

@@ -60,3 +60,42 @@ def test_paged_round_trip_of_a_pruned_cache(P):
     # pages not assigned stay untouched
     untouched = sorted(set(range(n_pages + 5)) - {int(x) for x in table.reshape(-1) if x >= 0})
     assert (pool[untouched] == 0).all()
+
+
+def test_extend_is_assign_when_nothing_is_owned():
+    rng = np.random.default_rng(5)
+    lengths = rng.integers(0, 300, (3, 4))
+    free = list(rng.permutation(200))
+    t0 = np.full((12, 24), -1, np.int32)
+    t, counts, used, ok = O.extend_pages(lengths, np.zeros(12, np.int32), t0, 16, free)
+    ta, useda, oka = O.assign_pages(lengths, 16, free, 24)
+    assert ok and oka and used == useda
+    assert np.array_equal(t, ta)
+    assert counts.tolist() == [O.pages_needed(int(x), 16) for x in lengths.reshape(-1)]
+
+
+def test_extend_appends_only_what_is_missing():
+    lengths = np.array([[16, 17, 40]])
+    counts = np.array([1, 1, 5], np.int32)                  # the last head owns more than it needs
+    table = np.array([[7, -1, -1, -1, -1, -1], [8, -1, -1, -1, -1, -1], [1, 2, 3, 4, 5, -1]], np.int32)
+    t, c, used, ok = O.extend_pages(lengths, counts, table, 16, [50, 51, 52], reserve_rows=1)
+    # 16+1 -> 2 pages, 17+1 -> 2 pages, 40+1 -> 3 pages (already 5)
+    assert ok and used == 2 and c.tolist() == [2, 2, 5]
+    assert t.tolist() == [[7, 50, -1, -1, -1, -1], [8, 51, -1, -1, -1, -1], [1, 2, 3, 4, 5, -1]]
+    # growing token by token with reserve 1 never leaves a head without room for the next row
+    counts = np.zeros(1, np.int32); table = np.full((1, 10), -1, np.int32); free = list(range(100, 110))
+    used_total = 0
+    for n in range(0, 100):
+        table, counts, used, ok = O.extend_pages(np.array([[n]]), counts, table, 16, free[used_total:], 1)
+        assert ok
+        used_total += used
+        assert counts[0] * 16 >= n + 1
+    assert used_total == 7 and table[0, :7].tolist() == free[:7]
+
+
+def test_extend_fails_atomically():
+    table = np.array([[3, -1]], np.int32)
+    t, c, used, ok = O.extend_pages(np.array([[40]]), np.array([1], np.int32), table, 16, [9, 10])
+    assert not ok and used == 0 and np.array_equal(t, table) and c.tolist() == [1]   # needs 3 > width 2
+    t, c, used, ok = O.extend_pages(np.array([[30]]), np.array([1], np.int32), table, 16, [])
+    assert not ok and np.array_equal(t, table)
