@@ -262,12 +262,28 @@ int kvzap_attend_decode(const void* q, const void* K_rows, const void* V_rows,
  * max_pages; on failure every table entry is -1 and nothing is consumed.  The library
  * never reads the pool here and keeps no allocator state: the caller removes the first
  * result[0] entries from its free list.
- *   lengths int32 [B,H]; free_pages int32 [n_free]; block_table fully overwritten.
+ *   lengths int32 [B,H]; free_pages int32 [n_free] (4-byte alignment is enough, so the
+ *   unconsumed tail of a list can be passed on); block_table fully overwritten.
  *   workspace: kvzap_workspace_bytes(KVZAP_CALL_ASSIGN_PAGES, B, 1, 0, 0, H).
  */
 int kvzap_assign_pages(const int32_t* lengths, int B, int H, int page_rows, int reserve_rows,
                        const int32_t* free_pages, int n_free, int32_t* block_table,
                        int max_pages, int32_t* result,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * kvzap_extend_pages -- the same assignment for a cache that grows (decoding): head (b,h)
+ * already owns the first page_counts[b,h] entries of its table row and is brought up to
+ * ceil((lengths[b,h] + reserve_rows) / page_rows) pages by appending the next entries of
+ * free_pages behind them (heads in (b,h) order); page_counts (int32 [B,H], in/out) is
+ * updated, every other table entry is left as it is.  result and failure as above (on
+ * failure nothing changes).  With reserve_rows >= the number of tokens decoded until the
+ * next call, kvzap_decode_evict_paged always finds room.  Same workspace as
+ * kvzap_assign_pages.
+ */
+int kvzap_extend_pages(const int32_t* lengths, int32_t* page_counts, int B, int H,
+                       int page_rows, int reserve_rows, const int32_t* free_pages, int n_free,
+                       int32_t* block_table, int max_pages, int32_t* result,
                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
@@ -297,6 +313,27 @@ int kvzap_attend_decode_paged(const void* q, const void* K_pool, const void* V_p
                               const void* V_ring, const int32_t* seq_pos, int window,
                               int max_rows, float scale, void* out, int B, int H, int HQ,
                               int D, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * kvzap_decode_evict_paged -- kvzap_decode_evict with the kept prefix in pages (caption of
+ * Algorithm 1; layout above).  Row j of head (b,h)'s prefix is row j % page_rows of page
+ * block_table[b*H+h][j / page_rows] in K_pool / V_pool, its position in the same place of
+ *   pos_pool  int32 [num_pages, page_rows].
+ * A kept pair is appended at row lengths[b,h]; if that table slot is beyond max_pages or
+ * does not hold a page of the pool, error_flag is set, the pair is not appended and the
+ * length stays (as a full slab does in kvzap_decode_evict).  Ring, scores, lengths, seq_pos,
+ * workspace and every other argument as in kvzap_decode_evict.
+ */
+int kvzap_decode_evict_paged(const void* hidden_new, const void* W1, const void* b1,
+                             const void* W2, const void* b2, int Dh, int M,
+                             const void* k_new, const void* v_new,
+                             void* K_pool, void* V_pool, int32_t* pos_pool, int num_pages,
+                             const int32_t* block_table, int max_pages, int page_rows,
+                             void* K_ring, void* V_ring, float* score_ring,
+                             int32_t* lengths, int32_t* seq_pos,
+                             float tau, int window, int B, int H, int D,
+                             int32_t* error_flag,
+                             void* workspace, size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

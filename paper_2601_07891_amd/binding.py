@@ -40,6 +40,13 @@ SIGNATURES = {
                             [_c_void_p, _c_size_t, _c_void_p]),
     "kvzap_assign_pages": (_c_int, [_c_void_p, _c_int, _c_int, _c_int, _c_int, _c_void_p, _c_int,
                                     _c_void_p, _c_int, _c_void_p, _c_void_p, _c_size_t, _c_void_p]),
+    "kvzap_extend_pages": (_c_int, [_c_void_p, _c_void_p, _c_int, _c_int, _c_int, _c_int, _c_void_p,
+                                    _c_int, _c_void_p, _c_int, _c_void_p, _c_void_p, _c_size_t,
+                                    _c_void_p]),
+    "kvzap_decode_evict_paged": (_c_int, [_c_void_p] * 5 + [_c_int, _c_int] + [_c_void_p] * 5 +
+                                 [_c_int, _c_void_p, _c_int, _c_int] + [_c_void_p] * 5 +
+                                 [_c_float] + [_c_int] * 4 + [_c_void_p, _c_void_p, _c_size_t,
+                                                              _c_void_p]),
     "kvzap_compact_paged": (_c_int, [_c_void_p] * 6 + [_c_int, _c_int, _c_void_p, _c_void_p] +
                             [_c_int] * 5 + [_c_void_p]),
     "kvzap_attend_decode_paged": (_c_int, [_c_void_p] * 3 + [_c_int, _c_void_p, _c_int, _c_int] +
@@ -411,3 +418,81 @@ def kvzap_attend_decode_paged(q: torch.Tensor, K_pool: torch.Tensor, V_pool: tor
     if rc != 0:
         raise KvzapError(rc, "kvzap_attend_decode_paged")
     return out
+
+
+def kvzap_extend_pages(lengths: torch.Tensor, page_counts: torch.Tensor, page_rows: int,
+                       free_pages: torch.Tensor, block_table: torch.Tensor,
+                       reserve_rows: int = 0, result: Optional[torch.Tensor] = None,
+                       workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Appends pages behind the page_counts[b,h] a head owns (both updated in place).
+    Returns result int32 [2] = (pages taken, status) on the device."""
+    _check(lengths, torch.int32, "lengths"); _check(page_counts, torch.int32, "page_counts")
+    _check(free_pages, torch.int32, "free_pages"); _check(block_table, torch.int32, "block_table")
+    B, H = lengths.shape
+    if page_counts.numel() != B * H or block_table.dim() != 2 or block_table.shape[0] != B * H:
+        raise ValueError("page_counts must have B*H entries and block_table B*H rows")
+    if result is None:
+        result = torch.empty(4, dtype=torch.int32, device=lengths.device)
+    ws, ws_bytes = _workspace(kvzap_workspace_bytes(CALL_ASSIGN_PAGES, B, 1, 0, 0, H),
+                              lengths.device, workspace)
+    n_free = free_pages.numel()
+    rc = lib().kvzap_extend_pages(_ptr(lengths), _ptr(page_counts), B, H, int(page_rows),
+                                  int(reserve_rows), _ptr(free_pages) if n_free else None, n_free,
+                                  _ptr(block_table), block_table.shape[1], _ptr(result),
+                                  _ptr(ws), ws_bytes, _stream(stream))
+    if rc != 0:
+        raise KvzapError(rc, "kvzap_extend_pages")
+    return result
+
+
+class PagedDecodeState:
+    """Device buffers of the paged decode cache described in include/kvzap.h (allocation
+    only; all updates happen in the library)."""
+
+    def __init__(self, B: int, H: int, D: int, window: int, page_rows: int, num_pages: int,
+                 max_pages: int, device):
+        bf = torch.bfloat16
+        self.B, self.H, self.D, self.window = B, H, D, window
+        self.page_rows, self.num_pages, self.max_pages = page_rows, num_pages, max_pages
+        n = max(num_pages, 1)
+        self.K_pool = torch.zeros((n, page_rows, D), dtype=bf, device=device)
+        self.V_pool = torch.zeros((n, page_rows, D), dtype=bf, device=device)
+        self.pos_pool = torch.full((n, page_rows), -1, dtype=torch.int32, device=device)
+        self.block_table = torch.full((B * H, max_pages), -1, dtype=torch.int32, device=device)
+        self.page_counts = torch.zeros((B, H), dtype=torch.int32, device=device)
+        w = max(window, 1)
+        self.K_ring = torch.zeros((B, H, w, D), dtype=bf, device=device)
+        self.V_ring = torch.zeros((B, H, w, D), dtype=bf, device=device)
+        self.score_ring = torch.zeros((B, H, w), dtype=torch.float32, device=device)
+        self.lengths = torch.zeros((B, H), dtype=torch.int32, device=device)
+        self.seq_pos = torch.zeros(B, dtype=torch.int32, device=device)
+        self.error_flag = torch.zeros(4, dtype=torch.int32, device=device)
+
+
+def kvzap_decode_evict_paged(hidden_new: torch.Tensor, W1: torch.Tensor, b1, W2, b2,
+                             k_new: torch.Tensor, v_new: torch.Tensor, state: PagedDecodeState,
+                             tau: float, workspace: Optional[torch.Tensor] = None,
+                             stream=None) -> None:
+    """One decode step of one layer on the paged cache; `state` is updated in place."""
+    bf = torch.bfloat16
+    _check(hidden_new, bf, "hidden_new"); _check(W1, bf, "W1"); _check(b1, bf, "b1", True)
+    _check(W2, bf, "W2", True); _check(b2, bf, "b2", True)
+    _check(k_new, bf, "k_new"); _check(v_new, bf, "v_new")
+    B, Dh = hidden_new.shape
+    M = W1.shape[0] if W2 is not None else 0
+    st = state
+    if (B, st.H, st.D) != tuple(k_new.shape) or k_new.shape != v_new.shape or B != st.B:
+        raise ValueError("k_new / v_new must be [B,H,D] matching the state")
+    ws, ws_bytes = _workspace(
+        kvzap_workspace_bytes(CALL_DECODE_EVICT, B, 1, Dh, M, st.H), hidden_new.device, workspace)
+    ring = st.window > 0
+    rc = lib().kvzap_decode_evict_paged(
+        _ptr(hidden_new), _ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2), Dh, M,
+        _ptr(k_new), _ptr(v_new), _ptr(st.K_pool), _ptr(st.V_pool), _ptr(st.pos_pool),
+        st.num_pages, _ptr(st.block_table), st.max_pages, st.page_rows,
+        _ptr(st.K_ring) if ring else None, _ptr(st.V_ring) if ring else None,
+        _ptr(st.score_ring) if ring else None, _ptr(st.lengths), _ptr(st.seq_pos),
+        float(tau), int(st.window), B, st.H, st.D, _ptr(st.error_flag),
+        _ptr(ws), ws_bytes, _stream(stream))
+    if rc != 0:
+        raise KvzapError(rc, "kvzap_decode_evict_paged")

@@ -9,6 +9,7 @@ namespace {
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
+inline bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
 
 constexpr int kMaxH = 16;
 constexpr int kMaxD = 512;
@@ -181,6 +182,7 @@ int kvzap_decode_evict(const void* hidden_new, const void* W1, const void* b1, c
   a.K_ring = K_ring; a.V_ring = V_ring; a.score_ring = score_ring;
   a.lengths = lengths; a.seq_pos = seq_pos; a.tau = tau; a.window = window;
   a.B = B; a.H = H; a.D = D; a.error_flag = error_flag; a.workspace = workspace;
+  a.block_table = nullptr; a.max_pages = 0; a.log_page = 0; a.num_pages = 0;
   return kvzap::launch_decode_evict(a, static_cast<hipStream_t>(stream));
 }
 
@@ -221,14 +223,75 @@ int kvzap_assign_pages(const int32_t* lengths, int B, int H, int page_rows, int 
   if (!valid_page_rows(page_rows)) return KVZAP_ERR_SHAPE;
   if ((long long)B * H > 65535) return KVZAP_ERR_UNSUPPORTED;
   if (!lengths || !block_table || !result || (n_free > 0 && !free_pages)) return KVZAP_ERR_NULL;
-  if (!aligned16(lengths) || !aligned16(free_pages) || !aligned16(block_table) || !aligned16(result))
+  if (!aligned16(lengths) || !aligned4(free_pages) || !aligned16(block_table) || !aligned16(result))
     return KVZAP_ERR_ALIGN;
   if (!workspace || !aligned256(workspace) ||
       workspace_bytes < kvzap::assign_pages_workspace_bytes(B * H))
     return KVZAP_ERR_WORKSPACE;
-  return kvzap::launch_assign_pages(lengths, B * H, page_rows, reserve_rows, free_pages, n_free,
-                                    block_table, max_pages, result, workspace,
+  return kvzap::launch_assign_pages(lengths, nullptr, B * H, page_rows, reserve_rows, free_pages,
+                                    n_free, block_table, max_pages, result, workspace,
                                     static_cast<hipStream_t>(stream));
+}
+
+int kvzap_extend_pages(const int32_t* lengths, int32_t* page_counts, int B, int H, int page_rows,
+                       int reserve_rows, const int32_t* free_pages, int n_free,
+                       int32_t* block_table, int max_pages, int32_t* result, void* workspace,
+                       size_t workspace_bytes, void* stream) {
+  if (B <= 0 || H <= 0 || reserve_rows < 0 || n_free < 0 || max_pages <= 0) return KVZAP_ERR_SHAPE;
+  if (!valid_page_rows(page_rows)) return KVZAP_ERR_SHAPE;
+  if ((long long)B * H > 65535) return KVZAP_ERR_UNSUPPORTED;
+  if (!lengths || !page_counts || !block_table || !result || (n_free > 0 && !free_pages))
+    return KVZAP_ERR_NULL;
+  if (!aligned16(lengths) || !aligned16(page_counts) || !aligned4(free_pages) ||
+      !aligned16(block_table) || !aligned16(result))
+    return KVZAP_ERR_ALIGN;
+  if (!workspace || !aligned256(workspace) ||
+      workspace_bytes < kvzap::assign_pages_workspace_bytes(B * H))
+    return KVZAP_ERR_WORKSPACE;
+  return kvzap::launch_assign_pages(lengths, page_counts, B * H, page_rows, reserve_rows,
+                                    free_pages, n_free, block_table, max_pages, result, workspace,
+                                    static_cast<hipStream_t>(stream));
+}
+
+int kvzap_decode_evict_paged(const void* hidden_new, const void* W1, const void* b1,
+                             const void* W2, const void* b2, int Dh, int M, const void* k_new,
+                             const void* v_new, void* K_pool, void* V_pool, int32_t* pos_pool,
+                             int num_pages, const int32_t* block_table, int max_pages,
+                             int page_rows, void* K_ring, void* V_ring, float* score_ring,
+                             int32_t* lengths, int32_t* seq_pos, float tau, int window, int B,
+                             int H, int D, int32_t* error_flag, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+  if (B <= 0 || H <= 0 || D <= 0 || window < 0 || num_pages < 0 || max_pages <= 0)
+    return KVZAP_ERR_SHAPE;
+  if (!valid_page_rows(page_rows) || tau != tau) return KVZAP_ERR_SHAPE;
+  const int rc = check_scorer_shape(Dh, M, H);
+  if (rc != KVZAP_OK) return rc;
+  if (D % 8 != 0 || D > kMaxD || B > 65535) return KVZAP_ERR_UNSUPPORTED;
+  if (!hidden_new || !W1 || !k_new || !v_new || !block_table || !lengths || !seq_pos)
+    return KVZAP_ERR_NULL;
+  if (num_pages > 0 && (!K_pool || !V_pool || !pos_pool)) return KVZAP_ERR_NULL;
+  if (window > 0 && (!K_ring || !V_ring || !score_ring)) return KVZAP_ERR_NULL;
+  if (M > 0 && !W2) return KVZAP_ERR_NULL;
+  if (M == 0 && (W2 || b2)) return KVZAP_ERR_SHAPE;
+  const void* ptrs[] = {hidden_new, W1, b1, W2, b2, k_new, v_new, K_pool, V_pool, pos_pool,
+                        block_table, K_ring, V_ring, score_ring, lengths, seq_pos};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return KVZAP_ERR_ALIGN;
+  const size_t need = kvzap::decode_workspace_bytes(B, Dh, M, H);
+  if (need > 0 && (!workspace || !aligned256(workspace) || workspace_bytes < need))
+    return KVZAP_ERR_WORKSPACE;
+  kvzap::DecodeArgs a;
+  a.hidden_new = hidden_new; a.W1 = W1; a.b1 = b1; a.W2 = W2; a.b2 = b2;
+  a.Dh = Dh; a.M = M; a.k_new = k_new; a.v_new = v_new;
+  a.K_prefix = K_pool; a.V_prefix = V_pool; a.prefix_pos = pos_pool;
+  a.slab_offsets = nullptr; a.slab_capacity = nullptr;
+  a.K_ring = K_ring; a.V_ring = V_ring; a.score_ring = score_ring;
+  a.lengths = lengths; a.seq_pos = seq_pos; a.tau = tau; a.window = window;
+  a.B = B; a.H = H; a.D = D; a.error_flag = error_flag; a.workspace = workspace;
+  a.block_table = block_table; a.max_pages = max_pages; a.num_pages = num_pages;
+  a.log_page = 0;
+  while ((1 << a.log_page) < page_rows) ++a.log_page;
+  return kvzap::launch_decode_evict(a, static_cast<hipStream_t>(stream));
 }
 
 int kvzap_compact_paged(const void* K, const void* V, const int32_t* keep_idx,

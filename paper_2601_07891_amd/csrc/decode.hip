@@ -136,8 +136,20 @@ __global__ __launch_bounds__(kFThreads) void decode_finish_kernel(DecodeArgs a, 
       k_in[c] = kn[i];
       v_in[c] = vn[i];
       len_r[c] = a.lengths[bh];
-      cap_r[c] = a.slab_capacity[bh];
-      slab_r[c] = a.slab_offsets[bh];
+      if (a.block_table) {
+        // paged prefix: the next row is row len % page_rows of the page in table slot
+        // len / page_rows.  Expressed as a slab whose row `len` is that row, with room for
+        // exactly one more row if the slot holds a page of the pool.
+        const int len = len_r[c] < 0 ? 0 : len_r[c];
+        const int pslot = len >> a.log_page;
+        const int page = pslot < a.max_pages ? a.block_table[(size_t)bh * a.max_pages + pslot] : -1;
+        const bool ok = page >= 0 && page < a.num_pages;
+        cap_r[c] = ok ? len_r[c] + 1 : len_r[c];
+        slab_r[c] = (((long long)(ok ? page : 0)) << a.log_page) + (len & ((1 << a.log_page) - 1)) - len_r[c];
+      } else {
+        cap_r[c] = a.slab_capacity[bh];
+        slab_r[c] = a.slab_offsets[bh];
+      }
       if (w > 0 && q >= 0) {
         const size_t ring_at = ((size_t)bh * w + slot) * lpr + piece;
         k_old[c] = Kr[ring_at];

@@ -60,6 +60,10 @@ struct DecodeArgs {
   float tau; int window, B, H, D;
   int32_t* error_flag;
   void* workspace;
+  // paged prefix (block_table != nullptr): K_prefix / V_prefix / prefix_pos are the pools,
+  // slab_offsets / slab_capacity are unused
+  const int32_t* block_table;
+  int max_pages, log_page, num_pages;
 };
 int launch_decode_evict(const DecodeArgs& a, hipStream_t stream);
 size_t decode_workspace_bytes(int B, int Dh, int M, int H);
@@ -71,9 +75,10 @@ int launch_attend_decode(const void* q, const void* K_rows, const void* V_rows,
                          const int32_t* seq_pos, int window, int max_rows, float scale,
                          void* out, int B, int H, int HQ, void* workspace,
                          hipStream_t stream);
-int launch_assign_pages(const int32_t* lengths, int BH, int page_rows, int reserve_rows,
-                        const int32_t* free_pages, int n_free, int32_t* block_table,
-                        int max_pages, int32_t* result, void* workspace, hipStream_t stream);
+int launch_assign_pages(const int32_t* lengths, int32_t* page_counts, int BH, int page_rows,
+                        int reserve_rows, const int32_t* free_pages, int n_free,
+                        int32_t* block_table, int max_pages, int32_t* result, void* workspace,
+                        hipStream_t stream);
 size_t assign_pages_workspace_bytes(int BH);
 int launch_compact_paged(const void* K, const void* V, const int32_t* keep_idx,
                          const int32_t* lengths, const int64_t* offsets,

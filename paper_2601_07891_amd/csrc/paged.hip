@@ -3,8 +3,10 @@
 // live in pages of `page_rows` rows of one pool; row j of the head is row j % page_rows of
 // page block_table[b*H+h][j / page_rows].
 //
-//   assign_*  : every head, in (b,h) order, takes the next ceil((n + reserve) / page_rows)
-//               entries of the caller's free list (first fit, so the result is unique)
+//   assign_*  : every head, in (b,h) order, takes the next entries of the caller's free
+//               list until it owns ceil((n + reserve) / page_rows) pages (first fit, so the
+//               result is unique); "assign" starts from nothing, "extend" appends behind the
+//               pages a head already owns
 //   compact_* : the gather of Algorithm 1's last line, written through the block table
 #include "kvzap_internal.h"
 
@@ -18,11 +20,13 @@ __device__ __forceinline__ int pages_for(int n, int reserve, int log_page) {
   return total <= 0 ? 0 : (int)((total + (1ll << log_page) - 1) >> log_page);
 }
 
-// One block: counts -> exclusive scan -> start[0..BH], result[0] = pages taken,
-// result[1] = 0 ok / 1 free list too short / 2 a head needs more than max_pages.
+// One block: pages to add per head -> exclusive scan -> start[0..BH], have[0..BH-1] (pages
+// owned before the call; 0 without page_counts), result[0] = pages taken, result[1] = 0 ok /
+// 1 free list too short / 2 a head would need more than max_pages.
 __global__ __launch_bounds__(kScanThreads) void assign_scan_kernel(
-    const int32_t* __restrict__ lengths, int BH, int log_page, int reserve, int n_free,
-    int max_pages, int32_t* __restrict__ start, int32_t* __restrict__ result) {
+    const int32_t* __restrict__ lengths, const int32_t* __restrict__ page_counts, int BH,
+    int log_page, int reserve, int n_free, int max_pages, int32_t* __restrict__ start,
+    int32_t* __restrict__ have, int32_t* __restrict__ result) {
   __shared__ long long s_sum[kScanThreads];
   __shared__ int s_over;
   const int tid = threadIdx.x;
@@ -30,11 +34,19 @@ __global__ __launch_bounds__(kScanThreads) void assign_scan_kernel(
   const int lo = tid * per, hi = lo + per < BH ? lo + per : BH;
   if (tid == 0) s_over = 0;
   __syncthreads();
+  auto owned = [&](int i) {
+    int h = page_counts ? page_counts[i] : 0;
+    return h < 0 ? 0 : h;
+  };
+  auto to_add = [&](int i) {
+    const int c = pages_for(lengths[i], reserve, log_page) - owned(i);
+    return c > 0 ? c : 0;
+  };
   long long mine = 0;
   bool over = false;
   for (int i = lo; i < hi; ++i) {
-    const int c = pages_for(lengths[i], reserve, log_page);
-    over |= c > max_pages;
+    const int c = to_add(i);
+    over |= (long long)owned(i) + c > max_pages;
     mine += c;
   }
   if (over) s_over = 1;
@@ -52,7 +64,8 @@ __global__ __launch_bounds__(kScanThreads) void assign_scan_kernel(
   long long run = s_sum[tid] - mine;                     // exclusive prefix of this thread
   for (int i = lo; i < hi; ++i) {
     start[i] = status ? 0 : (int32_t)run;
-    run += pages_for(lengths[i], reserve, log_page);
+    have[i] = owned(i);
+    run += to_add(i);
   }
   if (tid == 0) {
     start[BH] = status ? 0 : (int32_t)total;
@@ -61,14 +74,24 @@ __global__ __launch_bounds__(kScanThreads) void assign_scan_kernel(
   }
 }
 
-// grid (tiles, B*H): the blocks of head bh write its block-table row (-1 beyond its pages)
+// grid (tiles, B*H): the blocks of head bh write its new table entries.  kWholeRow (assign):
+// the row is overwritten, -1 beyond its pages; otherwise (extend) only the appended entries
+// are written and page_counts is updated.
+template <bool kWholeRow>
 __global__ __launch_bounds__(256) void assign_fill_kernel(
-    const int32_t* __restrict__ start, const int32_t* __restrict__ free_pages,
-    int32_t* __restrict__ block_table, int max_pages) {
+    const int32_t* __restrict__ start, const int32_t* __restrict__ have,
+    const int32_t* __restrict__ free_pages, int32_t* __restrict__ block_table,
+    int32_t* __restrict__ page_counts, int max_pages) {
   const int bh = blockIdx.y;
-  const int s = start[bh], c = start[bh + 1] - s;
-  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < max_pages; i += gridDim.x * blockDim.x)
-    block_table[(size_t)bh * max_pages + i] = i < c ? free_pages[s + i] : -1;
+  const int s = start[bh], c = start[bh + 1] - s, h = have[bh];
+  const int end = kWholeRow ? max_pages : (h + c < max_pages ? h + c : max_pages);
+  for (int i = (kWholeRow ? 0 : h) + blockIdx.x * blockDim.x + threadIdx.x; i < end;
+       i += gridDim.x * blockDim.x) {
+    const int k = i - h;
+    block_table[(size_t)bh * max_pages + i] = (k >= 0 && k < c) ? free_pages[s + k] : -1;
+  }
+  if (!kWholeRow && page_counts && blockIdx.x == 0 && threadIdx.x == 0 && c > 0)
+    page_counts[bh] = h + c;
 }
 
 constexpr int kThreads = 256;
@@ -108,20 +131,32 @@ __global__ __launch_bounds__(kThreads) void compact_paged_kernel(
 
 }  // namespace
 
-size_t assign_pages_workspace_bytes(int BH) { return align_up((size_t)(BH + 1) * sizeof(int32_t), 256); }
+size_t assign_pages_workspace_bytes(int BH) {
+  return align_up((size_t)(2 * BH + 1) * sizeof(int32_t), 256);
+}
 
-int launch_assign_pages(const int32_t* lengths, int BH, int page_rows, int reserve_rows,
-                        const int32_t* free_pages, int n_free, int32_t* block_table,
-                        int max_pages, int32_t* result, void* workspace, hipStream_t stream) {
+// page_counts == nullptr: kvzap_assign_pages (nothing owned, whole rows written);
+// otherwise kvzap_extend_pages.
+int launch_assign_pages(const int32_t* lengths, int32_t* page_counts, int BH, int page_rows,
+                        int reserve_rows, const int32_t* free_pages, int n_free,
+                        int32_t* block_table, int max_pages, int32_t* result, void* workspace,
+                        hipStream_t stream) {
   int log_page = 0;
   while ((1 << log_page) < page_rows) ++log_page;
   int32_t* start = static_cast<int32_t*>(workspace);
-  assign_scan_kernel<<<1, kScanThreads, 0, stream>>>(lengths, BH, log_page, reserve_rows, n_free,
-                                                     max_pages, start, result);
+  int32_t* have = start + BH + 1;
+  assign_scan_kernel<<<1, kScanThreads, 0, stream>>>(lengths, page_counts, BH, log_page,
+                                                     reserve_rows, n_free, max_pages, start, have,
+                                                     result);
   if (hipGetLastError() != hipSuccess) return KVZAP_ERR_RUNTIME;
   int tiles = (max_pages + 255) / 256;
   tiles = tiles < 64 ? tiles : 64;
-  assign_fill_kernel<<<dim3(tiles, BH), 256, 0, stream>>>(start, free_pages, block_table, max_pages);
+  if (page_counts)
+    assign_fill_kernel<false><<<dim3(tiles, BH), 256, 0, stream>>>(start, have, free_pages,
+                                                                   block_table, page_counts, max_pages);
+  else
+    assign_fill_kernel<true><<<dim3(tiles, BH), 256, 0, stream>>>(start, have, free_pages,
+                                                                  block_table, nullptr, max_pages);
   return hipGetLastError() == hipSuccess ? KVZAP_OK : KVZAP_ERR_RUNTIME;
 }
 

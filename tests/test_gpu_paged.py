@@ -224,3 +224,117 @@ def test_paged_calls_reject_bad_arguments():
     assert L.kvzap_assign_pages(*args(8, 4)) == -2        # below 16
     assert L.kvzap_assign_pages(*args(16, 0)) == -2
     torch.cuda.synchronize()
+
+
+def test_extend_pages_matches_oracle_over_many_rounds():
+    rng = np.random.default_rng(21)
+    B, H, P, max_pages = 3, 5, 16, 40
+    lengths = np.zeros((B, H), np.int64)
+    counts = np.zeros(B * H, np.int32)
+    table = np.full((B * H, max_pages), -1, np.int32)
+    free = rng.permutation(2000).astype(np.int32)
+    d_counts = _i32(counts).reshape(B, H).contiguous()
+    d_table = _i32(table)
+    used_total = 0
+    for rnd in range(12):
+        lengths += rng.integers(0, 40, (B, H))
+        res = binding.kvzap_extend_pages(_i32(lengths), d_counts, P, _i32(free[used_total:]), d_table,
+                                         reserve_rows=8)
+        table, counts, used, ok = O.extend_pages(lengths, counts, table, P, free[used_total:], 8)
+        assert ok and res[:2].tolist() == [used, 0], rnd
+        used_total += used
+        np.testing.assert_array_equal(parity.to_np(d_table), table)
+        np.testing.assert_array_equal(parity.to_np(d_counts).reshape(-1), counts)
+    # failure leaves table and counts as they were
+    before_t, before_c = parity.to_np(d_table).copy(), parity.to_np(d_counts).copy()
+    res = binding.kvzap_extend_pages(_i32(lengths + 400), d_counts, P, _i32(free[used_total:]), d_table)
+    assert res[:2].tolist() == [0, 2]                  # a head would exceed the table width
+    res = binding.kvzap_extend_pages(_i32(lengths + 64), d_counts, P, _i32(free[:3]), d_table)
+    assert res[:2].tolist() == [0, 1]                  # free list too short
+    np.testing.assert_array_equal(parity.to_np(d_table), before_t)
+    np.testing.assert_array_equal(parity.to_np(d_counts), before_c)
+
+
+def _paged_canonical(st, b, h):
+    bh = b * st.H + h
+    n = int(st.lengths.reshape(-1)[bh]); p = int(st.seq_pos[b]); P = st.page_rows
+    row = parity.to_np(st.block_table)[bh]
+    Kc = O.gather_from_pages(parity.to_np(st.K_pool), row, n, P)
+    Vc = O.gather_from_pages(parity.to_np(st.V_pool), row, n, P)
+    pos = O.gather_from_pages(parity.to_np(st.pos_pool)[:, :, None], row, n, P)[:, 0].astype(np.int64)
+    w = st.window
+    win = list(range(max(p - w, 0), p)) if w > 0 else []
+    slots = [t % w for t in win]
+    Kw = parity.to_np(st.K_ring[b, h])[slots] if win else np.zeros((0, st.D), np.uint16)
+    Vw = parity.to_np(st.V_ring[b, h])[slots] if win else np.zeros((0, st.D), np.uint16)
+    return (np.concatenate([pos, np.array(win, np.int64)]),
+            np.concatenate([Kc, Kw]), np.concatenate([Vc, Vw]))
+
+
+@pytest.mark.parametrize("w,P,steps", [(0, 16, 70), (4, 16, 90), (128, 32, 300)])
+def test_decode_evict_paged_equals_the_slab_form_and_the_oracle(w, P, steps):
+    """The same token stream through kvzap_decode_evict (slabs) and kvzap_decode_evict_paged
+    (pages topped up every few steps by kvzap_extend_pages): identical canonical caches, and
+    equal to the decode oracle's with exact-integer linear scores."""
+    from tests.test_gpu_decode import _canonical_gpu
+    B, H, D, Dh, tau = 3, 4, 128, 256, 1.0
+    T = steps
+    hid, wts = synth.make_exact_case(T, Dh, H, 0, seed=w + P)
+    hid = hid.expand(B, T, Dh).contiguous()
+    hid = hid + torch.arange(B).view(B, 1, 1).to(torch.bfloat16)          # sequences differ
+    K = synth.make_scores(B, H, T * D, seed=1).view(B, H, T, D).bfloat16()
+    V = synth.make_scores(B, H, T * D, seed=2).view(B, H, T, D).bfloat16()
+    ow = synth.oracle_weights(wts)
+    S = np.stack([O.score_linear(O.bf16_bits_to_f64(synth.bits(hid[b])), ow["W"], ow["b"])
+                  for b in range(B)])
+    dec = O.DecodeOracle(B, H, w, tau)
+    slab = binding.DecodeState(B, H, D, w, np.full((B, H), T + 1), DEV)
+    max_pages = T // P + 2
+    paged = binding.PagedDecodeState(B, H, D, w, P, B * H * max_pages, max_pages, DEV)
+    free = torch.randperm(paged.num_pages, dtype=torch.int32).to(DEV)
+    used = 0
+    d = {k: (None if v is None else v.to(DEV)) for k, v in wts.items()}
+    hid_d, K_d, V_d = hid.to(DEV), K.to(DEV), V.to(DEV)
+    every = 5                                           # pages topped up every 5 steps, room for 5 rows
+    for t in range(T):
+        if t % every == 0:
+            res = binding.kvzap_extend_pages(paged.lengths, paged.page_counts, P, free[used:],
+                                             paged.block_table, reserve_rows=every)
+            assert int(res[1]) == 0
+            used += int(res[0])
+        args = (hid_d[:, t].contiguous(), d["W1"], d["b1"], None, None,
+                K_d[:, :, t].contiguous(), V_d[:, :, t].contiguous())
+        binding.kvzap_decode_evict(*args, slab, tau)
+        binding.kvzap_decode_evict_paged(*args, paged, tau)
+        dec.step(S[:, :, t], synth.bits(K[:, :, t]), synth.bits(V[:, :, t]))
+    torch.cuda.synchronize()
+    assert int(paged.error_flag[0]) == 0 and int(slab.error_flag[0]) == 0
+    np.testing.assert_array_equal(parity.to_np(paged.lengths), parity.to_np(slab.lengths))
+    kept = 0
+    for b in range(B):
+        for h in range(H):
+            pp, Kp_, Vp_ = _paged_canonical(paged, b, h)
+            ps, Ks_, Vs_ = _canonical_gpu(slab, b, h)
+            rpos, rK, rV = dec.canonical(b, h)
+            np.testing.assert_array_equal(pp, ps)
+            np.testing.assert_array_equal(Kp_, Ks_); np.testing.assert_array_equal(Vp_, Vs_)
+            np.testing.assert_array_equal(pp, rpos)
+            np.testing.assert_array_equal(Kp_, rK.reshape(-1, D))
+            kept += len(pp)
+    assert kept < B * H * T                             # something was evicted
+
+
+def test_decode_evict_paged_without_a_page_sets_the_error_flag():
+    B, H, D, Dh, w, P = 1, 2, 128, 256, 2, 16
+    hid, wts = synth.make_exact_case(40, Dh, H, 0, seed=1)
+    st = binding.PagedDecodeState(B, H, D, w, P, 4, 2, DEV)
+    st.block_table.copy_(torch.tensor([[0, -1], [1, 77]], dtype=torch.int32))     # one page each
+    d = {k: (None if v is None else v.to(DEV)) for k, v in wts.items()}
+    kv = torch.ones((B, H, D), dtype=torch.bfloat16, device=DEV)
+    for t in range(40):
+        binding.kvzap_decode_evict_paged(hid[:, t].to(DEV).contiguous(), d["W1"], d["b1"], None, None,
+                                         kv, kv, st, float("-inf"))
+    torch.cuda.synchronize()
+    assert int(st.error_flag[0]) == 1
+    assert (parity.to_np(st.lengths) == P).all()        # never beyond the pages a head owns
+    assert (parity.to_np(st.pos_pool)[2:] == -1).all()  # pages 2, 3 untouched
