@@ -111,6 +111,9 @@ def keep_mask(scores: np.ndarray, tau: float, window: int,
     if window < 0:
         raise ValueError("window must be >= 0")
     t = np.arange(T)
+    tau = np.asarray(tau, dtype=np.float64)
+    if tau.ndim == 1:                       # one threshold per head (fixed-budget variants)
+        tau = tau[:, None]
     with np.errstate(invalid="ignore"):
         keep = scores >= tau
     keep = keep | (t >= Tb - window)[None, :]
@@ -170,7 +173,8 @@ def prune(scores: np.ndarray, tau: float, window: int,
     all_idx, all_len = [], []
     for b in range(B):
         Tb = None if seq_lens is None else int(seq_lens[b])
-        idx, n = kept_indices(keep_mask(scores[b], tau, window, Tb))
+        tau_b = tau if np.ndim(tau) == 0 else np.asarray(tau)[b]    # scalar, or [B, H]
+        idx, n = kept_indices(keep_mask(scores[b], tau_b, window, Tb))
         all_idx.append(idx)
         all_len.append(n)
     lengths = (np.stack(all_len) if B else np.zeros((0, H), np.int32)).astype(np.int32)
@@ -446,3 +450,46 @@ def extend_pages(lengths: np.ndarray, page_counts: np.ndarray, table: np.ndarray
             pos += 1
         new_counts[bh] += c
     return table, new_counts, pos, True
+
+
+# --------------------------------------------------------------------------
+# fixed-budget selection on the same scores (Sec. 3.3: KVzip keeps a fixed
+# fraction; ablation of Sec. 4: fixed-ratio top-k per head, or per layer as in
+# AdaKV, against thresholding)
+# --------------------------------------------------------------------------
+def topk_threshold(scores: np.ndarray, window: int, k: int, per_layer: bool,
+                   seq_lens: Optional[Sequence[int]] = None) -> np.ndarray:
+    """Thresholds that turn Algorithm 1's comparison into a fixed-budget rule.
+
+    Population of sequence b, head h: its non-window positions t < T_b - window
+    whose score is not NaN.  per_layer = False: tau[b,h] is the k-th largest
+    score of that population (each head keeps its own top k).  per_layer = True:
+    the populations of all H heads of sequence b are pooled and tau[b,:] is the
+    k-th largest of the pool (the heads share one budget of k).  k <= 0 gives
+    +inf (only the window is kept), k >= population size gives -inf.
+
+    Reading: the kept set is {score >= tau}, so entries tied with the k-th
+    largest are all kept (the unique set; equal to a top-k whenever scores are
+    distinct), and the window stays protected as in Algorithm 1.
+    Returns float64 [B, H].
+    """
+    scores = np.asarray(scores, dtype=np.float64)
+    B, H, T = scores.shape
+    tau = np.empty((B, H))
+    for b in range(B):
+        Tb = T if seq_lens is None else int(seq_lens[b])
+        n_pop = max(Tb - window, 0)
+        pops = []
+        for h in range(H):
+            pop = scores[b, h, :n_pop]
+            pops.append(pop[~np.isnan(pop)])
+        groups = [np.concatenate(pops)] * H if per_layer else pops
+        for h in range(H):
+            pop = groups[h]
+            if k <= 0:
+                tau[b, h] = np.inf
+            elif k >= pop.size:
+                tau[b, h] = -np.inf
+            else:
+                tau[b, h] = np.sort(pop)[::-1][k - 1]
+    return tau
