@@ -63,7 +63,8 @@ typedef enum kvzap_call {
   KVZAP_CALL_COMPACT = 2,
   KVZAP_CALL_DECODE_EVICT = 3,
   KVZAP_CALL_ATTEND_DECODE = 4,  /* pass T = max_rows, Dh = HQ, M = window (also for the paged form) */
-  KVZAP_CALL_ASSIGN_PAGES = 5    /* only B and H matter (pass T = 1) */
+  KVZAP_CALL_ASSIGN_PAGES = 5,   /* only B and H matter (pass T = 1) */
+  KVZAP_CALL_TOPK_THRESHOLD = 6  /* pass M = per_layer (0 or 1) */
 } kvzap_call;
 
 /* Text for a status code (host pointer to a static string, never NULL). */
@@ -135,6 +136,34 @@ int kvzap_mask(const float* scores, float tau, int window,
                const int32_t* seq_lens, int B, int H, int T,
                int32_t* keep_idx, int32_t* lengths, int64_t* offsets,
                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * kvzap_topk_threshold -- thresholds for the fixed-budget variants (Sec. 3.3: keeping a
+ * fixed fraction; Sec. 4 ablation: fixed-ratio top-k per head, or per layer as in AdaKV).
+ * The population of head (b,h) is its non-window positions t < T_b - window whose score is
+ * not NaN.  per_layer == 0: tau_out[b,h] = the k-th largest score of that population.
+ * per_layer != 0: the populations of the H heads of sequence b are pooled and
+ * tau_out[b,:] = the k-th largest of the pool (one budget of k shared by the heads).
+ * k <= 0 gives +inf, k >= the population size gives -inf.  Feeding tau_out to
+ * kvzap_mask_per_head keeps {score >= tau} plus the window: exactly k non-window entries
+ * per head (per sequence) when scores are distinct, all entries tied with the k-th largest
+ * otherwise.  Exact (a radix select on the bits): no tolerance.
+ *   scores fp32 [B,H,T]; seq_lens int32 [B] or NULL; tau_out fp32 [B,H] (device).
+ *   workspace: kvzap_workspace_bytes(KVZAP_CALL_TOPK_THRESHOLD, B, T, 0, per_layer, H).
+ */
+int kvzap_topk_threshold(const float* scores, int window, const int32_t* seq_lens,
+                         int64_t k, int per_layer, int B, int H, int T, float* tau_out,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * kvzap_mask_per_head -- kvzap_mask with one threshold per (sequence, head), read from
+ * device memory: tau fp32 [B,H] (NaN entries keep nothing but the window).  Everything else
+ * as kvzap_mask, including the workspace.
+ */
+int kvzap_mask_per_head(const float* scores, const float* tau, int window,
+                        const int32_t* seq_lens, int B, int H, int T,
+                        int32_t* keep_idx, int32_t* lengths, int64_t* offsets,
+                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * kvzap_compact -- the ragged per-head gather (Algorithm 1, last line; Sec. 5).

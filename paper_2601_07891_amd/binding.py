@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libkvzap.so")
 
 CALL_SCORE, CALL_MASK, CALL_COMPACT, CALL_DECODE_EVICT, CALL_ATTEND_DECODE = 0, 1, 2, 3, 4
-CALL_ASSIGN_PAGES = 5
+CALL_ASSIGN_PAGES, CALL_TOPK_THRESHOLD = 5, 6
 
 _c_void_p, _c_int, _c_float, _c_size_t, _c_int64 = (
     ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t, ctypes.c_int64)
@@ -31,6 +31,11 @@ SIGNATURES = {
     "kvzap_score": (_c_int, [_c_void_p] * 6 + [_c_int] * 5 + [_c_void_p, _c_size_t, _c_void_p]),
     "kvzap_mask": (_c_int, [_c_void_p, _c_float, _c_int, _c_void_p, _c_int, _c_int, _c_int,
                             _c_void_p, _c_void_p, _c_void_p, _c_void_p, _c_size_t, _c_void_p]),
+    "kvzap_topk_threshold": (_c_int, [_c_void_p, _c_int, _c_void_p, _c_int64, _c_int, _c_int, _c_int,
+                                      _c_int, _c_void_p, _c_void_p, _c_size_t, _c_void_p]),
+    "kvzap_mask_per_head": (_c_int, [_c_void_p, _c_void_p, _c_int, _c_void_p, _c_int, _c_int, _c_int,
+                                     _c_void_p, _c_void_p, _c_void_p, _c_void_p, _c_size_t,
+                                     _c_void_p]),
     "kvzap_compact": (_c_int, [_c_void_p] * 7 + [_c_int64] + [_c_int] * 4 + [_c_void_p]),
     "kvzap_decode_evict": (_c_int, [_c_void_p] * 5 + [_c_int, _c_int] + [_c_void_p] * 12 +
                            [_c_float] + [_c_int] * 4 + [_c_void_p, _c_void_p, _c_size_t,
@@ -496,3 +501,54 @@ def kvzap_decode_evict_paged(hidden_new: torch.Tensor, W1: torch.Tensor, b1, W2,
         _ptr(ws), ws_bytes, _stream(stream))
     if rc != 0:
         raise KvzapError(rc, "kvzap_decode_evict_paged")
+
+
+def kvzap_topk_threshold(scores: torch.Tensor, window: int, k: int, per_layer: bool,
+                         seq_lens: Optional[torch.Tensor] = None,
+                         tau_out: Optional[torch.Tensor] = None,
+                         workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """scores fp32 [B,H,T] -> tau fp32 [B,H]: the k-th largest non-window score per head, or
+    per sequence over its pooled heads."""
+    _check(scores, torch.float32, "scores"); _check(seq_lens, torch.int32, "seq_lens", True)
+    B, H, T = scores.shape
+    if tau_out is None:
+        tau_out = torch.empty((B, H), dtype=torch.float32, device=scores.device)
+    else:
+        _check(tau_out, torch.float32, "tau_out")
+    ws, ws_bytes = _workspace(
+        kvzap_workspace_bytes(CALL_TOPK_THRESHOLD, B, T, 0, 1 if per_layer else 0, H),
+        scores.device, workspace)
+    rc = lib().kvzap_topk_threshold(_ptr(scores), int(window), _ptr(seq_lens), int(k),
+                                    1 if per_layer else 0, B, H, T, _ptr(tau_out), _ptr(ws),
+                                    ws_bytes, _stream(stream))
+    if rc != 0:
+        raise KvzapError(rc, "kvzap_topk_threshold")
+    return tau_out
+
+
+def kvzap_mask_per_head(scores: torch.Tensor, tau: torch.Tensor, window: int,
+                        seq_lens: Optional[torch.Tensor] = None,
+                        keep_idx: Optional[torch.Tensor] = None,
+                        lengths: Optional[torch.Tensor] = None,
+                        offsets: Optional[torch.Tensor] = None,
+                        workspace: Optional[torch.Tensor] = None, stream=None):
+    """kvzap_mask with tau fp32 [B,H] on the device.  Returns (keep_idx, lengths, offsets)."""
+    _check(scores, torch.float32, "scores"); _check(tau, torch.float32, "tau")
+    _check(seq_lens, torch.int32, "seq_lens", True)
+    B, H, T = scores.shape
+    if tau.numel() != B * H:
+        raise ValueError("tau must have B*H entries")
+    dev = scores.device
+    if keep_idx is None:
+        keep_idx = torch.empty(B * H * T, dtype=torch.int32, device=dev)
+    if lengths is None:
+        lengths = torch.empty((B, H), dtype=torch.int32, device=dev)
+    if offsets is None:
+        offsets = torch.empty(B * H + 1, dtype=torch.int64, device=dev)
+    ws, ws_bytes = _workspace(kvzap_workspace_bytes(CALL_MASK, B, T, 0, 0, H), dev, workspace)
+    rc = lib().kvzap_mask_per_head(_ptr(scores), _ptr(tau), int(window), _ptr(seq_lens), B, H, T,
+                                   _ptr(keep_idx), _ptr(lengths), _ptr(offsets), _ptr(ws),
+                                   ws_bytes, _stream(stream))
+    if rc != 0:
+        raise KvzapError(rc, "kvzap_mask_per_head")
+    return keep_idx, lengths, offsets

@@ -76,6 +76,9 @@ size_t kvzap_workspace_bytes(int which_call, int B, int T, int Dh, int M, int H)
     case KVZAP_CALL_ATTEND_DECODE:   // T = max_rows, Dh = HQ, M = window
       if (check_attend_shape(B, H, Dh, T, M) != KVZAP_OK) return 0;
       return kvzap::attend_workspace_bytes(B, H, Dh, T, M);
+    case KVZAP_CALL_TOPK_THRESHOLD:
+      if ((long long)B * H > 65535) return 0;
+      return kvzap::topk_workspace_bytes(B, H, M != 0);
     case KVZAP_CALL_ASSIGN_PAGES:
       if ((long long)B * H > 65535) return 0;
       return kvzap::assign_pages_workspace_bytes(B * H);
@@ -120,8 +123,39 @@ int kvzap_mask(const float* scores, float tau, int window, const int32_t* seq_le
     return KVZAP_ERR_ALIGN;
   if (!workspace || !aligned256(workspace) || workspace_bytes < mask_workspace(B, H, T))
     return KVZAP_ERR_WORKSPACE;
-  return kvzap::launch_mask(scores, tau, window, seq_lens, B, H, T, keep_idx, lengths, offsets,
+  return kvzap::launch_mask(scores, tau, nullptr, window, seq_lens, B, H, T, keep_idx, lengths, offsets,
                             workspace, static_cast<hipStream_t>(stream));
+}
+
+int kvzap_mask_per_head(const float* scores, const float* tau, int window,
+                        const int32_t* seq_lens, int B, int H, int T, int32_t* keep_idx,
+                        int32_t* lengths, int64_t* offsets, void* workspace,
+                        size_t workspace_bytes, void* stream) {
+  if (B <= 0 || H <= 0 || T <= 0 || window < 0) return KVZAP_ERR_SHAPE;
+  if ((long long)B * H > 65535) return KVZAP_ERR_UNSUPPORTED;
+  if (!scores || !tau || !keep_idx || !lengths || !offsets) return KVZAP_ERR_NULL;
+  if (!aligned16(scores) || !aligned16(tau) || !aligned16(keep_idx) || !aligned16(lengths) ||
+      !aligned16(offsets) || !aligned16(seq_lens))
+    return KVZAP_ERR_ALIGN;
+  if (!workspace || !aligned256(workspace) || workspace_bytes < mask_workspace(B, H, T))
+    return KVZAP_ERR_WORKSPACE;
+  return kvzap::launch_mask(scores, 0.0f, tau, window, seq_lens, B, H, T, keep_idx, lengths,
+                            offsets, workspace, static_cast<hipStream_t>(stream));
+}
+
+int kvzap_topk_threshold(const float* scores, int window, const int32_t* seq_lens, int64_t k,
+                         int per_layer, int B, int H, int T, float* tau_out, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+  if (B <= 0 || H <= 0 || T <= 0 || window < 0) return KVZAP_ERR_SHAPE;
+  if ((long long)B * H > 65535) return KVZAP_ERR_UNSUPPORTED;
+  if ((long long)H * T > 0xFFFFFFFFll) return KVZAP_ERR_UNSUPPORTED;     // 32-bit histogram bins
+  if (!scores || !tau_out) return KVZAP_ERR_NULL;
+  if (!aligned16(scores) || !aligned16(tau_out) || !aligned16(seq_lens)) return KVZAP_ERR_ALIGN;
+  if (!workspace || !aligned256(workspace) ||
+      workspace_bytes < kvzap::topk_workspace_bytes(B, H, per_layer != 0))
+    return KVZAP_ERR_WORKSPACE;
+  return kvzap::launch_topk_threshold(scores, window, seq_lens, (long long)k, per_layer != 0, B,
+                                      H, T, tau_out, workspace, static_cast<hipStream_t>(stream));
 }
 
 int kvzap_compact(const void* K, const void* V, const int32_t* keep_idx,

@@ -33,9 +33,14 @@ __device__ __forceinline__ unsigned short float_to_bf16_bits(float f) {
 }
 
 // launchers (each returns a kvzap_status); arguments are already validated
-int launch_mask(const float* scores, float tau, int window, const int32_t* seq_lens,
-                int B, int H, int T, int32_t* keep_idx, int32_t* lengths,
-                int64_t* offsets, void* workspace, hipStream_t stream);
+int launch_mask(const float* scores, float tau, const float* tau_head, int window,
+                const int32_t* seq_lens, int B, int H, int T, int32_t* keep_idx,
+                int32_t* lengths, int64_t* offsets, void* workspace, hipStream_t stream);
+
+int launch_topk_threshold(const float* scores, int window, const int32_t* seq_lens, long long k,
+                          bool per_layer, int B, int H, int T, float* tau_out, void* workspace,
+                          hipStream_t stream);
+size_t topk_workspace_bytes(int B, int H, bool per_layer);
 
 int launch_compact(const void* K, const void* V, const int32_t* keep_idx,
                    const int32_t* lengths, const int64_t* offsets, void* K_out,

@@ -46,10 +46,11 @@ __device__ __forceinline__ unsigned keep_bits4(const float* __restrict__ row, in
 }
 
 __global__ __launch_bounds__(kThreads) void mask_count_kernel(
-    const float* __restrict__ scores, float tau, int window,
+    const float* __restrict__ scores, float tau_all, const float* __restrict__ tau_head, int window,
     const int32_t* __restrict__ seq_lens, int H, int T, int nchunks,
     int32_t* __restrict__ chunk_counts) {
   const int chunk = blockIdx.x, bh = blockIdx.y;
+  const float tau = tau_head ? tau_head[bh] : tau_all;     // one threshold, or one per head
   const int Tb = seq_lens ? seq_lens[bh / H] : T;
   const float* row = scores + (size_t)bh * T;
   const bool vec_ok = (T % 4) == 0;
@@ -129,7 +130,7 @@ __device__ __forceinline__ long long block_sum_i64(long long v, long long* lds_s
 
 template <bool kFused>
 __global__ __launch_bounds__(kThreads) void mask_emit_kernel(
-    const float* __restrict__ scores, float tau, int window,
+    const float* __restrict__ scores, float tau_all, const float* __restrict__ tau_head, int window,
     const int32_t* __restrict__ seq_lens, int H, int T, int nchunks,
     const int64_t* __restrict__ chunk_prefix, const int32_t* __restrict__ chunk_counts,
     int32_t* __restrict__ keep_idx, int32_t* __restrict__ lengths,
@@ -156,6 +157,7 @@ __global__ __launch_bounds__(kThreads) void mask_emit_kernel(
   } else {
     my_prefix = chunk_prefix[(size_t)bh * nchunks + chunk];
   }
+  const float tau = tau_head ? tau_head[bh] : tau_all;
   const int Tb = seq_lens ? seq_lens[bh / H] : T;
   const float* row = scores + (size_t)bh * T;
   const bool vec_ok = (T % 4) == 0;
@@ -185,7 +187,8 @@ __global__ __launch_bounds__(kThreads) void mask_emit_kernel(
 
 }  // namespace
 
-int launch_mask(const float* scores, float tau, int window, const int32_t* seq_lens,
+int launch_mask(const float* scores, float tau, const float* tau_head, int window,
+                const int32_t* seq_lens,
                 int B, int H, int T, int32_t* keep_idx, int32_t* lengths,
                 int64_t* offsets, void* workspace, hipStream_t stream) {
   const int BH = B * H;
@@ -194,16 +197,16 @@ int launch_mask(const float* scores, float tau, int window, const int32_t* seq_l
   int64_t* chunk_prefix = reinterpret_cast<int64_t*>(
       static_cast<char*>(workspace) + align_up((size_t)BH * nchunks * sizeof(int32_t), 256));
   const dim3 grid(nchunks, BH);
-  mask_count_kernel<<<grid, kThreads, 0, stream>>>(scores, tau, window, seq_lens, H, T,
+  mask_count_kernel<<<grid, kThreads, 0, stream>>>(scores, tau, tau_head, window, seq_lens, H, T,
                                                    nchunks, chunk_counts);
   if ((long long)BH * nchunks <= kFusedMaxChunks) {
-    mask_emit_kernel<true><<<grid, kThreads, 0, stream>>>(scores, tau, window, seq_lens, H, T,
+    mask_emit_kernel<true><<<grid, kThreads, 0, stream>>>(scores, tau, tau_head, window, seq_lens, H, T,
                                                           nchunks, chunk_prefix, chunk_counts,
                                                           keep_idx, lengths, offsets);
   } else {
     mask_scan_kernel<<<1, kScanThreads, 0, stream>>>(chunk_counts, chunk_prefix, BH, nchunks,
                                                      lengths, offsets);
-    mask_emit_kernel<false><<<grid, kThreads, 0, stream>>>(scores, tau, window, seq_lens, H, T,
+    mask_emit_kernel<false><<<grid, kThreads, 0, stream>>>(scores, tau, tau_head, window, seq_lens, H, T,
                                                            nchunks, chunk_prefix, chunk_counts,
                                                            keep_idx, lengths, offsets);
   }

@@ -1,0 +1,116 @@
+"""GPU parity of the fixed-budget variants: kvzap_topk_threshold must return exactly the
+oracle's threshold (bit work, no tolerance; -0.0 and +0.0 compare equal), and
+kvzap_mask_per_head with those thresholds exactly the oracle's kept sets."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import kvzap_oracle as O
+from paper_2601_07891_amd import binding, synth
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _check(S, window, k, per_layer, seq_lens=None):
+    Sd = torch.from_numpy(S.astype(np.float32)).to(DEV)
+    sl = None if seq_lens is None else torch.tensor(seq_lens, dtype=torch.int32, device=DEV)
+    tau = binding.kvzap_topk_threshold(Sd, window, k, per_layer, sl)
+    idx, n, off = binding.kvzap_mask_per_head(Sd, tau, window, sl)
+    torch.cuda.synchronize()
+    S64 = S.astype(np.float32).astype(np.float64)
+    ref_tau = O.topk_threshold(S64, window, k, per_layer, seq_lens)
+    got_tau = tau.double().cpu().numpy()
+    assert np.array_equal(got_tau, ref_tau), (k, per_layer, got_tau, ref_tau)
+    ref = O.prune(S64, ref_tau, window, None, None, seq_lens)
+    np.testing.assert_array_equal(parity.to_np(n), ref.lengths)
+    np.testing.assert_array_equal(parity.to_np(off), ref.offsets)
+    got_idx = parity.to_np(idx)
+    B, H = ref.lengths.shape
+    for b in range(B):
+        for h in range(H):
+            o = int(ref.offsets[b * H + h])
+            np.testing.assert_array_equal(got_idx[o:o + len(ref.idx[b][h])], ref.idx[b][h])
+    return ref
+
+
+@pytest.mark.parametrize("per_layer", [False, True])
+def test_random_scores_many_budgets(per_layer):
+    rng = np.random.default_rng(0)
+    B, H, T, w = 2, 4, 9000, 128                     # T spans three 4096-score blocks, ragged tail
+    S = (rng.standard_normal((B, H, T)) * np.array([0.3, 1.0, 2.0, 5.0])[None, :, None])
+    pop = (T - w) * (H if per_layer else 1)
+    for k in (1, 2, 255, 256, 257, 1000, pop // 2, pop - 1):
+        ref = _check(S, w, k, per_layer)
+        if per_layer:
+            assert ((ref.lengths - w).sum(axis=1) == k).all()
+        else:
+            assert (ref.lengths == k + w).all()
+
+
+@pytest.mark.parametrize("per_layer", [False, True])
+def test_limits(per_layer):
+    rng = np.random.default_rng(1)
+    S = rng.standard_normal((2, 3, 500))
+    pop = (500 - 16) * (3 if per_layer else 1)
+    for k in (-5, 0, pop, pop + 1, 10 ** 9):
+        _check(S, 16, k, per_layer)
+    _check(S, 600, 3, per_layer)                     # the window covers everything
+    _check(S, 0, 7, per_layer)                       # no window
+
+
+def test_ties_special_values_and_padding():
+    rng = np.random.default_rng(2)
+    B, H, T, w = 2, 2, 5000, 10
+    S = rng.integers(-3, 4, (B, H, T)).astype(np.float64)          # heavy ties, +-0 absent
+    S[0, 0, 5] = np.nan; S[0, 0, 77] = np.inf; S[0, 1, 3] = -np.inf; S[1, 0, 9] = np.nan
+    S[1, 1, 100:200] = -0.0
+    S[1, 1, 200:300] = 0.0
+    for k in (1, 3, 700, 2500, 4000, 4989, 4990):
+        _check(S, w, k, False)
+        _check(S, w, k * 2, True)
+    _check(S, w, 100, False, seq_lens=[5000, 1234])
+    _check(S, w, 100, True, seq_lens=[37, 4097])
+    _check(S, w, 5, False, seq_lens=[0, 3])          # populations of size zero
+
+
+def test_extreme_floats():
+    # denormals, huge magnitudes, both signs: the order-preserving key must sort them all
+    vals = np.array([1e-45, -1e-45, 1e-38, -1e-38, 3e38, -3e38, 1.0, -1.0, 0.5, 1.5, 2.0 ** -126,
+                     -2.0 ** -126, 65504.0, 1e-20, -1e-20, 7.0], dtype=np.float32)
+    rng = np.random.default_rng(3)
+    S = rng.choice(vals, size=(1, 2, 3000)).astype(np.float64)
+    for k in (1, 10, 500, 1500, 2900):
+        _check(S, 20, k, False)
+        _check(S, 20, k, True)
+
+
+def test_topk_at_config_shape_keeps_exactly_the_budget():
+    # the 128k-token shape: 25 % of every head, and the same budget pooled per layer
+    B, H, T, w = 1, 8, 131072, 128
+    S = synth.make_scores(B, H, T, seed=5, device=DEV) * torch.linspace(0.5, 2.0, H, device=DEV).view(1, H, 1)
+    k = (T - w) // 4
+    tau = binding.kvzap_topk_threshold(S, w, k, False)
+    _, n, _ = binding.kvzap_mask_per_head(S, tau, w)
+    assert (n == k + w).all()
+    ref = O.topk_threshold(S.double().cpu().numpy(), w, k, False)
+    assert np.array_equal(tau.double().cpu().numpy(), ref)
+    tau = binding.kvzap_topk_threshold(S, w, k * H, True)
+    _, n, _ = binding.kvzap_mask_per_head(S, tau, w)
+    assert int(n.sum()) == k * H + w * H
+    assert n[0, -1] > n[0, 0]                        # the budget moves to the wide heads
+    ref = O.topk_threshold(S.double().cpu().numpy(), w, k * H, True)
+    assert np.array_equal(tau.double().cpu().numpy(), ref)
+
+
+def test_rejects_bad_arguments():
+    L = binding.lib()
+    S = torch.zeros((1, 2, 64), dtype=torch.float32, device=DEV)
+    tau = torch.zeros(2, dtype=torch.float32, device=DEV)
+    ws = torch.empty(1 << 16, dtype=torch.uint8, device=DEV)
+    assert L.kvzap_topk_threshold(S.data_ptr(), 4, None, 3, 0, 1, 2, 64, tau.data_ptr(), ws.data_ptr(), ws.numel(), None) == 0
+    assert L.kvzap_topk_threshold(S.data_ptr(), -1, None, 3, 0, 1, 2, 64, tau.data_ptr(), ws.data_ptr(), ws.numel(), None) == -2
+    assert L.kvzap_topk_threshold(S.data_ptr(), 4, None, 3, 0, 1, 2, 64, None, ws.data_ptr(), ws.numel(), None) == -1
+    assert L.kvzap_topk_threshold(S.data_ptr(), 4, None, 3, 0, 1, 2, 64, tau.data_ptr(), ws.data_ptr(), 16, None) == -6
+    torch.cuda.synchronize()
