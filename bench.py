@@ -301,6 +301,9 @@ def main() -> int:
                          "default is one stream, which keeps per-kernel timings clean")
     ap.add_argument("--decode-cache-rows", type=int, nargs=2, default=[4096, 32768],
                     help="decode workload: range of rows already kept per (sequence, head)")
+    ap.add_argument("--select", default="threshold", choices=["threshold", "topk-head", "topk-layer"],
+                    help="eviction rule of the mask stage: the paper's global threshold (default) or "
+                         "the fixed-budget variants of its ablation at the same kept fraction")
     ap.add_argument("--page-rows", type=int, default=0,
                     help="0 (default): packed contiguous output; a power of two >= 16: paged output "
                          "(kvzap_assign_pages + kvzap_compact_paged) and, for --stage attend, the "
@@ -379,8 +382,21 @@ def main() -> int:
         w = ly["w"]
         binding.kvzap_score(ly["hidden"], w["W1"], w["b1"], w["W2"], w["b2"], ly["scores"], ws_score)
 
+    ws_topk = torch.empty(max(binding.kvzap_workspace_bytes(binding.CALL_TOPK_THRESHOLD, B, T, 0, 1, H),
+                              binding.kvzap_workspace_bytes(binding.CALL_TOPK_THRESHOLD, B, T, 0, 0, H), 256),
+                          dtype=torch.uint8, device=dev)
+    tau_heads = torch.empty((B, H), dtype=torch.float32, device=dev)
+    k_head = int(round(wl.keep_fraction * max(T - wl.window, 0)))
+
     def mask(ly):
-        binding.kvzap_mask(ly["scores"], tau, wl.window, None, ly["idx"], ly["n"], ly["off"], ws)
+        if args.select == "threshold":
+            binding.kvzap_mask(ly["scores"], tau, wl.window, None, ly["idx"], ly["n"], ly["off"], ws)
+        else:       # fixed budget: the same kept fraction as a top-k per head / per layer
+            per_layer = args.select == "topk-layer"
+            binding.kvzap_topk_threshold(ly["scores"], wl.window, k_head * (H if per_layer else 1),
+                                         per_layer, None, tau_heads, ws_topk)
+            binding.kvzap_mask_per_head(ly["scores"], tau_heads, wl.window, None, ly["idx"],
+                                        ly["n"], ly["off"], ws)
 
     ws_pages = torch.empty(max(binding.kvzap_workspace_bytes(binding.CALL_ASSIGN_PAGES, B, 1, 0, 0, H), 256),
                            dtype=torch.uint8, device=dev)
@@ -503,6 +519,7 @@ def main() -> int:
                    "keep_fraction_target": wl.keep_fraction, "tau": tau,
                    "kept_fraction_measured": kept_fraction, "scorer": wl.scorer,
                    "output_layout": f"paged, {P} rows per page" if P else "packed contiguous",
+                   "selection": args.select,
                    "generator": f"torch {torch.__version__} cuda philox, seeds per layer"},
         "roofline": roofline,
         "roofline_compact": compact_roof,
