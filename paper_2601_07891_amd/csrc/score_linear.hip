@@ -106,13 +106,11 @@ int launch_linear(const void* hidden, const void* W, const void* b, float* score
   if (gpb < kWaves) gpb = kWaves;                     // at least one group per wavefront
   const long long blocks = (ngroups + gpb - 1) / gpb;
   const size_t lds = (size_t)H * ((size_t)Dh * 2 + 64);   // validated <= 160 KB by the caller
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(score_linear_kernel<kThreads>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-      return KVZAP_ERR_RUNTIME;
-    attr_set = true;
-  }
+  // once per process, which drives one GPU (thread-safe: a function-local static)
+  static const hipError_t attr_rc =
+      hipFuncSetAttribute(reinterpret_cast<const void*>(score_linear_kernel<kThreads>),
+      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  if (attr_rc != hipSuccess) return KVZAP_ERR_RUNTIME;
   score_linear_kernel<kThreads><<<dim3((unsigned)blocks), kThreads, lds, stream>>>(
       static_cast<const unsigned short*>(hidden), static_cast<const unsigned short*>(W),
       static_cast<const unsigned short*>(b), scores, rows, T, Dh, H, (int)gpb);

@@ -538,13 +538,11 @@ int launch_frag(const void* hidden, const void* W1, const void* b1, const void* 
   constexpr size_t ring = (size_t)kNS * TOK * 128;
   static_assert(ring >= (size_t)4 * 16 * TOK * sizeof(float), "reduction buffer fits");
   constexpr size_t lds = ring + (size_t)16 * (128 * UB) * 2 + (size_t)(128 * UB) * 4;   // + W2, b1
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(score_mlp_frag_kernel<UB, TB>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-      return KVZAP_ERR_RUNTIME;
-    attr_set = true;
-  }
+  // once per process, which drives one GPU (thread-safe: a function-local static)
+  static const hipError_t attr_rc =
+      hipFuncSetAttribute(reinterpret_cast<const void*>(score_mlp_frag_kernel<UB, TB>),
+      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (attr_rc != hipSuccess) return KVZAP_ERR_RUNTIME;
   const int M = 128 * UB;
   arrange_w1_kernel<<<512, 256, 0, stream>>>(static_cast<const u32x4*>(W1),
                                              static_cast<u32x4*>(workspace), M, Dh);
@@ -561,13 +559,11 @@ int launch_one(const void* hidden, const void* W1, const void* b1, const void* W
                const void* b2, float* scores, long long rows, int T, int Dh, int H,
                hipStream_t stream) {
   constexpr size_t lds = (size_t)(128 * UB + kTok) * 128;
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(score_mlp_kernel<UB>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-      return KVZAP_ERR_RUNTIME;
-    attr_set = true;
-  }
+  // once per process, which drives one GPU (thread-safe: a function-local static)
+  static const hipError_t attr_rc =
+      hipFuncSetAttribute(reinterpret_cast<const void*>(score_mlp_kernel<UB>),
+      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (attr_rc != hipSuccess) return KVZAP_ERR_RUNTIME;
   const long long blocks = (rows + kTok - 1) / kTok;
   score_mlp_kernel<UB><<<dim3((unsigned)blocks), kThreads, lds, stream>>>(
       static_cast<const unsigned short*>(hidden), static_cast<const unsigned short*>(W1),
