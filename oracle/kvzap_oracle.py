@@ -493,3 +493,46 @@ def topk_threshold(scores: np.ndarray, window: int, k: int, per_layer: bool,
             else:
                 tau[b, h] = np.sort(pop)[::-1][k - 1]
     return tau
+
+
+# --------------------------------------------------------------------------
+# the scores the surrogate is trained on (Sec. 3.1 Eq. 1: KVzip; Sec. 3.2
+# Eq. 3: KVzip+), on an extended prompt "prompt, instruction, repeated prompt"
+# --------------------------------------------------------------------------
+def teacher_log_scores(q: np.ndarray, k: np.ndarray, scale: float, T: int,
+                       vnorm: Optional[np.ndarray] = None,
+                       hnorm: Optional[np.ndarray] = None) -> np.ndarray:
+    """log s_i^+ for the T positions of the original prompt, per KV head.
+
+    q      float64 [H_Q, Tq, D]: queries of the Tq positions of the repeated
+           prompt, which sit at positions P0 .. P0+Tq-1 with P0 = Tk - Tq
+    k      float64 [H, Tk, D]: keys of all positions of the extended prompt
+    a_ji   causal softmax over the keys i' <= P0 + j of scale * q_j . k_i'
+    vnorm  [H, T] = ||W_O v_i|| (None = 1: Eq. 1), hnorm [Tq] = ||h_j|| (None = 1)
+    s_i = max over j and over the query heads g of the KV head's group of
+          a_ji * vnorm[h, i] / hnorm[j]                               (Eq. 3)
+    Returned in log space (what the surrogate regresses, Sec. 3.3), float64
+    [H, T]; requires T <= P0 so that every scored key is visible to every query.
+    """
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    HQ, Tq, D = q.shape
+    H, Tk, _ = k.shape
+    G = HQ // H
+    P0 = Tk - Tq
+    if G * H != HQ or P0 < 0 or not (0 <= T <= P0):
+        raise ValueError("shapes do not describe an extended prompt")
+    out = np.full((H, T), -np.inf)
+    lv = np.zeros((H, T)) if vnorm is None else np.log(np.asarray(vnorm, dtype=np.float64))
+    lh = np.zeros(Tq) if hnorm is None else np.log(np.asarray(hnorm, dtype=np.float64))
+    visible = np.arange(Tk)[None, :] <= (P0 + np.arange(Tq))[:, None]
+    for g in range(HQ):
+        h = g // G
+        s = (q[g] @ k[h].T) * scale                       # [Tq, Tk]
+        s = np.where(visible, s, -np.inf)
+        m = s.max(axis=1, keepdims=True)
+        lse = m + np.log(np.exp(s - m).sum(axis=1, keepdims=True))
+        log_a = s - lse                                   # log a_ji
+        cand = (log_a[:, :T] - lh[:, None]).max(axis=0)   # max over j
+        out[h] = np.maximum(out[h], cand)                 # max over the group
+    return out + lv
