@@ -64,7 +64,8 @@ typedef enum kvzap_call {
   KVZAP_CALL_DECODE_EVICT = 3,
   KVZAP_CALL_ATTEND_DECODE = 4,  /* pass T = max_rows, Dh = HQ, M = window (also for the paged form) */
   KVZAP_CALL_ASSIGN_PAGES = 5,   /* only B and H matter (pass T = 1) */
-  KVZAP_CALL_TOPK_THRESHOLD = 6  /* pass M = per_layer (0 or 1) */
+  KVZAP_CALL_TOPK_THRESHOLD = 6, /* pass M = per_layer (0 or 1) */
+  KVZAP_CALL_TEACHER_SCORES = 7  /* pass B = 1, T = prompt length, Dh = HQ, M = Tq */
 } kvzap_call;
 
 /* Text for a status code (host pointer to a static string, never NULL). */
@@ -363,6 +364,28 @@ int kvzap_decode_evict_paged(const void* hidden_new, const void* W1, const void*
                              float tau, int window, int B, int H, int D,
                              int32_t* error_flag,
                              void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * kvzap_teacher_scores -- the scores the surrogate is trained on, for one layer of one
+ * extended prompt "prompt, instruction, repeated prompt" (Sec. 3.1 Eq. 1: KVzip; Sec. 3.2
+ * Eq. 3: KVzip+), in log space (Sec. 3.3: the surrogate regresses log s+).
+ *
+ *   q      bf16 [HQ, Tq, D]  queries of the Tq positions of the repeated prompt, which sit
+ *                            at positions P0 .. P0+Tq-1 of the extended prompt, P0 = Tk - Tq
+ *   k      bf16 [H, Tk, D]   keys of all Tk positions
+ *   vnorm  fp32 [H, T] or NULL (= 1): ||W_O v_i|| for the T <= P0 prompt positions
+ *   hnorm  fp32 [Tq]   or NULL (= 1): ||h_j||
+ *   log_s  fp32 [H, T]: log max_{j, g in group(h)} a_ji * vnorm[h,i] / hnorm[j], where a is
+ *          the causal softmax of scale * q_gj . k_i' over the keys i' <= P0 + j and the
+ *          group of KV head h is its HQ/H query heads.  NULL norms give Eq. 1.
+ * Supported: D = 128, HQ a multiple of H.  bf16 products accumulated in fp32 on the matrix
+ * cores, softmax statistics in fp32; the maximum is taken on the logits, so no weight
+ * underflows.  Deterministic.  workspace:
+ * kvzap_workspace_bytes(KVZAP_CALL_TEACHER_SCORES, 1, T, Dh = HQ, M = Tq, H).
+ */
+int kvzap_teacher_scores(const void* q, const void* k, const float* vnorm, const float* hnorm,
+                         float scale, float* log_s, int H, int HQ, int Tq, int Tk, int T,
+                         int D, void* workspace, size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libkvzap.so")
 
 CALL_SCORE, CALL_MASK, CALL_COMPACT, CALL_DECODE_EVICT, CALL_ATTEND_DECODE = 0, 1, 2, 3, 4
-CALL_ASSIGN_PAGES, CALL_TOPK_THRESHOLD = 5, 6
+CALL_ASSIGN_PAGES, CALL_TOPK_THRESHOLD, CALL_TEACHER_SCORES = 5, 6, 7
 
 _c_void_p, _c_int, _c_float, _c_size_t, _c_int64 = (
     ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t, ctypes.c_int64)
@@ -31,6 +31,8 @@ SIGNATURES = {
     "kvzap_score": (_c_int, [_c_void_p] * 6 + [_c_int] * 5 + [_c_void_p, _c_size_t, _c_void_p]),
     "kvzap_mask": (_c_int, [_c_void_p, _c_float, _c_int, _c_void_p, _c_int, _c_int, _c_int,
                             _c_void_p, _c_void_p, _c_void_p, _c_void_p, _c_size_t, _c_void_p]),
+    "kvzap_teacher_scores": (_c_int, [_c_void_p] * 4 + [_c_float, _c_void_p] + [_c_int] * 6 +
+                             [_c_void_p, _c_size_t, _c_void_p]),
     "kvzap_topk_threshold": (_c_int, [_c_void_p, _c_int, _c_void_p, _c_int64, _c_int, _c_int, _c_int,
                                       _c_int, _c_void_p, _c_void_p, _c_size_t, _c_void_p]),
     "kvzap_mask_per_head": (_c_int, [_c_void_p, _c_void_p, _c_int, _c_void_p, _c_int, _c_int, _c_int,
@@ -552,3 +554,35 @@ def kvzap_mask_per_head(scores: torch.Tensor, tau: torch.Tensor, window: int,
     if rc != 0:
         raise KvzapError(rc, "kvzap_mask_per_head")
     return keep_idx, lengths, offsets
+
+
+def kvzap_teacher_scores(q: torch.Tensor, k: torch.Tensor, T: int, scale: float,
+                         vnorm: Optional[torch.Tensor] = None,
+                         hnorm: Optional[torch.Tensor] = None,
+                         log_s: Optional[torch.Tensor] = None,
+                         workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """q bf16 [HQ,Tq,D] (queries of the repeated prompt), k bf16 [H,Tk,D] (all keys of the
+    extended prompt), vnorm fp32 [H,T], hnorm fp32 [Tq] -> log scores fp32 [H,T]."""
+    bf = torch.bfloat16
+    _check(q, bf, "q"); _check(k, bf, "k")
+    _check(vnorm, torch.float32, "vnorm", True); _check(hnorm, torch.float32, "hnorm", True)
+    HQ, Tq, D = q.shape
+    H, Tk, Dk = k.shape
+    if Dk != D:
+        raise ValueError("q and k must have the same head dimension")
+    if vnorm is not None and tuple(vnorm.shape) != (H, T):
+        raise ValueError("vnorm must be [H,T]")
+    if hnorm is not None and hnorm.numel() != Tq:
+        raise ValueError("hnorm must have Tq entries")
+    if log_s is None:
+        log_s = torch.empty((H, T), dtype=torch.float32, device=q.device)
+    else:
+        _check(log_s, torch.float32, "log_s")
+    ws, ws_bytes = _workspace(kvzap_workspace_bytes(CALL_TEACHER_SCORES, 1, int(T), HQ, Tq, H),
+                              q.device, workspace)
+    rc = lib().kvzap_teacher_scores(_ptr(q), _ptr(k), _ptr(vnorm), _ptr(hnorm), float(scale),
+                                    _ptr(log_s), H, HQ, Tq, Tk, int(T), D, _ptr(ws), ws_bytes,
+                                    _stream(stream))
+    if rc != 0:
+        raise KvzapError(rc, "kvzap_teacher_scores")
+    return log_s

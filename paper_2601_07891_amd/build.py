@@ -13,7 +13,7 @@ OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libkvzap.so")
 CEILINGS_PATH = os.path.join(HERE, "kvzap_ceilings")
 SOURCES = ["api.hip", "mask.hip", "compact.hip", "score_linear.hip", "score_mlp.hip",
-           "decode.hip", "attend.hip", "paged.hip", "topk.hip"]
+           "decode.hip", "attend.hip", "paged.hip", "topk.hip", "teacher.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",

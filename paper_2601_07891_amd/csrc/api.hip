@@ -62,7 +62,8 @@ const char* kvzap_version(void) { return "0.1.0"; }
 
 size_t kvzap_workspace_bytes(int which_call, int B, int T, int Dh, int M, int H) {
   if (B <= 0 || H <= 0) return 0;
-  if (T <= 0 && which_call != KVZAP_CALL_ATTEND_DECODE) return 0;
+  if (T <= 0 && which_call != KVZAP_CALL_ATTEND_DECODE && which_call != KVZAP_CALL_TEACHER_SCORES)
+    return 0;
   switch (which_call) {
     case KVZAP_CALL_MASK:
       if ((long long)B * H > 65535) return 0;
@@ -76,6 +77,9 @@ size_t kvzap_workspace_bytes(int which_call, int B, int T, int Dh, int M, int H)
     case KVZAP_CALL_ATTEND_DECODE:   // T = max_rows, Dh = HQ, M = window
       if (check_attend_shape(B, H, Dh, T, M) != KVZAP_OK) return 0;
       return kvzap::attend_workspace_bytes(B, H, Dh, T, M);
+    case KVZAP_CALL_TEACHER_SCORES:       // T = prompt length, Dh = HQ, M = Tq
+      if (Dh <= 0 || M <= 0 || Dh % H != 0 || H > 65535) return 0;
+      return kvzap::teacher_workspace_bytes(H, Dh, M, T);
     case KVZAP_CALL_TOPK_THRESHOLD:
       if ((long long)B * H > 65535) return 0;
       return kvzap::topk_workspace_bytes(B, H, M != 0);
@@ -383,6 +387,23 @@ int kvzap_attend_decode_paged(const void* q, const void* K_pool, const void* V_p
                                      page_rows, num_pages, lengths, K_ring, V_ring, seq_pos, window,
                                      max_rows, scale, out, B, H, HQ, workspace,
                                      static_cast<hipStream_t>(stream));
+}
+
+int kvzap_teacher_scores(const void* q, const void* k, const float* vnorm, const float* hnorm,
+                         float scale, float* log_s, int H, int HQ, int Tq, int Tk, int T, int D,
+                         void* workspace, size_t workspace_bytes, void* stream) {
+  if (H <= 0 || HQ <= 0 || Tq <= 0 || Tk < Tq || T < 0 || D <= 0) return KVZAP_ERR_SHAPE;
+  if (HQ % H != 0 || T > Tk - Tq || scale != scale) return KVZAP_ERR_SHAPE;
+  if (D != 128 || H > 65535 || HQ > 65535 || (long long)Tk > (1ll << 30)) return KVZAP_ERR_UNSUPPORTED;
+  if (!q || !k || (T > 0 && !log_s)) return KVZAP_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(vnorm) || !aligned16(hnorm) || !aligned16(log_s))
+    return KVZAP_ERR_ALIGN;
+  if (T == 0) return KVZAP_OK;                              // nothing to score
+  if (!workspace || !aligned256(workspace) ||
+      workspace_bytes < kvzap::teacher_workspace_bytes(H, HQ, Tq, T))
+    return KVZAP_ERR_WORKSPACE;
+  return kvzap::launch_teacher_scores(q, k, vnorm, hnorm, scale, log_s, H, HQ, Tq, Tk, T, workspace,
+                                      static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

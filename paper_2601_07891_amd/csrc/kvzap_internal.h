@@ -42,6 +42,11 @@ int launch_topk_threshold(const float* scores, int window, const int32_t* seq_le
                           hipStream_t stream);
 size_t topk_workspace_bytes(int B, int H, bool per_layer);
 
+int launch_teacher_scores(const void* q, const void* k, const float* vnorm, const float* hnorm,
+                          float scale, float* log_s, int H, int HQ, int Tq, int Tk, int T,
+                          void* workspace, hipStream_t stream);
+size_t teacher_workspace_bytes(int H, int HQ, int Tq, int T);
+
 int launch_compact(const void* K, const void* V, const int32_t* keep_idx,
                    const int32_t* lengths, const int64_t* offsets, void* K_out,
                    void* V_out, int64_t cap_rows, int BH, int T, int D,
