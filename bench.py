@@ -286,6 +286,84 @@ def bench_attend(wl, args) -> int:
     return 0
 
 
+def bench_teacher(wl, args) -> int:
+    """Teacher scores (KVzip+ of Eq. 3) of one layer of one extended prompt: a prompt of
+    --teacher-tokens tokens, a 32-token instruction, the prompt repeated (non-default stage)."""
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    H, D, HQ = wl.H, wl.D, args.query_heads
+    T = Tq = args.teacher_tokens
+    instr = 32
+    Tk = T + instr + Tq
+    nbuf = 3
+    g = torch.Generator(device=dev).manual_seed(wl.seed)
+    bufs = []
+    for _ in range(nbuf):
+        q = torch.randn((HQ, Tq, D), generator=g, device=dev).bfloat16()
+        k = torch.randn((H, Tk, D), generator=g, device=dev).bfloat16()
+        vn = torch.rand((H, T), generator=g, device=dev) * 3.0 + 0.1
+        hn = torch.rand((Tq,), generator=g, device=dev) * 5.0 + 0.5
+        bufs.append((q, k, vn, hn))
+    scale = D ** -0.5
+    out = torch.empty((H, T), dtype=torch.float32, device=dev)
+    ws = torch.empty(binding.kvzap_workspace_bytes(binding.CALL_TEACHER_SCORES, 1, T, HQ, Tq, H),
+                     dtype=torch.uint8, device=dev)
+
+    def step(i):
+        q, k, vn, hn = bufs[i % nbuf]
+        binding.kvzap_teacher_scores(q, k, T, scale, vn, hn, out, ws)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for i in range(args.steps):
+        step(i)
+    ev1.record()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_call = ev0.elapsed_time(ev1) / args.steps
+    P0 = Tk - Tq
+    pairs1 = sum(P0 + j + 1 for j in range(Tq))              # visible (query, key) pairs, row pass
+    flops = 2 * D * HQ * (pairs1 + Tq * T)                   # both passes compute q.k once per pair
+    achieved = flops / (ms_call * 1e-3) / 1e12
+
+    from oracle import kvzap_oracle as O       # cpu_baseline leg only
+    q, k, vn, hn = bufs[0]
+    G = HQ // H
+    c0 = time.perf_counter()
+    ref = O.teacher_log_scores(synth.f64(q[:G]), synth.f64(k[:1]), scale, T, synth.f64(vn[:1]),
+                               synth.f64(hn))
+    c1 = time.perf_counter()
+    got = binding.kvzap_teacher_scores(q, k, T, scale, vn, hn)
+    err = float(np.abs(got[:1].double().cpu().numpy() - ref).max())
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    print(json.dumps({
+        "metric": "teacher-score prompt tokens/sec per layer (KVzip+ scores, all KV heads)",
+        "value": T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"teacher scores, prompt {T} + instruction {instr} + repeat {Tq}",
+                   "kv_heads": H, "query_heads": HQ, "head_dim": D},
+        "ms_per_call": ms_call,
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "kernel": "teacher_rowstat_kernel + teacher_colmax_kernel (one interval)",
+                     "algorithmic_flops_per_launch": flops},
+        "cpu_baseline": {"value": T / (c1 - c0) / H, "unit": "tokens/s", "cores": int(threads),
+                         "kind": "oracle",
+                         "sample": f"KV head 0 ({G} query heads) of the same prompt, float64 numpy; "
+                                   f"value scaled to all {H} KV heads",
+                         "max_abs_diff_vs_gpu": err}}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -310,9 +388,12 @@ def main() -> int:
                          "paged attention over a shuffled page pool")
     ap.add_argument("--graph", action="store_true",
                     help="decode workload: also time the step replayed from a HIP graph")
-    ap.add_argument("--stage", default="evict", choices=["evict", "attend"],
+    ap.add_argument("--stage", default="evict", choices=["evict", "attend", "teacher"],
                     help="decode workload: time the eviction step (default) or the attention "
-                         "over the ragged cache it maintains")
+                         "over the ragged cache it maintains; 'teacher' (any config): the "
+                         "KVzip+ training scores of one extended prompt")
+    ap.add_argument("--teacher-tokens", type=int, default=8192,
+                    help="--stage teacher: prompt length (the extended prompt is twice that + 32)")
     ap.add_argument("--query-heads", type=int, default=32,
                     help="decode attention: number of query heads (Qwen3-8B: 32 over 8 KV heads)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -328,6 +409,8 @@ def main() -> int:
         return 2
     binding.lib()                                   # fail loudly if the library is not built
     wl = synth.CONFIGS[args.config]
+    if args.stage == "teacher":
+        return bench_teacher(wl, args)
     if wl.T == 1:
         return bench_attend(wl, args) if args.stage == "attend" else bench_decode(wl, args)
     L = args.layers or wl.L

@@ -378,8 +378,8 @@ int kvzap_decode_evict_paged(const void* hidden_new, const void* W1, const void*
  *   log_s  fp32 [H, T]: log max_{j, g in group(h)} a_ji * vnorm[h,i] / hnorm[j], where a is
  *          the causal softmax of scale * q_gj . k_i' over the keys i' <= P0 + j and the
  *          group of KV head h is its HQ/H query heads.  NULL norms give Eq. 1.
- * Supported: D = 128, HQ a multiple of H.  bf16 products accumulated in fp32 on the matrix
- * cores, softmax statistics in fp32; the maximum is taken on the logits, so no weight
+ * Supported: D = 128, HQ a multiple of H, scale > 0.  bf16 products accumulated in fp32 on the
+ * matrix cores, softmax statistics in fp32; the maximum is taken on the logits, so no weight
  * underflows.  Deterministic.  workspace:
  * kvzap_workspace_bytes(KVZAP_CALL_TEACHER_SCORES, 1, T, Dh = HQ, M = Tq, H).
  */

@@ -393,7 +393,7 @@ int kvzap_teacher_scores(const void* q, const void* k, const float* vnorm, const
                          float scale, float* log_s, int H, int HQ, int Tq, int Tk, int T, int D,
                          void* workspace, size_t workspace_bytes, void* stream) {
   if (H <= 0 || HQ <= 0 || Tq <= 0 || Tk < Tq || T < 0 || D <= 0) return KVZAP_ERR_SHAPE;
-  if (HQ % H != 0 || T > Tk - Tq || scale != scale) return KVZAP_ERR_SHAPE;
+  if (HQ % H != 0 || T > Tk - Tq || !(scale > 0.0f)) return KVZAP_ERR_SHAPE;   // also NaN
   if (D != 128 || H > 65535 || HQ > 65535 || (long long)Tk > (1ll << 30)) return KVZAP_ERR_UNSUPPORTED;
   if (!q || !k || (T > 0 && !log_s)) return KVZAP_ERR_NULL;
   if (!aligned16(q) || !aligned16(k) || !aligned16(vnorm) || !aligned16(hnorm) || !aligned16(log_s))

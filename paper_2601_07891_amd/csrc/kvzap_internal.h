@@ -32,6 +32,50 @@ __device__ __forceinline__ unsigned short float_to_bf16_bits(float f) {
   return (unsigned short)(u >> 16);
 }
 
+// ---- asynchronous global -> LDS loads with hand-counted completion ----
+// Wait until at most N vector-memory operations of this wavefront are outstanding
+// (they complete in issue order).  Written as asm with a memory clobber so that the
+// compiler keeps every load that precedes it in the source before it.
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// Workgroup barrier that does NOT wait for outstanding vector-memory traffic (a
+// __syncthreads() would drain the prefetched tiles).  The caller has already
+// waited for the loads it needs; every LDS read issued before this point has been
+// consumed by an MFMA, so it has completed.  The "memory" clobber keeps the
+// compiler from moving LDS accesses across it.
+__device__ __forceinline__ void block_barrier_no_drain() {
+  asm volatile("s_barrier" ::: "memory");
+}
+
+// One load-to-LDS instruction: every lane fetches 16 bytes from its own global address and
+// the wavefront's 64 pieces land at LDS bytes [lds_base, lds_base + 1024) in lane order.
+// Issued as inline asm on purpose: the compiler tracks the builtin form as an LDS write
+// that may alias every later LDS read and then waits for ALL outstanding vector-memory
+// operations before those reads, which would undo the multi-tile prefetch.  Completion is
+// tracked by hand with wait_vmcnt(); the compiler's own vmcnt waits (for ordinary loads)
+// do not know about these operations and therefore only ever wait longer, never shorter.
+// M0 (the LDS base of the instruction) is written here and used nowhere else in the kernel.
+__device__ __forceinline__ void load_to_lds_b128(const void* gptr, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+               ::"s"(lds_base), "v"(gptr)
+               : "memory");
+}
+
+__device__ __forceinline__ unsigned lds_address(const void* p) {
+  return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+
+// The 4-byte form: lane i's dword lands at LDS byte lds_base + 4*i.
+__device__ __forceinline__ void load_to_lds_b32(const void* gptr, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off"
+               ::"s"(lds_base), "v"(gptr)
+               : "memory");
+}
+
 // launchers (each returns a kvzap_status); arguments are already validated
 int launch_mask(const float* scores, float tau, const float* tau_head, int window,
                 const int32_t* seq_lens, int B, int H, int T, int32_t* keep_idx,
