@@ -65,7 +65,8 @@ typedef enum kvzap_call {
   KVZAP_CALL_ATTEND_DECODE = 4,  /* pass T = max_rows, Dh = HQ, M = window (also for the paged form) */
   KVZAP_CALL_ASSIGN_PAGES = 5,   /* only B and H matter (pass T = 1) */
   KVZAP_CALL_TOPK_THRESHOLD = 6, /* pass M = per_layer (0 or 1) */
-  KVZAP_CALL_TEACHER_SCORES = 7  /* pass B = 1, T = prompt length, Dh = HQ, M = Tq */
+  KVZAP_CALL_TEACHER_SCORES = 7, /* pass B = 1, T = prompt length, Dh = HQ, M = Tq */
+  KVZAP_CALL_COMPRESS = 8        /* as KVZAP_CALL_SCORE: the larger of the score and mask needs */
 } kvzap_call;
 
 /* Text for a status code (host pointer to a static string, never NULL). */
@@ -184,6 +185,20 @@ int kvzap_compact(const void* K, const void* V, const int32_t* keep_idx,
                   const int32_t* lengths, const int64_t* offsets,
                   void* K_out, void* V_out, int64_t cap_rows,
                   int B, int H, int T, int D, void* stream);
+
+/*
+ * kvzap_compress -- the whole of Algorithm 1 for one layer in one call: kvzap_score, then
+ * kvzap_mask, then kvzap_compact on the same stream, with the arguments of those three
+ * calls (`scores` receives the surrogate's scores and is part of the result).  Identical,
+ * bit for bit, to making the three calls; validation of all three happens before the
+ * first launch.  workspace: kvzap_workspace_bytes(KVZAP_CALL_COMPRESS, B, T, Dh, M, H).
+ */
+int kvzap_compress(const void* hidden, const void* W1, const void* b1, const void* W2,
+                   const void* b2, const void* K, const void* V, float tau, int window,
+                   const int32_t* seq_lens, float* scores, int32_t* keep_idx,
+                   int32_t* lengths, int64_t* offsets, void* K_out, void* V_out,
+                   int64_t cap_rows, int B, int T, int Dh, int M, int H, int D,
+                   void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * kvzap_decode_evict -- one decoding step of one layer for B sequences

@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libkvzap.so")
 
 CALL_SCORE, CALL_MASK, CALL_COMPACT, CALL_DECODE_EVICT, CALL_ATTEND_DECODE = 0, 1, 2, 3, 4
-CALL_ASSIGN_PAGES, CALL_TOPK_THRESHOLD, CALL_TEACHER_SCORES = 5, 6, 7
+CALL_ASSIGN_PAGES, CALL_TOPK_THRESHOLD, CALL_TEACHER_SCORES, CALL_COMPRESS = 5, 6, 7, 8
 
 _c_void_p, _c_int, _c_float, _c_size_t, _c_int64 = (
     ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t, ctypes.c_int64)
@@ -31,6 +31,8 @@ SIGNATURES = {
     "kvzap_score": (_c_int, [_c_void_p] * 6 + [_c_int] * 5 + [_c_void_p, _c_size_t, _c_void_p]),
     "kvzap_mask": (_c_int, [_c_void_p, _c_float, _c_int, _c_void_p, _c_int, _c_int, _c_int,
                             _c_void_p, _c_void_p, _c_void_p, _c_void_p, _c_size_t, _c_void_p]),
+    "kvzap_compress": (_c_int, [_c_void_p] * 7 + [_c_float, _c_int] + [_c_void_p] * 7 + [_c_int64] +
+                       [_c_int] * 6 + [_c_void_p, _c_size_t, _c_void_p]),
     "kvzap_teacher_scores": (_c_int, [_c_void_p] * 4 + [_c_float, _c_void_p] + [_c_int] * 6 +
                              [_c_void_p, _c_size_t, _c_void_p]),
     "kvzap_topk_threshold": (_c_int, [_c_void_p, _c_int, _c_void_p, _c_int64, _c_int, _c_int, _c_int,
@@ -586,3 +588,37 @@ def kvzap_teacher_scores(q: torch.Tensor, k: torch.Tensor, T: int, scale: float,
     if rc != 0:
         raise KvzapError(rc, "kvzap_teacher_scores")
     return log_s
+
+
+def kvzap_compress(hidden: torch.Tensor, W1: torch.Tensor, b1, W2, b2, K: torch.Tensor,
+                   V: torch.Tensor, tau: float, window: int,
+                   seq_lens: Optional[torch.Tensor] = None,
+                   workspace: Optional[torch.Tensor] = None, stream=None):
+    """Algorithm 1 for one layer in one library call.  Returns (scores, keep_idx, lengths,
+    offsets, K_out, V_out) as the three separate calls would."""
+    bf = torch.bfloat16
+    _check(hidden, bf, "hidden"); _check(W1, bf, "W1"); _check(b1, bf, "b1", True)
+    _check(W2, bf, "W2", True); _check(b2, bf, "b2", True); _check(K, bf, "K"); _check(V, bf, "V")
+    _check(seq_lens, torch.int32, "seq_lens", True)
+    B, T, Dh = hidden.shape
+    M = W1.shape[0] if W2 is not None else 0
+    H = W2.shape[0] if W2 is not None else W1.shape[0]
+    if tuple(K.shape[:3]) != (B, H, T) or K.shape != V.shape:
+        raise ValueError("K and V must be [B,H,T,D]")
+    D = K.shape[3]
+    dev = hidden.device
+    scores = torch.empty((B, H, T), dtype=torch.float32, device=dev)
+    keep_idx = torch.empty(B * H * T, dtype=torch.int32, device=dev)
+    lengths = torch.empty((B, H), dtype=torch.int32, device=dev)
+    offsets = torch.empty(B * H + 1, dtype=torch.int64, device=dev)
+    K_out = torch.empty((B * H * T, D), dtype=bf, device=dev)
+    V_out = torch.empty((B * H * T, D), dtype=bf, device=dev)
+    ws, ws_bytes = _workspace(max(kvzap_workspace_bytes(CALL_COMPRESS, B, T, Dh, M, H), 256), dev,
+                              workspace)
+    rc = lib().kvzap_compress(_ptr(hidden), _ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2), _ptr(K), _ptr(V),
+                              float(tau), int(window), _ptr(seq_lens), _ptr(scores), _ptr(keep_idx),
+                              _ptr(lengths), _ptr(offsets), _ptr(K_out), _ptr(V_out), B * H * T,
+                              B, T, Dh, M, H, D, _ptr(ws), ws_bytes, _stream(stream))
+    if rc != 0:
+        raise KvzapError(rc, "kvzap_compress")
+    return scores, keep_idx, lengths, offsets, K_out, V_out

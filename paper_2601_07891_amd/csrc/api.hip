@@ -74,6 +74,12 @@ size_t kvzap_workspace_bytes(int which_call, int B, int T, int Dh, int M, int H)
     case KVZAP_CALL_SCORE:
       if (check_scorer_shape(Dh, M, H) != KVZAP_OK) return 0;
       return M > 0 ? kvzap::align_up((size_t)M * Dh * 2, 256) : 0;   // W1 in fragment order
+    case KVZAP_CALL_COMPRESS: {
+      if (check_scorer_shape(Dh, M, H) != KVZAP_OK || (long long)B * H > 65535) return 0;
+      const size_t a = M > 0 ? kvzap::align_up((size_t)M * Dh * 2, 256) : 0;
+      const size_t b = mask_workspace(B, H, T);
+      return a > b ? a : b;
+    }
     case KVZAP_CALL_ATTEND_DECODE:   // T = max_rows, Dh = HQ, M = window
       if (check_attend_shape(B, H, Dh, T, M) != KVZAP_OK) return 0;
       return kvzap::attend_workspace_bytes(B, H, Dh, T, M);
@@ -92,9 +98,11 @@ size_t kvzap_workspace_bytes(int which_call, int B, int T, int Dh, int M, int H)
   }
 }
 
-int kvzap_score(const void* hidden, const void* W1, const void* b1, const void* W2,
-                const void* b2, float* scores, int B, int T, int Dh, int M, int H,
-                void* workspace, size_t workspace_bytes, void* stream) {
+namespace {
+// argument checks of kvzap_score / kvzap_mask / kvzap_compact, shared with kvzap_compress
+int check_score(const void* hidden, const void* W1, const void* b1, const void* W2,
+                const void* b2, const float* scores, int B, int T, int Dh, int M, int H,
+                const void* workspace, size_t workspace_bytes) {
   if (B < 0 || T < 0) return KVZAP_ERR_SHAPE;
   const int rc = check_scorer_shape(Dh, M, H);
   if (rc != KVZAP_OK) return rc;
@@ -106,18 +114,16 @@ int kvzap_score(const void* hidden, const void* W1, const void* b1, const void* 
   if (!aligned16(hidden) || !aligned16(W1) || !aligned16(scores) || !aligned16(W2) ||
       !aligned16(b1) || !aligned16(b2))
     return KVZAP_ERR_ALIGN;
-  hipStream_t s = static_cast<hipStream_t>(stream);
   if (M > 0) {
     const size_t need = kvzap::align_up((size_t)M * Dh * 2, 256);
     if (!workspace || !aligned256(workspace) || workspace_bytes < need) return KVZAP_ERR_WORKSPACE;
-    return kvzap::launch_score_mlp(hidden, W1, b1, W2, b2, scores, B, T, Dh, M, H, workspace, s);
   }
-  return kvzap::launch_score_linear(hidden, W1, b1, scores, B, T, Dh, H, s);
+  return KVZAP_OK;
 }
 
-int kvzap_mask(const float* scores, float tau, int window, const int32_t* seq_lens, int B,
-               int H, int T, int32_t* keep_idx, int32_t* lengths, int64_t* offsets,
-               void* workspace, size_t workspace_bytes, void* stream) {
+int check_mask(const float* scores, float tau, int window, const int32_t* seq_lens, int B, int H,
+               int T, const int32_t* keep_idx, const int32_t* lengths, const int64_t* offsets,
+               const void* workspace, size_t workspace_bytes) {
   if (B <= 0 || H <= 0 || T <= 0 || window < 0) return KVZAP_ERR_SHAPE;
   if (tau != tau) return KVZAP_ERR_SHAPE;                 // NaN threshold
   if ((long long)B * H > 65535) return KVZAP_ERR_UNSUPPORTED;
@@ -127,8 +133,58 @@ int kvzap_mask(const float* scores, float tau, int window, const int32_t* seq_le
     return KVZAP_ERR_ALIGN;
   if (!workspace || !aligned256(workspace) || workspace_bytes < mask_workspace(B, H, T))
     return KVZAP_ERR_WORKSPACE;
-  return kvzap::launch_mask(scores, tau, nullptr, window, seq_lens, B, H, T, keep_idx, lengths, offsets,
-                            workspace, static_cast<hipStream_t>(stream));
+  return KVZAP_OK;
+}
+
+int check_compact(const void* K, const void* V, const int32_t* keep_idx, const int32_t* lengths,
+                  const int64_t* offsets, const void* K_out, const void* V_out, int64_t cap_rows,
+                  int B, int H, int T, int D) {
+  if (B <= 0 || H <= 0 || T <= 0 || D <= 0 || cap_rows < 0) return KVZAP_ERR_SHAPE;
+  if (D % 8 != 0 || D > kMaxD || (long long)B * H > 65535) return KVZAP_ERR_UNSUPPORTED;
+  if (!K || !V || !keep_idx || !lengths || !offsets || !K_out || !V_out) return KVZAP_ERR_NULL;
+  if (!aligned16(K) || !aligned16(V) || !aligned16(keep_idx) || !aligned16(lengths) ||
+      !aligned16(offsets) || !aligned16(K_out) || !aligned16(V_out))
+    return KVZAP_ERR_ALIGN;
+  // the gather is not an in-place operation
+  const size_t in_bytes = (size_t)B * H * T * D * 2, out_bytes = (size_t)cap_rows * D * 2;
+  auto overlaps = [](const void* a, size_t na, const void* b, size_t nb) {
+    const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+    return x < y + nb && y < x + na;
+  };
+  if (overlaps(K, in_bytes, K_out, out_bytes) || overlaps(V, in_bytes, K_out, out_bytes) ||
+      overlaps(K, in_bytes, V_out, out_bytes) || overlaps(V, in_bytes, V_out, out_bytes) ||
+      overlaps(K_out, out_bytes, V_out, out_bytes))
+    return KVZAP_ERR_SHAPE;
+  return KVZAP_OK;
+}
+
+int run_score(const void* hidden, const void* W1, const void* b1, const void* W2, const void* b2,
+              float* scores, int B, int T, int Dh, int M, int H, void* workspace, hipStream_t s) {
+  if ((long long)B * T == 0) return KVZAP_OK;
+  if (M > 0)
+    return kvzap::launch_score_mlp(hidden, W1, b1, W2, b2, scores, B, T, Dh, M, H, workspace, s);
+  return kvzap::launch_score_linear(hidden, W1, b1, scores, B, T, Dh, H, s);
+}
+}  // namespace
+
+int kvzap_score(const void* hidden, const void* W1, const void* b1, const void* W2,
+                const void* b2, float* scores, int B, int T, int Dh, int M, int H,
+                void* workspace, size_t workspace_bytes, void* stream) {
+  const int rc = check_score(hidden, W1, b1, W2, b2, scores, B, T, Dh, M, H, workspace,
+                             workspace_bytes);
+  if (rc != KVZAP_OK) return rc;
+  return run_score(hidden, W1, b1, W2, b2, scores, B, T, Dh, M, H, workspace,
+                   static_cast<hipStream_t>(stream));
+}
+
+int kvzap_mask(const float* scores, float tau, int window, const int32_t* seq_lens, int B,
+               int H, int T, int32_t* keep_idx, int32_t* lengths, int64_t* offsets,
+               void* workspace, size_t workspace_bytes, void* stream) {
+  const int rc = check_mask(scores, tau, window, seq_lens, B, H, T, keep_idx, lengths, offsets,
+                            workspace, workspace_bytes);
+  if (rc != KVZAP_OK) return rc;
+  return kvzap::launch_mask(scores, tau, nullptr, window, seq_lens, B, H, T, keep_idx, lengths,
+                            offsets, workspace, static_cast<hipStream_t>(stream));
 }
 
 int kvzap_mask_per_head(const float* scores, const float* tau, int window,
@@ -165,25 +221,36 @@ int kvzap_topk_threshold(const float* scores, int window, const int32_t* seq_len
 int kvzap_compact(const void* K, const void* V, const int32_t* keep_idx,
                   const int32_t* lengths, const int64_t* offsets, void* K_out, void* V_out,
                   int64_t cap_rows, int B, int H, int T, int D, void* stream) {
-  if (B <= 0 || H <= 0 || T <= 0 || D <= 0 || cap_rows < 0) return KVZAP_ERR_SHAPE;
-  if (D % 8 != 0 || D > kMaxD || (long long)B * H > 65535) return KVZAP_ERR_UNSUPPORTED;
-  if (!K || !V || !keep_idx || !lengths || !offsets || !K_out || !V_out) return KVZAP_ERR_NULL;
-  if (!aligned16(K) || !aligned16(V) || !aligned16(keep_idx) || !aligned16(lengths) ||
-      !aligned16(offsets) || !aligned16(K_out) || !aligned16(V_out))
-    return KVZAP_ERR_ALIGN;
-  {  // the gather is not an in-place operation
-    const size_t in_bytes = (size_t)B * H * T * D * 2, out_bytes = (size_t)cap_rows * D * 2;
-    auto overlaps = [](const void* a, size_t na, const void* b, size_t nb) {
-      const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
-      return x < y + nb && y < x + na;
-    };
-    if (overlaps(K, in_bytes, K_out, out_bytes) || overlaps(V, in_bytes, K_out, out_bytes) ||
-        overlaps(K, in_bytes, V_out, out_bytes) || overlaps(V, in_bytes, V_out, out_bytes) ||
-        overlaps(K_out, out_bytes, V_out, out_bytes))
-      return KVZAP_ERR_SHAPE;
-  }
+  const int rc = check_compact(K, V, keep_idx, lengths, offsets, K_out, V_out, cap_rows, B, H, T, D);
+  if (rc != KVZAP_OK) return rc;
   return kvzap::launch_compact(K, V, keep_idx, lengths, offsets, K_out, V_out, cap_rows, B * H,
                                T, D, static_cast<hipStream_t>(stream));
+}
+
+int kvzap_compress(const void* hidden, const void* W1, const void* b1, const void* W2,
+                   const void* b2, const void* K, const void* V, float tau, int window,
+                   const int32_t* seq_lens, float* scores, int32_t* keep_idx, int32_t* lengths,
+                   int64_t* offsets, void* K_out, void* V_out, int64_t cap_rows, int B, int T,
+                   int Dh, int M, int H, int D, void* workspace, size_t workspace_bytes,
+                   void* stream) {
+  // all three sets of checks before anything is launched (the mask's demand B, T > 0)
+  int rc = check_mask(scores, tau, window, seq_lens, B, H, T, keep_idx, lengths, offsets, workspace,
+                      workspace_bytes);
+  if (rc == KVZAP_OK)
+    rc = check_score(hidden, W1, b1, W2, b2, scores, B, T, Dh, M, H, workspace, workspace_bytes);
+  if (rc == KVZAP_OK)
+    rc = check_compact(K, V, keep_idx, lengths, offsets, K_out, V_out, cap_rows, B, H, T, D);
+  if (rc != KVZAP_OK) return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  // the score workspace (W1 in fragment order) is dead once the scorer has run, the mask
+  // then reuses the same bytes on the same stream
+  rc = run_score(hidden, W1, b1, W2, b2, scores, B, T, Dh, M, H, workspace, s);
+  if (rc != KVZAP_OK) return rc;
+  rc = kvzap::launch_mask(scores, tau, nullptr, window, seq_lens, B, H, T, keep_idx, lengths,
+                          offsets, workspace, s);
+  if (rc != KVZAP_OK) return rc;
+  return kvzap::launch_compact(K, V, keep_idx, lengths, offsets, K_out, V_out, cap_rows, B * H, T,
+                               D, s);
 }
 
 int kvzap_decode_evict(const void* hidden_new, const void* W1, const void* b1, const void* W2,

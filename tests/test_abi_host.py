@@ -130,6 +130,37 @@ def test_compact_argument_errors(lib):
     assert call(6, big) == ERR["shape"]               # V_out aliases K_out
 
 
+def test_compress_argument_errors(lib):
+    # the one-call form refuses whatever any of its three stages refuses, before launching
+    f = lib.kvzap_compress
+    q = lib.kvzap_workspace_bytes
+    ws = q(binding.CALL_COMPRESS, 1, 1024, 4096, 512, 8)
+    assert ws == max(q(binding.CALL_SCORE, 1, 1024, 4096, 512, 8), q(binding.CALL_MASK, 1, 1024, 0, 0, 8))
+    assert q(binding.CALL_COMPRESS, 1, 1024, 4096, 0, 8) == q(binding.CALL_MASK, 1, 1024, 0, 0, 8)
+    big = 1 << 40
+    ok = dict(hidden=P, W1=P, b1=None, W2=P, b2=None, K=P + (1 << 30), V=P + (2 << 30), tau=0.0,
+              window=128, seq=None, scores=P, idx=P, lens=P, offs=P, Ko=big, Vo=big + (1 << 30),
+              cap=8192, B=1, T=1024, Dh=4096, M=512, H=8, D=128, ws=0x20000, wsb=ws, stream=None)
+    order = list(ok)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(*[a[k] for k in order])
+
+    assert call(hidden=None) == ERR["null"]
+    assert call(K=None) == ERR["null"]
+    assert call(idx=None) == ERR["null"]
+    assert call(W2=None) == ERR["null"]
+    assert call(T=0) == ERR["shape"]
+    assert call(tau=float("nan")) == ERR["shape"]
+    assert call(M=500) == ERR["unsupported"]
+    assert call(D=100) == ERR["unsupported"]
+    assert call(V=P + 6) == ERR["align"]
+    assert call(Ko=P + (1 << 30)) == ERR["shape"]      # K_out aliases K
+    assert call(wsb=ws - 1) == ERR["workspace"]
+    assert call(ws=None) == ERR["workspace"]
+
+
 def test_decode_argument_errors(lib):
     f = lib.kvzap_decode_evict
     ws = lib.kvzap_workspace_bytes(binding.CALL_DECODE_EVICT, 4, 1, 4096, 512, 8)

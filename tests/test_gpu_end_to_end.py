@@ -68,3 +68,29 @@ def test_config4_shape_reduced_batched():
 def test_batched_right_padded():
     wl = synth.with_size(synth.CONFIGS["c2_llama8b_32k_mlp"], B=3, T=700)
     _check(wl, seq_lens=[700, 401, 128])
+
+
+@pytest.mark.parametrize("name,T,padded", [("c1_t1k_linear", 1024, False),
+                                           ("c2_llama8b_32k_mlp", 5000 + 19, False),
+                                           ("c4_qwen32b_4x64k_linear", 700, True)])
+def test_compress_is_the_three_calls(name, T, padded):
+    # Algorithm 1 through the one-call entry point: bit-identical to score, mask, compact
+    wl = synth.with_size(synth.CONFIGS[name], L=1, T=T)
+    if padded:
+        wl = synth.with_size(wl, B=3)
+    w = synth.make_weights(wl); hid = synth.make_hidden(wl); K, V = synth.make_kv(wl)
+    seq_lens = [T, T // 2 + 1, 1][:wl.B] if padded else None
+    sl = None if seq_lens is None else torch.tensor(seq_lens, dtype=torch.int32, device=DEV)
+    d = {k: (None if v is None else v.to(DEV)) for k, v in w.items()}
+    tau = float(binding.kvzap_score(hid.to(DEV), d["W1"], d["b1"], d["W2"], d["b2"]).median())
+    want = _pipeline(wl, hid, K, V, w, tau, seq_lens)
+    got = binding.kvzap_compress(hid.to(DEV), d["W1"], d["b1"], d["W2"], d["b2"], K.to(DEV),
+                                 V.to(DEV), tau, wl.window, sl)
+    torch.cuda.synchronize()
+    kept = int(parity.to_np(want[3])[-1])
+    assert 0 < kept < wl.B * wl.H * wl.T
+    assert torch.equal(got[0], want[0])
+    assert torch.equal(got[2], want[2]) and torch.equal(got[3], want[3])
+    assert torch.equal(got[1][:kept], want[1][:kept])
+    assert torch.equal(got[4][:kept].view(torch.int16), want[4][:kept].view(torch.int16))
+    assert torch.equal(got[5][:kept].view(torch.int16), want[5][:kept].view(torch.int16))
