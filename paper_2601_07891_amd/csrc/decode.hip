@@ -9,7 +9,7 @@
 //      v_mfma_f32_32x32x16_bf16 on operands loaded straight from global memory
 //      and write fp32 partial sums (fixed order -> deterministic).
 //   2. decode_finish  : one block per sequence sums the K-slices, applies bias,
-//      GELU and the M -> H projection in fp32, then performs the O(1)-row cache
+//      GELU and the M -> H projection in fp32, and performs the O(1)-row cache
 //      update of its H heads.  For the linear surrogate step 1 is skipped and the
 //      block computes the H dot products itself.
 // State layout: an append-only ascending prefix per (b,h) plus a `window`-row
@@ -97,170 +97,234 @@ __global__ __launch_bounds__(kPThreads) void decode_partial_kernel(
 }
 
 constexpr int kFThreads = 256;
+constexpr int kFWaves = kFThreads / 64;
+constexpr int kHeadsPerWave = 4;     // H <= 16: head h belongs to wavefront h % 4
+constexpr int kUnitRounds = 2;       // M <= 1024: a lane covers 8 hidden units per round
 
+// low / high bf16 of a 32-bit word as fp32
+__device__ __forceinline__ float bf16_lo(unsigned int u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(unsigned int u) { return __uint_as_float(u & 0xffff0000u); }
+
+// sum over the 8 bf16 pairs of two 16-byte operands
+__device__ __forceinline__ float dot8_bf16(const u32x4& x, const u32x4& y) {
+  float s = 0.f;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    s += bf16_lo(x[e]) * bf16_lo(y[e]);
+    s += bf16_hi(x[e]) * bf16_hi(y[e]);
+  }
+  return s;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+// The step is a chain of dependent memory round trips, so the kernel is written around
+// their number, not around arithmetic: every load whose address does not depend on loaded
+// data is issued at entry without a branch around it (out-of-range lanes read a clamped
+// address and discard the value), the loads that need the position follow as soon as it
+// arrives, and one barrier separates them from the stores.  With a window, whether the
+// leaving token is kept depends only on the score already in the ring, so the row moves
+// do not wait for the new score.  NPER = 16-byte pieces of the H new rows per thread;
+// kMlp: MLP surrogate (a.M > 0) or linear.
+template <int NPER, bool kMlp>
 __global__ __launch_bounds__(kFThreads) void decode_finish_kernel(DecodeArgs a, int ksplit) {
   extern __shared__ __align__(16) unsigned char smem[];
   float* g = reinterpret_cast<float*>(smem);          // [M] (MLP) -- or unused
-  __shared__ float s_new[16];
   __shared__ int s_keep[16];
-  const int b = blockIdx.x, tid = threadIdx.x;
+  __shared__ float s_red[16][kFWaves];                 // linear scorer: per-wavefront sums
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int H = a.H, D = a.D, w = a.window, M = a.M, Dh = a.Dh;
-  const unsigned short* b1 = static_cast<const unsigned short*>(a.b1);
-  const unsigned short* b2 = static_cast<const unsigned short*>(a.b2);
-
-  // ---- 0. everything the cache update needs that does not depend on the new score is
-  // fetched first, so that its (HBM) latency overlaps the scorer arithmetic below: the
-  // position, and per (head, 16-byte piece) the new rows, the ring rows of the slot that is
-  // about to be vacated (read speculatively: they are only used if the token is kept), the
-  // head's length, slab offset and capacity, and the leaving token's score.
   const int p = a.seq_pos[b];
-  const int q = p - w;
-  const int slot = (w > 0) ? (p % w) : 0;
+  // head h is reduced by wavefront h % 4; its lane h / 4 owns the head: it reads the leaving
+  // token's score, decides keep / drop and later writes the new score to the same ring slot
+  const int own_h = (lane < kHeadsPerWave) ? lane * kFWaves + wv : H;
+  const bool owner = own_h < H;
+  const int own_hc = owner ? own_h : H - 1;
+
+  // ---- 0a. loads that need nothing but the block index ----
   const int lpr = D / 8;
-  const int npieces = H * lpr;                         // <= 16 * 64 = 1024 -> at most 4 per thread
-  constexpr int kMaxPer = 4;
-  u32x4 k_in[kMaxPer], v_in[kMaxPer], k_old[kMaxPer], v_old[kMaxPer];
-  int len_r[kMaxPer], cap_r[kMaxPer];
-  long long slab_r[kMaxPer];
-  const u32x4* kn = static_cast<const u32x4*>(a.k_new) + (size_t)b * H * lpr;
-  const u32x4* vn = static_cast<const u32x4*>(a.v_new) + (size_t)b * H * lpr;
+  const int npieces = H * lpr;                         // <= 16 * 64 = 1024 = 4 * kFThreads
+  u32x4 k_in[NPER], v_in[NPER], k_old[NPER], v_old[NPER];
+  int len_r[NPER], cap_r[NPER], head_r[NPER], piece_r[NPER];
+  long long slab_r[NPER];
+  const u32x4* kn = static_cast<const u32x4*>(a.k_new) + (size_t)b * npieces;
+  const u32x4* vn = static_cast<const u32x4*>(a.v_new) + (size_t)b * npieces;
   u32x4* Kp = static_cast<u32x4*>(a.K_prefix);
   u32x4* Vp = static_cast<u32x4*>(a.V_prefix);
   u32x4* Kr = static_cast<u32x4*>(a.K_ring);
   u32x4* Vr = static_cast<u32x4*>(a.V_ring);
 #pragma unroll
-  for (int c = 0; c < kMaxPer; ++c) {
-    const int i = tid + c * kFThreads;
-    if (i < npieces) {
-      const int h = i / lpr, piece = i % lpr, bh = b * H + h;
-      k_in[c] = kn[i];
-      v_in[c] = vn[i];
-      len_r[c] = a.lengths[bh];
-      if (a.block_table) {
-        // paged prefix: the next row is row len % page_rows of the page in table slot
-        // len / page_rows.  Expressed as a slab whose row `len` is that row, with room for
-        // exactly one more row if the slot holds a page of the pool.
-        const int len = len_r[c] < 0 ? 0 : len_r[c];
-        const int pslot = len >> a.log_page;
-        const int page = pslot < a.max_pages ? a.block_table[(size_t)bh * a.max_pages + pslot] : -1;
-        const bool ok = page >= 0 && page < a.num_pages;
-        cap_r[c] = ok ? len_r[c] + 1 : len_r[c];
-        slab_r[c] = (((long long)(ok ? page : 0)) << a.log_page) + (len & ((1 << a.log_page) - 1)) - len_r[c];
-      } else {
-        cap_r[c] = a.slab_capacity[bh];
-        slab_r[c] = a.slab_offsets[bh];
-      }
-      if (w > 0 && q >= 0) {
-        const size_t ring_at = ((size_t)bh * w + slot) * lpr + piece;
-        k_old[c] = Kr[ring_at];
-        v_old[c] = Vr[ring_at];
-      }
+  for (int c = 0; c < NPER; ++c) {
+    int i = tid + c * kFThreads;
+    if (i > npieces - 1) i = npieces - 1;
+    head_r[c] = i / lpr;
+    piece_r[c] = i - head_r[c] * lpr;
+    const int bh = b * H + head_r[c];
+    k_in[c] = kn[i];
+    v_in[c] = vn[i];
+    len_r[c] = a.lengths[bh];
+    if (!a.block_table) {
+      cap_r[c] = a.slab_capacity[bh];
+      slab_r[c] = a.slab_offsets[bh];
     }
   }
-  float s_q_r = 0.0f;
-  if (tid < H && w > 0 && q >= 0) s_q_r = a.score_ring[(size_t)(b * H + tid) * w + slot];
-  // second-projection weights of this thread's hidden units (M <= 640 -> at most 3 per head)
-  constexpr int kMaxUnits = 3;
-  unsigned short w2r[16][kMaxUnits];
-  if (M > 0) {
+  // an absent bias is read from a stand-in address and discarded: a branch around the load
+  // would make the wavefront wait for it on the spot
+  const unsigned short* bias2p = static_cast<const unsigned short*>(kMlp ? a.b2 : a.b1);
+  const unsigned short* bias2_at = bias2p ? bias2p + own_hc : static_cast<const unsigned short*>(a.k_new);
+  const unsigned short bias2_raw = *bias2_at;
+  const unsigned short bias2 = bias2p ? bias2_raw : (unsigned short)0;
+  // MLP: the K-slices of the first projection (two adjacent units per thread and round), the
+  // first bias, the second projection's weights (8 units per lane and round, heads by wavefront)
+  float2 part[kUnitRounds][kMaxKSplit];
+  unsigned int bias1[kUnitRounds];
+  u32x4 w2[kHeadsPerWave][kUnitRounds];
+  // linear: per-thread sums over its 8-input chunks
+  float dot[16];
+  if constexpr (kMlp) {
+    const float* partial = static_cast<const float*>(a.workspace);
+    const unsigned short* b1 = static_cast<const unsigned short*>(a.b1);
     const unsigned short* W2 = static_cast<const unsigned short*>(a.W2);
 #pragma unroll
-    for (int h = 0; h < 16; ++h)
+    for (int r = 0; r < kUnitRounds; ++r) {
+      if (r == 0 || M > r * 2 * kFThreads) {
+        int m0 = 2 * tid + r * 2 * kFThreads;
+        if (m0 > M - 2) m0 = M - 2;
 #pragma unroll
-      for (int u = 0; u < kMaxUnits; ++u) {
-        const int m = tid + u * kFThreads;
-        w2r[h][u] = (h < H && m < M) ? W2[(size_t)h * M + m] : (unsigned short)0;
+        for (int ks = 0; ks < kMaxKSplit; ++ks) {
+          const int kc = ks < ksplit ? ks : ksplit - 1;
+          part[r][ks] = *reinterpret_cast<const float2*>(partial + ((size_t)kc * a.B + b) * M + m0);
+        }
+        const unsigned int raw = *reinterpret_cast<const unsigned int*>(b1 ? b1 + m0 : static_cast<const unsigned short*>(a.k_new));
+        bias1[r] = b1 ? raw : 0u;
       }
-  }
-
-  // ---- 1. scores of the new token ----
-  if (M > 0) {
-    const float* partial = static_cast<const float*>(a.workspace);
-    for (int m = tid; m < M; m += kFThreads) {
-      // the partial sums were written by other XCDs, so each read is a trip to memory: issue
-      // all K-slices' loads together (ksplit <= kMaxKSplit), then add them in a fixed order
-      float part[kMaxKSplit];
+      if (r == 0 || M > r * 512) {
+        int u0 = (r * 64 + lane) * 8;
+        if (u0 > M - 8) u0 = M - 8;
 #pragma unroll
-      for (int ks = 0; ks < kMaxKSplit; ++ks)
-        part[ks] = (ks < ksplit) ? partial[((size_t)ks * a.B + b) * M + m] : 0.0f;
-      float z = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < kMaxKSplit; ++ks) z += part[ks];
-      if (b1) z += bf16_bits_to_float(b1[m]);
-      g[m] = 0.5f * z * (1.0f + erff(z * 0.70710678118654752f));
-    }
-    __syncthreads();
-  }
-  // all H dot products at once: every load below is independent of the others, and a single
-  // block reduction follows (a loop over heads with a barrier each would serialise H memory
-  // round trips)
-  float dot[16];
-#pragma unroll
-  for (int h = 0; h < 16; ++h) dot[h] = 0.f;
-  if (M > 0) {
-#pragma unroll
-    for (int u = 0; u < kMaxUnits; ++u) {
-      const int m = tid + u * kFThreads;
-      const float gm = (m < M) ? g[m] : 0.f;
-#pragma unroll
-      for (int h = 0; h < 16; ++h) dot[h] += gm * bf16_bits_to_float(w2r[h][u]);
+        for (int j = 0; j < kHeadsPerWave; ++j) {
+          int h = j * kFWaves + wv;
+          if (h > H - 1) h = H - 1;
+          w2[j][r] = *reinterpret_cast<const u32x4*>(W2 + (size_t)h * M + u0);
+        }
+      }
     }
   } else {
-    const unsigned short* hid = static_cast<const unsigned short*>(a.hidden_new) + (size_t)b * Dh;
-    const unsigned short* W = static_cast<const unsigned short*>(a.W1);
-    for (int k = tid; k < Dh; k += kFThreads) {
-      const float x = bf16_bits_to_float(hid[k]);
+    const u32x4* hid = reinterpret_cast<const u32x4*>(static_cast<const unsigned short*>(a.hidden_new) + (size_t)b * Dh);
+    const u32x4* W = static_cast<const u32x4*>(a.W1);
+    const int nchunk = Dh / 8;
 #pragma unroll
-      for (int h = 0; h < 16; ++h)
-        if (h < H) dot[h] += x * bf16_bits_to_float(W[(size_t)h * Dh + k]);
+    for (int h = 0; h < 16; ++h) dot[h] = 0.f;
+    for (int c0 = 0; c0 < nchunk; c0 += 2 * kFThreads) {
+      // two rounds of loads in flight
+      u32x4 x[2], wt[2][16];
+      bool ok[2];
+#pragma unroll
+      for (int r = 0; r < 2; ++r) {
+        int ch = c0 + r * kFThreads + tid;
+        ok[r] = ch < nchunk;
+        if (!ok[r]) ch = nchunk - 1;
+        x[r] = hid[ch];
+#pragma unroll
+        for (int h = 0; h < 16; ++h)
+          if (h < H) wt[r][h] = W[(size_t)h * nchunk + ch];
+      }
+#pragma unroll
+      for (int r = 0; r < 2; ++r)
+#pragma unroll
+        for (int h = 0; h < 16; ++h)
+          if (h < H) dot[h] += ok[r] ? dot8_bf16(x[r], wt[r][h]) : 0.f;
     }
   }
-  __shared__ float red[16][kFThreads / 64];
+
+  // ---- 0b. loads that need the position: the ring rows of the slot about to be vacated
+  // (read before it is known whether they are needed), the leaving token's score, and for
+  // the paged layout the page of the prefix's next row
+  const int q = p - w;
+  const int slot = (w > 0) ? (p % w) : 0;
+  float s_q = 0.f;
+  if (w > 0) {
 #pragma unroll
-  for (int h = 0; h < 16; ++h) {
-    if (h < H) {
-      float v = dot[h];
+    for (int c = 0; c < NPER; ++c) {
+      const size_t ring_at = ((size_t)(b * H + head_r[c]) * w + slot) * lpr + piece_r[c];
+      k_old[c] = Kr[ring_at];
+      v_old[c] = Vr[ring_at];
+    }
+    s_q = a.score_ring[(size_t)(b * H + own_hc) * w + slot];
+  }
+  if (a.block_table) {
 #pragma unroll
-      for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
-      if ((tid & 63) == 0) red[h][tid >> 6] = v;
+    for (int c = 0; c < NPER; ++c) {
+      // paged prefix: the next row is row len % page_rows of the page in table slot
+      // len / page_rows.  Expressed as a slab whose row `len` is that row, with room for
+      // exactly one more row if the slot holds a page of the pool.
+      const int len = len_r[c] < 0 ? 0 : len_r[c];
+      const int pslot = len >> a.log_page;
+      const int pc = pslot < a.max_pages ? pslot : a.max_pages - 1;
+      const int entry = a.block_table[(size_t)(b * H + head_r[c]) * a.max_pages + pc];
+      const int page = pslot < a.max_pages ? entry : -1;
+      const bool ok = page >= 0 && page < a.num_pages;
+      cap_r[c] = ok ? len_r[c] + 1 : len_r[c];
+      slab_r[c] = (((long long)(ok ? page : 0)) << a.log_page) + (len & ((1 << a.log_page) - 1)) - len_r[c];
     }
   }
-  __syncthreads();
-  if (tid < H) {
-    float s = 0.f;
+
+  // ---- 1. hidden activations (MLP) or per-wavefront sums (linear) into LDS; keep flags ----
+  if constexpr (kMlp) {
 #pragma unroll
-    for (int wv = 0; wv < kFThreads / 64; ++wv) s += red[tid][wv];
-    const unsigned short* bias = (M > 0) ? b2 : b1;
-    s_new[tid] = s + (bias ? bf16_bits_to_float(bias[tid]) : 0.f);
+    for (int r = 0; r < kUnitRounds; ++r) {
+      if (r == 0 || M > r * 2 * kFThreads) {
+        const int m0 = 2 * tid + r * 2 * kFThreads;
+        float z0 = 0.f, z1 = 0.f;                      // K-slices in a fixed order
+#pragma unroll
+        for (int ks = 0; ks < kMaxKSplit; ++ks) {
+          z0 += ks < ksplit ? part[r][ks].x : 0.f;
+          z1 += ks < ksplit ? part[r][ks].y : 0.f;
+        }
+        z0 += bf16_lo(bias1[r]);
+        z1 += bf16_hi(bias1[r]);
+        float2 gv;
+        gv.x = 0.5f * z0 * (1.0f + erff(z0 * 0.70710678118654752f));
+        gv.y = 0.5f * z1 * (1.0f + erff(z1 * 0.70710678118654752f));
+        if (m0 < M) *reinterpret_cast<float2*>(g + m0) = gv;
+      }
+    }
+  } else {
+#pragma unroll
+    for (int h = 0; h < 16; ++h) {
+      if (h < H) {
+        const float v = wave_sum(dot[h]);
+        if (lane == 0) s_red[h][wv] = v;
+      }
+    }
   }
+  if (w > 0 && owner) s_keep[own_h] = (q >= 0) && (s_q >= a.tau);
   __syncthreads();
 
-  // ---- 2. is the token that leaves the window kept ----
-  if (tid < H) {
-    const float s_q = (w > 0) ? s_q_r : s_new[tid];      // w == 0: the new token itself
-    s_keep[tid] = (q >= 0) && (s_q >= a.tau);
-  }
-  __syncthreads();
-
-  // ---- 3. move rows: ring -> prefix tail (kept), new -> ring slot ----
+  // ring -> prefix tail (kept), new -> ring slot, and the head's bookkeeping by the thread
+  // that owns piece 0
+  auto move_rows = [&]() {
 #pragma unroll
-  for (int c = 0; c < kMaxPer; ++c) {
-    const int i = tid + c * kFThreads;
-    if (i < npieces) {
-      const int h = i / lpr, piece = i % lpr, bh = b * H + h;
-      if (s_keep[h] && len_r[c] < cap_r[c]) {
-        const size_t dst = ((size_t)slab_r[c] + len_r[c]) * lpr + piece;
-        Kp[dst] = (w > 0) ? k_old[c] : k_in[c];
-        Vp[dst] = (w > 0) ? v_old[c] : v_in[c];
-      }
-      if (w > 0) {
-        const size_t ring_at = ((size_t)bh * w + slot) * lpr + piece;
-        Kr[ring_at] = k_in[c];
-        Vr[ring_at] = v_in[c];
-      }
-      // ---- 4. bookkeeping, by the thread that owns piece 0 of the head ----
-      if (piece == 0) {
-        if (s_keep[h]) {
+    for (int c = 0; c < NPER; ++c) {
+      const int i = tid + c * kFThreads;
+      if (i < npieces) {
+        const int h = head_r[c], piece = piece_r[c], bh = b * H + h;
+        const bool keep = s_keep[h] != 0;
+        if (keep && len_r[c] < cap_r[c]) {
+          const size_t dst = ((size_t)slab_r[c] + len_r[c]) * lpr + piece;
+          Kp[dst] = (w > 0) ? k_old[c] : k_in[c];
+          Vp[dst] = (w > 0) ? v_old[c] : v_in[c];
+        }
+        if (w > 0) {
+          const size_t ring_at = ((size_t)bh * w + slot) * lpr + piece;
+          Kr[ring_at] = k_in[c];
+          Vr[ring_at] = v_in[c];
+        }
+        if (piece == 0 && keep) {
           if (len_r[c] < cap_r[c]) {
             a.prefix_pos[(size_t)slab_r[c] + len_r[c]] = q;
             a.lengths[bh] = len_r[c] + 1;
@@ -268,9 +332,48 @@ __global__ __launch_bounds__(kFThreads) void decode_finish_kernel(DecodeArgs a, 
             *a.error_flag = 1;
           }
         }
-        if (w > 0) a.score_ring[(size_t)bh * w + slot] = s_new[h];
       }
     }
+  };
+  if (w > 0) move_rows();
+
+  // ---- 2. scores of the new token: head 4j + wv by this wavefront, result in lane j ----
+  float s_new = 0.f;
+  if constexpr (kMlp) {
+#pragma unroll
+    for (int j = 0; j < kHeadsPerWave; ++j) {
+      if (j * kFWaves + wv < H) {
+        float acc = 0.f;
+#pragma unroll
+        for (int r = 0; r < kUnitRounds; ++r) {
+          if (r == 0 || M > r * 512) {
+            const int u0 = (r * 64 + lane) * 8;
+            if (u0 < M) {
+              const floatx4 g0 = *reinterpret_cast<const floatx4*>(g + u0);
+              const floatx4 g1 = *reinterpret_cast<const floatx4*>(g + u0 + 4);
+              const u32x4 wq = w2[j][r];
+              acc += g0[0] * bf16_lo(wq[0]) + g0[1] * bf16_hi(wq[0]) + g0[2] * bf16_lo(wq[1]) +
+                     g0[3] * bf16_hi(wq[1]) + g1[0] * bf16_lo(wq[2]) + g1[1] * bf16_hi(wq[2]) +
+                     g1[2] * bf16_lo(wq[3]) + g1[3] * bf16_hi(wq[3]);
+            }
+          }
+        }
+        acc = wave_sum(acc);
+        if (lane == j) s_new = acc;
+      }
+    }
+  } else if (owner) {
+#pragma unroll
+    for (int x = 0; x < kFWaves; ++x) s_new += s_red[own_h][x];
+  }
+  s_new += bf16_bits_to_float(bias2);
+  if (w > 0) {
+    if (owner) a.score_ring[(size_t)(b * H + own_h) * w + slot] = s_new;
+  } else {
+    // no window: the new token itself is tested
+    if (owner) s_keep[own_h] = (q >= 0) && (s_new >= a.tau);
+    __syncthreads();
+    move_rows();
   }
   if (tid == 0) a.seq_pos[b] = p + 1;
 }
@@ -293,8 +396,15 @@ int launch_decode_evict(const DecodeArgs& a, hipStream_t stream) {
         static_cast<const unsigned short*>(a.W1), static_cast<float*>(a.workspace), a.B,
         a.Dh, a.M, a.Dh / ks);
   }
-  const size_t lds = (size_t)(a.M > 0 ? a.M : 1) * sizeof(float);
-  decode_finish_kernel<<<a.B, kFThreads, lds, stream>>>(a, ks);
+  const size_t lds = (size_t)(a.M > 0 ? a.M : 4) * sizeof(float);
+  const bool small = a.H * (a.D / 8) <= kFThreads;
+  if (a.M > 0) {
+    if (small) decode_finish_kernel<1, true><<<a.B, kFThreads, lds, stream>>>(a, ks);
+    else       decode_finish_kernel<4, true><<<a.B, kFThreads, lds, stream>>>(a, ks);
+  } else {
+    if (small) decode_finish_kernel<1, false><<<a.B, kFThreads, lds, stream>>>(a, ks);
+    else       decode_finish_kernel<4, false><<<a.B, kFThreads, lds, stream>>>(a, ks);
+  }
   return hipGetLastError() == hipSuccess ? KVZAP_OK : KVZAP_ERR_RUNTIME;
 }
 
