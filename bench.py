@@ -592,6 +592,27 @@ def main() -> int:
                     "algorithmic_bytes_per_launch": compact_bytes}
     compact_roof["frac"] = compact_roof["achieved"] / compact_roof["peak"]
 
+    # context, not a target and not on the product path: the vendor library's GEMM (torch.matmul,
+    # i.e. hipBLASLt) on the scorer's FIRST projection alone, same operands, bf16 output
+    library_gemm = None
+    if M:
+        hid2d = [ly["hidden"].reshape(B * T, Dh) for ly in layers]
+        w1 = [ly["w"]["W1"] for ly in layers]
+        z = torch.empty((B * T, M), dtype=torch.bfloat16, device=dev)
+        for i in range(2):
+            torch.matmul(hid2d[i % L], w1[i % L].t(), out=z)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = max(10, L)
+        e0.record()
+        for i in range(reps):
+            torch.matmul(hid2d[i % L], w1[i % L].t(), out=z)
+        e1.record(); torch.cuda.synchronize()
+        gemm_ms = e0.elapsed_time(e1) / reps
+        library_gemm = {"what": "torch.matmul hidden[B*T,Dh] x W1^T -> bf16 [B*T,M]; no bias, GELU or "
+                                "second projection", "avg_ms": gemm_ms,
+                        "TFLOP/s": 2.0 * B * T * Dh * M / (gemm_ms * 1e-3) / 1e12}
+        del z
+
     out = {
         "metric": "prune-step tokens/sec per layer (score+mask+compact)",
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -614,6 +635,7 @@ def main() -> int:
                                 "note": "score timed inside the step; mask and compact timed "
                                         "alone on one stream after it"},
         "score_max_rel_err_vs_oracle_sample": score_err,
+        "library_gemm_context": library_gemm,
         "cpu_baseline": cpu_info,
     }
     print(json.dumps(out))
