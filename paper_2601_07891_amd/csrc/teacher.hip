@@ -30,7 +30,7 @@ constexpr int kStay = 4;                   // 32-row tiles of the operand kept i
 constexpr int kStayRow = 2;                // row pass: it is bound by the exponentials, not by operand reuse,
                                            // and two tiles leave room for two wavefronts per SIMD
 constexpr float kNegBig = -1.0e30f;        // "minus infinity" that survives subtraction
-constexpr float kLazyMargin = 16.0f;
+constexpr float kLazyLimit = 1048576.0f;    // 2^20: a tile's 16 terms may sum to this before the reference moves
 
 // The streamed operand goes through an LDS ring filled by load-to-LDS kAhead tiles ahead, so
 // that the four wavefronts of a block share one copy, the global reads are whole 256-byte
@@ -114,11 +114,16 @@ __global__ __launch_bounds__(256, 2) void teacher_rowstat_kernel(
     const u32x4* q, const u32x4* k, const float* __restrict__ hnorm, int G, int Tq, int Tk,
     int tq_pad, float cscale, float* __restrict__ rowbias) {
   extern __shared__ __align__(16) unsigned char smem[];
-  const int g = blockIdx.y, h = g / G;
+  // Blocks are handed out in the order of the linear block index, and a block of late
+  // queries sees up to twice the keys of an early one: the index is mapped so that the
+  // longest blocks of all heads start first and the shortest fill the tail.
+  const int lin = blockIdx.y * gridDim.x + blockIdx.x;
+  const int bx = gridDim.x - 1 - lin / gridDim.y;
+  const int g = lin % gridDim.y, h = g / G;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int r = lane & 31, kg = lane >> 5;
-  const int q0 = (blockIdx.x * 4 + wave) * (kStayRow * 32);
+  const int q0 = (bx * 4 + wave) * (kStayRow * 32);
   const int P0 = Tk - Tq;
   const u32x4* qh = q + (size_t)g * Tq * kRowVec;
   const u32x4* kh = k + (size_t)h * Tk * kRowVec;
@@ -126,7 +131,7 @@ __global__ __launch_bounds__(256, 2) void teacher_rowstat_kernel(
 
   // every wavefront walks all the key tiles of the block (barriers), also one whose queries
   // are all padding
-  int block_last_q = blockIdx.x * 4 * (kStayRow * 32) + 4 * kStayRow * 32 - 1;
+  int block_last_q = bx * 4 * (kStayRow * 32) + 4 * kStayRow * 32 - 1;
   block_last_q = block_last_q < Tq - 1 ? block_last_q : Tq - 1;
   const int ntiles = (P0 + block_last_q) / 32 + 1;
 
@@ -162,19 +167,28 @@ __global__ __launch_bounds__(256, 2) void teacher_rowstat_kernel(
         for (int e = 0; e < 16; ++e)
           if (key0 + c_row(e, kg) > P0 + qcol) x[e] = -INFINITY;
       }
-      float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-      mx = fmaxf(mx, fmaxf(fmaxf(fmaxf(x[8], x[9]), fmaxf(x[10], x[11])),
-                           fmaxf(fmaxf(x[12], x[13]), fmaxf(x[14], x[15]))));
-      mx *= cscale;                                      // cscale > 0: max commutes with the scaling
-      if (__any(mx > m[t] + kLazyMargin)) {              // per-lane statistics: no cross-lane step
-        const float mn = fmaxf(m[t], mx);
-        l[t] *= __builtin_amdgcn_exp2f(m[t] - mn);
-        m[t] = mn;
-      }
-      const float neg_m = -m[t];
+      // The reference m is lazy: the tile is summed against the current one, and only if
+      // some lane's sum leaves the safe range (an element more than kLazyLimit above the
+      // reference, an overflow to infinity, the first tile) is the tile's maximum taken and
+      // the tile summed again.  That keeps the 16 maximum operations out of the common path
+      // (three vector operations per logit instead of four).
+      float neg_m = -m[t];
       float sum = 0.f;
 #pragma unroll
       for (int e = 0; e < 16; ++e) sum += __builtin_amdgcn_exp2f(fmaf(x[e], cscale, neg_m));
+      if (__any(!(sum <= kLazyLimit))) {                 // per-lane statistics: no cross-lane step
+        float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+        mx = fmaxf(mx, fmaxf(fmaxf(fmaxf(x[8], x[9]), fmaxf(x[10], x[11])),
+                             fmaxf(fmaxf(x[12], x[13]), fmaxf(x[14], x[15]))));
+        mx *= cscale;                                    // cscale > 0: max commutes with the scaling
+        const float mn = fmaxf(m[t], mx);
+        l[t] *= __builtin_amdgcn_exp2f(m[t] - mn);
+        m[t] = mn;
+        neg_m = -mn;
+        sum = 0.f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) sum += __builtin_amdgcn_exp2f(fmaf(x[e], cscale, neg_m));
+      }
       l[t] += sum;
     }
   };
