@@ -88,7 +88,7 @@ size_t kvzap_workspace_bytes(int which_call, int B, int T, int Dh, int M, int H)
       return kvzap::teacher_workspace_bytes(H, Dh, M, T);
     case KVZAP_CALL_TOPK_THRESHOLD:
       if ((long long)B * H > 65535) return 0;
-      return kvzap::topk_workspace_bytes(B, H, M != 0);
+      return kvzap::topk_workspace_bytes(B, H, T, M != 0);
     case KVZAP_CALL_ASSIGN_PAGES:
       if ((long long)B * H > 65535) return 0;
       return kvzap::assign_pages_workspace_bytes(B * H);
@@ -212,7 +212,7 @@ int kvzap_topk_threshold(const float* scores, int window, const int32_t* seq_len
   if (!scores || !tau_out) return KVZAP_ERR_NULL;
   if (!aligned16(scores) || !aligned16(tau_out) || !aligned16(seq_lens)) return KVZAP_ERR_ALIGN;
   if (!workspace || !aligned256(workspace) ||
-      workspace_bytes < kvzap::topk_workspace_bytes(B, H, per_layer != 0))
+      workspace_bytes < kvzap::topk_workspace_bytes(B, H, T, per_layer != 0))
     return KVZAP_ERR_WORKSPACE;
   return kvzap::launch_topk_threshold(scores, window, seq_lens, (long long)k, per_layer != 0, B,
                                       H, T, tau_out, workspace, static_cast<hipStream_t>(stream));

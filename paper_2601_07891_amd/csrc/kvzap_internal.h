@@ -84,7 +84,7 @@ int launch_mask(const float* scores, float tau, const float* tau_head, int windo
 int launch_topk_threshold(const float* scores, int window, const int32_t* seq_lens, long long k,
                           bool per_layer, int B, int H, int T, float* tau_out, void* workspace,
                           hipStream_t stream);
-size_t topk_workspace_bytes(int B, int H, bool per_layer);
+size_t topk_workspace_bytes(int B, int H, int T, bool per_layer);
 
 int launch_teacher_scores(const void* q, const void* k, const float* vnorm, const float* hnorm,
                           float scale, float* log_s, int H, int HQ, int Tq, int Tk, int T,

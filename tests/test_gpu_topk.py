@@ -86,6 +86,20 @@ def test_extreme_floats():
         _check(S, 20, k, True)
 
 
+def test_unaligned_rows_and_more_tiles_than_blocks():
+    # T not a multiple of four: rows are not 16-byte aligned and the scalar loads run;
+    # 16 pooled heads of 70001 scores: a block walks several 4096-score tiles
+    rng = np.random.default_rng(4)
+    S = rng.standard_normal((2, 3, 4099)) * 3.0
+    S[0, 1, 17] = np.nan
+    for k in (1, 100, 2000, 3970):
+        _check(S, 129, k, False)
+        _check(S, 129, 3 * k, True, seq_lens=[4099, 2051])
+    S = rng.standard_normal((1, 16, 70001)) * np.linspace(0.2, 4.0, 16)[None, :, None]
+    _check(S, 128, 16 * 20000, True)
+    _check(S[:, :2], 128, 33333, False)
+
+
 def test_topk_at_config_shape_keeps_exactly_the_budget():
     # the 128k-token shape: 25 % of every head, and the same budget pooled per layer
     B, H, T, w = 1, 8, 131072, 128
@@ -108,7 +122,8 @@ def test_rejects_bad_arguments():
     L = binding.lib()
     S = torch.zeros((1, 2, 64), dtype=torch.float32, device=DEV)
     tau = torch.zeros(2, dtype=torch.float32, device=DEV)
-    ws = torch.empty(1 << 16, dtype=torch.uint8, device=DEV)
+    ws = torch.empty(binding.kvzap_workspace_bytes(binding.CALL_TOPK_THRESHOLD, 1, 64, 0, 0, 2),
+                     dtype=torch.uint8, device=DEV)
     assert L.kvzap_topk_threshold(S.data_ptr(), 4, None, 3, 0, 1, 2, 64, tau.data_ptr(), ws.data_ptr(), ws.numel(), None) == 0
     assert L.kvzap_topk_threshold(S.data_ptr(), -1, None, 3, 0, 1, 2, 64, tau.data_ptr(), ws.data_ptr(), ws.numel(), None) == -2
     assert L.kvzap_topk_threshold(S.data_ptr(), 4, None, 3, 0, 1, 2, 64, None, ws.data_ptr(), ws.numel(), None) == -1
