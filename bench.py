@@ -377,6 +377,10 @@ def main() -> int:
                     help="run mask+compact of layer l on a second stream while the scorer of layer "
                          "l+1 runs (measured: +1 %% throughput, the scorer slows under contention); "
                          "default is one stream, which keeps per-kernel timings clean")
+    ap.add_argument("--prepared-weights", action="store_true",
+                    help="MLP surrogate: re-order W1 once with kvzap_prepare_scorer before the timed "
+                         "region and score with kvzap_score_prepared (default: kvzap_score, which "
+                         "re-orders W1 on every call)")
     ap.add_argument("--decode-cache-rows", type=int, nargs=2, default=[4096, 32768],
                     help="decode workload: range of rows already kept per (sequence, head)")
     ap.add_argument("--select", default="threshold", choices=["threshold", "topk-head", "topk-layer"],
@@ -461,9 +465,17 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
+    if args.prepared_weights and M:
+        for ly in layers:                            # at weight-load time, outside every timed region
+            ly["w1p"] = binding.kvzap_prepare_scorer(ly["w"]["W1"])
+        torch.cuda.synchronize()
+
     def score(ly):
         w = ly["w"]
-        binding.kvzap_score(ly["hidden"], w["W1"], w["b1"], w["W2"], w["b2"], ly["scores"], ws_score)
+        if args.prepared_weights and M:
+            binding.kvzap_score_prepared(ly["hidden"], ly["w1p"], w["b1"], w["W2"], w["b2"], ly["scores"])
+        else:
+            binding.kvzap_score(ly["hidden"], w["W1"], w["b1"], w["W2"], w["b2"], ly["scores"], ws_score)
 
     ws_topk = torch.empty(max(binding.kvzap_workspace_bytes(binding.CALL_TOPK_THRESHOLD, B, T, 0, 1, H),
                               binding.kvzap_workspace_bytes(binding.CALL_TOPK_THRESHOLD, B, T, 0, 0, H), 256),
@@ -624,6 +636,7 @@ def main() -> int:
                    "kept_fraction_measured": kept_fraction, "scorer": wl.scorer,
                    "output_layout": f"paged, {P} rows per page" if P else "packed contiguous",
                    "selection": args.select,
+                   "scorer_entry": "kvzap_score_prepared" if (args.prepared_weights and M) else "kvzap_score",
                    "generator": f"torch {torch.__version__} cuda philox, seeds per layer"},
         "roofline": roofline,
         "roofline_compact": compact_roof,

@@ -140,6 +140,23 @@ int kvzap_mask(const float* scores, float tau, int window,
                void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * kvzap_prepare_scorer / kvzap_score_prepared -- kvzap_score for MLP surrogates (Sec. 3.3,
+ * App. B Eq. 5) whose weights do not change between calls: kvzap_score re-orders W1 into the
+ * matrix cores' operand order in its workspace on every call; kvzap_prepare_scorer does that
+ * once, into a buffer the caller keeps (W1_prepared: device, 256-byte aligned, at least
+ * kvzap_workspace_bytes(KVZAP_CALL_SCORE, ...) bytes, not overlapping W1), and
+ * kvzap_score_prepared takes that buffer in place of W1 and needs no workspace.  Scores are
+ * bit-identical to kvzap_score's.  M > 0 only (the linear surrogate has nothing to prepare);
+ * other arguments, layouts and errors as kvzap_score.  The prepared layout is private to
+ * the library version that wrote it.
+ */
+int kvzap_prepare_scorer(const void* W1, int Dh, int M, void* W1_prepared, size_t prepared_bytes,
+                         void* stream);
+int kvzap_score_prepared(const void* hidden, const void* W1_prepared, const void* b1,
+                         const void* W2, const void* b2, float* scores, int B, int T, int Dh,
+                         int M, int H, void* stream);
+
+/*
  * kvzap_topk_threshold -- thresholds for the fixed-budget variants (Sec. 3.3: keeping a
  * fixed fraction; Sec. 4 ablation: fixed-ratio top-k per head, or per layer as in AdaKV).
  * The population of head (b,h) is its non-window positions t < T_b - window whose score is

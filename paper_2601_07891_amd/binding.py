@@ -31,6 +31,8 @@ SIGNATURES = {
     "kvzap_score": (_c_int, [_c_void_p] * 6 + [_c_int] * 5 + [_c_void_p, _c_size_t, _c_void_p]),
     "kvzap_mask": (_c_int, [_c_void_p, _c_float, _c_int, _c_void_p, _c_int, _c_int, _c_int,
                             _c_void_p, _c_void_p, _c_void_p, _c_void_p, _c_size_t, _c_void_p]),
+    "kvzap_prepare_scorer": (_c_int, [_c_void_p, _c_int, _c_int, _c_void_p, _c_size_t, _c_void_p]),
+    "kvzap_score_prepared": (_c_int, [_c_void_p] * 6 + [_c_int] * 5 + [_c_void_p]),
     "kvzap_compress": (_c_int, [_c_void_p] * 7 + [_c_float, _c_int] + [_c_void_p] * 7 + [_c_int64] +
                        [_c_int] * 6 + [_c_void_p, _c_size_t, _c_void_p]),
     "kvzap_teacher_scores": (_c_int, [_c_void_p] * 4 + [_c_float, _c_void_p] + [_c_int] * 6 +
@@ -622,3 +624,37 @@ def kvzap_compress(hidden: torch.Tensor, W1: torch.Tensor, b1, W2, b2, K: torch.
     if rc != 0:
         raise KvzapError(rc, "kvzap_compress")
     return scores, keep_idx, lengths, offsets, K_out, V_out
+
+
+def kvzap_prepare_scorer(W1: torch.Tensor, stream=None) -> torch.Tensor:
+    """W1 bf16 [M,Dh] of an MLP surrogate -> the copy kvzap_score_prepared takes (opaque bytes)."""
+    _check(W1, torch.bfloat16, "W1")
+    M, Dh = W1.shape
+    nbytes = max(kvzap_workspace_bytes(CALL_SCORE, 1, 1, Dh, M, 1), 256)
+    out = torch.empty(nbytes, dtype=torch.uint8, device=W1.device)
+    rc = lib().kvzap_prepare_scorer(_ptr(W1), Dh, M, _ptr(out), nbytes, _stream(stream))
+    if rc != 0:
+        raise KvzapError(rc, "kvzap_prepare_scorer")
+    return out
+
+
+def kvzap_score_prepared(hidden: torch.Tensor, W1_prepared: torch.Tensor, b1, W2: torch.Tensor, b2,
+                         scores: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """kvzap_score with W1 replaced by kvzap_prepare_scorer's output; no workspace."""
+    bf = torch.bfloat16
+    _check(hidden, bf, "hidden"); _check(W1_prepared, torch.uint8, "W1_prepared")
+    _check(b1, bf, "b1", True); _check(W2, bf, "W2"); _check(b2, bf, "b2", True)
+    B, T, Dh = hidden.shape
+    H, M = W2.shape
+    if W1_prepared.numel() < M * Dh * 2:
+        raise ValueError("W1_prepared is smaller than M*Dh bf16 values")
+    if scores is None:
+        scores = torch.empty((B, H, T), dtype=torch.float32, device=hidden.device)
+    _check(scores, torch.float32, "scores")
+    if scores.shape != (B, H, T):
+        raise ValueError("scores must be [B,H,T]")
+    rc = lib().kvzap_score_prepared(_ptr(hidden), _ptr(W1_prepared), _ptr(b1), _ptr(W2), _ptr(b2),
+                                    _ptr(scores), B, T, Dh, M, H, _stream(stream))
+    if rc != 0:
+        raise KvzapError(rc, "kvzap_score_prepared")
+    return scores

@@ -177,6 +177,33 @@ int kvzap_score(const void* hidden, const void* W1, const void* b1, const void* 
                    static_cast<hipStream_t>(stream));
 }
 
+int kvzap_prepare_scorer(const void* W1, int Dh, int M, void* W1_prepared, size_t prepared_bytes,
+                         void* stream) {
+  const int rc = check_scorer_shape(Dh, M, 1);
+  if (rc != KVZAP_OK) return rc;
+  if (M == 0) return KVZAP_ERR_SHAPE;                     // the linear surrogate needs no preparation
+  if (!W1 || !W1_prepared) return KVZAP_ERR_NULL;
+  if (!aligned16(W1) || !aligned256(W1_prepared)) return KVZAP_ERR_ALIGN;
+  if (prepared_bytes < kvzap::align_up((size_t)M * Dh * 2, 256)) return KVZAP_ERR_WORKSPACE;
+  const size_t n = (size_t)M * Dh * 2;
+  const uintptr_t a = reinterpret_cast<uintptr_t>(W1), b = reinterpret_cast<uintptr_t>(W1_prepared);
+  if (a < b + n && b < a + n) return KVZAP_ERR_SHAPE;     // not an in-place operation
+  return kvzap::launch_prepare_w1(W1, Dh, M, W1_prepared, static_cast<hipStream_t>(stream));
+}
+
+int kvzap_score_prepared(const void* hidden, const void* W1_prepared, const void* b1,
+                         const void* W2, const void* b2, float* scores, int B, int T, int Dh,
+                         int M, int H, void* stream) {
+  if (M <= 0) return KVZAP_ERR_SHAPE;
+  // as kvzap_score, with the workspace requirement replaced by the prepared copy's alignment
+  int rc = check_score(hidden, W1_prepared, b1, W2, b2, scores, B, T, Dh, M, H,
+                       W1_prepared, kvzap::align_up((size_t)M * Dh * 2, 256));
+  if (rc != KVZAP_OK) return rc == KVZAP_ERR_WORKSPACE ? KVZAP_ERR_ALIGN : rc;
+  if ((long long)B * T == 0) return KVZAP_OK;
+  return kvzap::launch_score_mlp(hidden, W1_prepared, b1, W2, b2, scores, B, T, Dh, M, H, nullptr,
+                                 static_cast<hipStream_t>(stream));
+}
+
 int kvzap_mask(const float* scores, float tau, int window, const int32_t* seq_lens, int B,
                int H, int T, int32_t* keep_idx, int32_t* lengths, int64_t* offsets,
                void* workspace, size_t workspace_bytes, void* stream) {

@@ -99,6 +99,8 @@ int launch_compact(const void* K, const void* V, const int32_t* keep_idx,
 int launch_score_linear(const void* hidden, const void* W, const void* b, float* scores,
                         int B, int T, int Dh, int H, hipStream_t stream);
 
+int launch_prepare_w1(const void* W1, int Dh, int M, void* out, hipStream_t stream);
+// workspace == nullptr: W1 is the copy made by launch_prepare_w1
 int launch_score_mlp(const void* hidden, const void* W1, const void* b1, const void* W2,
                      const void* b2, float* scores, int B, int T, int Dh, int M, int H,
                      void* workspace, hipStream_t stream);

@@ -508,11 +508,14 @@ int launch_frag(const void* hidden, const void* W1, const void* b1, const void* 
       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (attr_rc != hipSuccess) return KVZAP_ERR_RUNTIME;
   const int M = 128 * UB;
-  arrange_w1_kernel<<<512, 256, 0, stream>>>(static_cast<const u32x4*>(W1),
-                                             static_cast<u32x4*>(workspace), M, Dh);
+  // workspace == nullptr: W1 already is the fragment-ordered copy (launch_prepare_w1)
+  if (workspace)
+    arrange_w1_kernel<<<512, 256, 0, stream>>>(static_cast<const u32x4*>(W1),
+                                               static_cast<u32x4*>(workspace), M, Dh);
+  const void* w1f = workspace ? workspace : W1;
   const long long blocks = (rows + TOK - 1) / TOK;
   score_mlp_frag_kernel<UB, TB><<<dim3((unsigned)blocks), 256, lds, stream>>>(
-      static_cast<const unsigned short*>(hidden), static_cast<const unsigned char*>(workspace),
+      static_cast<const unsigned short*>(hidden), static_cast<const unsigned char*>(w1f),
       static_cast<const unsigned short*>(b1), static_cast<const unsigned short*>(W2),
       static_cast<const unsigned short*>(b2), scores, rows, T, Dh, H);
   return hipGetLastError() == hipSuccess ? KVZAP_OK : KVZAP_ERR_RUNTIME;
@@ -536,7 +539,26 @@ int launch_one(const void* hidden, const void* W1, const void* b1, const void* W
   return hipGetLastError() == hipSuccess ? KVZAP_OK : KVZAP_ERR_RUNTIME;
 }
 
+__global__ __launch_bounds__(256) void copy_w1_kernel(const u32x4* __restrict__ W1,
+                                                      u32x4* __restrict__ out, int n) {
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x)
+    out[i] = W1[i];
+}
+
 }  // namespace
+
+// The form of W1 that launch_score_mlp takes with workspace == nullptr: fragment order for
+// the main kernel, a plain copy for the small-D_h kernel.
+int launch_prepare_w1(const void* W1, int Dh, int M, void* out, hipStream_t stream) {
+  const bool frag = (Dh / kBK) >= kPD + 1;
+  if (frag)
+    arrange_w1_kernel<<<512, 256, 0, stream>>>(static_cast<const u32x4*>(W1),
+                                               static_cast<u32x4*>(out), M, Dh);
+  else
+    copy_w1_kernel<<<64, 256, 0, stream>>>(static_cast<const u32x4*>(W1),
+                                           static_cast<u32x4*>(out), M * (Dh / 8));
+  return hipGetLastError() == hipSuccess ? KVZAP_OK : KVZAP_ERR_RUNTIME;
+}
 
 int launch_score_mlp(const void* hidden, const void* W1, const void* b1, const void* W2,
                      const void* b2, float* scores, int B, int T, int Dh, int M, int H,

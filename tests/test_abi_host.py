@@ -85,6 +85,26 @@ def test_score_argument_errors(lib):
     assert f(None, None, None, None, None, None, 1, 0, 4096, 0, 8, None, 0, None) == 0
 
 
+def test_prepared_scorer_argument_errors(lib):
+    f = lib.kvzap_prepare_scorer
+    need = lib.kvzap_workspace_bytes(binding.CALL_SCORE, 1, 1, 4096, 512, 8)
+    Q = 0x4000000
+    assert f(None, 4096, 512, Q, need, None) == ERR["null"]
+    assert f(P, 4096, 512, None, need, None) == ERR["null"]
+    assert f(P, 4096, 0, Q, need, None) == ERR["shape"]          # nothing to prepare
+    assert f(P, 4096, 500, Q, need, None) == ERR["unsupported"]
+    assert f(P, 4096, 512, Q + 16, need, None) == ERR["align"]
+    assert f(P, 4096, 512, Q, need - 1, None) == ERR["workspace"]
+    assert f(P, 4096, 512, P + 4096, need, None) == ERR["shape"]  # overlaps W1
+    g = lib.kvzap_score_prepared
+    assert g(P, Q, None, P, None, P, 1, 16, 4096, 0, 8, None) == ERR["shape"]
+    assert g(P, None, None, P, None, P, 1, 16, 4096, 512, 8, None) == ERR["null"]
+    assert g(P, Q, None, None, None, P, 1, 16, 4096, 512, 8, None) == ERR["null"]
+    assert g(P, Q + 16, None, P, None, P, 1, 16, 4096, 512, 8, None) == ERR["align"]
+    assert g(P, Q, None, P, None, P, 1, 16, 4096, 768, 8, None) == ERR["unsupported"]
+    assert g(None, None, None, None, None, None, 1, 0, 4096, 512, 8, None) == 0   # empty input
+
+
 def test_mask_argument_errors(lib):
     f = lib.kvzap_mask
     ws = lib.kvzap_workspace_bytes(binding.CALL_MASK, 1, 1024, 0, 0, 8)

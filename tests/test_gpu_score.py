@@ -121,3 +121,24 @@ def test_scores_deterministic():
     a = _gpu_scores(hid, w).clone()
     b = _gpu_scores(hid, w)
     assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("B,T,Dh,M,H", [(1, 1000, 4096, 512, 8), (1, 257, 5120, 640, 8),
+                                        (2, 70, 320, 256, 4), (1, 500, 192, 512, 8)])
+def test_prepared_weights_give_the_same_bits(B, T, Dh, M, H):
+    # W1 re-ordered once and reused: the scores of kvzap_score, bit for bit, also after the
+    # original W1 is gone and on repeated calls
+    wl = synth.Workload("t", L=1, B=B, T=T, Dh=Dh, H=H, scorer="mlp", seed=T + M, bias_std=0.1)
+    g = torch.Generator().manual_seed(T)
+    w = _dev({"W1": (torch.randn((M, Dh), generator=g) * Dh ** -0.5).bfloat16(),
+              "b1": (torch.randn((M,), generator=g) * 0.1).bfloat16(),
+              "W2": (torch.randn((H, M), generator=g) * M ** -0.5).bfloat16(),
+              "b2": (torch.randn((H,), generator=g) * 0.1).bfloat16()})
+    hid = synth.make_hidden(wl).to(DEV)
+    want = binding.kvzap_score(hid, w["W1"], w["b1"], w["W2"], w["b2"]).clone()
+    prep = binding.kvzap_prepare_scorer(w["W1"])
+    w["W1"].zero_()
+    for _ in range(2):
+        got = binding.kvzap_score_prepared(hid, prep, w["b1"], w["W2"], w["b2"])
+        torch.cuda.synchronize()
+        assert torch.equal(got, want)
