@@ -96,10 +96,12 @@ __global__ __launch_bounds__(kPThreads) void decode_partial_kernel(
   }
 }
 
-constexpr int kFThreads = 256;
-constexpr int kFWaves = kFThreads / 64;
-constexpr int kHeadsPerWave = 4;     // H <= 16: head h belongs to wavefront h % 4
-constexpr int kUnitRounds = 2;       // M <= 1024: a lane covers 8 hidden units per round
+constexpr int kFThreads = 1024;
+constexpr int kFWaves = kFThreads / 64;       // 16 >= H: wavefront h reduces head h, its lane 0 owns it
+constexpr int kKGroups = 4;                   // thread t sums K-slices 4*(t/256) .. +4 of unit pair t%256
+constexpr int kPairs = kFThreads / kKGroups;  // unit pairs per round
+constexpr int kUnitRounds = 2;                // M <= 1024
+static_assert(kKGroups * 4 == kMaxKSplit, "four K-slices per group");
 
 // low / high bf16 of a 32-bit word as fp32
 __device__ __forceinline__ float bf16_lo(unsigned int u) { return __uint_as_float(u << 16); }
@@ -122,68 +124,65 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
+__device__ __forceinline__ float gelu_erf(float z) {
+  return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f));
+}
+
 // The step is a chain of dependent memory round trips, so the kernel is written around
-// their number, not around arithmetic: every load whose address does not depend on loaded
-// data is issued at entry without a branch around it (out-of-range lanes read a clamped
-// address and discard the value), the loads that need the position follow as soon as it
-// arrives, and one barrier separates them from the stores.  With a window, whether the
-// leaving token is kept depends only on the score already in the ring, so the row moves
-// do not wait for the new score.  NPER = 16-byte pieces of the H new rows per thread;
+// their number and around how fast a wavefront issues instructions, not around arithmetic:
+//  * every load whose address does not depend on loaded data is issued at entry without a
+//    branch around it (out-of-range lanes read a clamped address and discard the value; a
+//    branch with a load inside makes the wavefront wait for that load on the spot), the
+//    loads that need the position follow as soon as it arrives;
+//  * a lone wavefront per SIMD issues an instruction only every ~10 cycles, so the block
+//    has 16 wavefronts and every thread few loads: a quarter of the K-slices of one pair of
+//    hidden units, one 16-byte piece of the new rows, one head's second-projection weights;
+//  * with a window, whether the leaving token is kept depends only on the score already in
+//    the ring, so the row moves follow the first barrier and do not wait for the new score.
 // kMlp: MLP surrogate (a.M > 0) or linear.
-template <int NPER, bool kMlp>
+template <bool kMlp>
 __global__ __launch_bounds__(kFThreads) void decode_finish_kernel(DecodeArgs a, int ksplit) {
   extern __shared__ __align__(16) unsigned char smem[];
-  float* g = reinterpret_cast<float*>(smem);          // [M] (MLP) -- or unused
+  float* g = reinterpret_cast<float*>(smem);          // [M] hidden activations (MLP)
+  float* zpart = g + a.M;                             // [kKGroups][M] sums of four K-slices each
   __shared__ int s_keep[16];
   __shared__ float s_red[16][kFWaves];                 // linear scorer: per-wavefront sums
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int H = a.H, D = a.D, w = a.window, M = a.M, Dh = a.Dh;
   const int p = a.seq_pos[b];
-  // head h is reduced by wavefront h % 4; its lane h / 4 owns the head: it reads the leaving
-  // token's score, decides keep / drop and later writes the new score to the same ring slot
-  const int own_h = (lane < kHeadsPerWave) ? lane * kFWaves + wv : H;
-  const bool owner = own_h < H;
-  const int own_hc = owner ? own_h : H - 1;
+  // lane 0 of wavefront h owns head h: it reads the leaving token's score, decides keep /
+  // drop and later writes the new score to the same ring slot
+  const bool owner = lane == 0 && wv < H;
+  const int hw = wv < H ? wv : H - 1;                  // this wavefront's head (clamped)
 
   // ---- 0a. loads that need nothing but the block index ----
   const int lpr = D / 8;
-  const int npieces = H * lpr;                         // <= 16 * 64 = 1024 = 4 * kFThreads
-  u32x4 k_in[NPER], v_in[NPER], k_old[NPER], v_old[NPER];
-  int len_r[NPER], cap_r[NPER], head_r[NPER], piece_r[NPER];
-  long long slab_r[NPER];
-  const u32x4* kn = static_cast<const u32x4*>(a.k_new) + (size_t)b * npieces;
-  const u32x4* vn = static_cast<const u32x4*>(a.v_new) + (size_t)b * npieces;
+  const int npieces = H * lpr;                         // <= 16 * 64 = kFThreads
+  const int pi = tid < npieces ? tid : npieces - 1;    // this thread's 16-byte piece of the new rows
+  const int head_r = pi / lpr, piece_r = pi - head_r * lpr, bh_r = b * H + head_r;
   u32x4* Kp = static_cast<u32x4*>(a.K_prefix);
   u32x4* Vp = static_cast<u32x4*>(a.V_prefix);
   u32x4* Kr = static_cast<u32x4*>(a.K_ring);
   u32x4* Vr = static_cast<u32x4*>(a.V_ring);
-#pragma unroll
-  for (int c = 0; c < NPER; ++c) {
-    int i = tid + c * kFThreads;
-    if (i > npieces - 1) i = npieces - 1;
-    head_r[c] = i / lpr;
-    piece_r[c] = i - head_r[c] * lpr;
-    const int bh = b * H + head_r[c];
-    k_in[c] = kn[i];
-    v_in[c] = vn[i];
-    len_r[c] = a.lengths[bh];
-    if (!a.block_table) {
-      cap_r[c] = a.slab_capacity[bh];
-      slab_r[c] = a.slab_offsets[bh];
-    }
+  const u32x4 k_in = static_cast<const u32x4*>(a.k_new)[(size_t)b * npieces + pi];
+  const u32x4 v_in = static_cast<const u32x4*>(a.v_new)[(size_t)b * npieces + pi];
+  const int len_r = a.lengths[bh_r];
+  int cap_r = 0;
+  long long slab_r = 0;
+  if (!a.block_table) {
+    cap_r = a.slab_capacity[bh_r];
+    slab_r = a.slab_offsets[bh_r];
   }
-  // an absent bias is read from a stand-in address and discarded: a branch around the load
-  // would make the wavefront wait for it on the spot
+  // an absent bias is read from a stand-in address and discarded
   const unsigned short* bias2p = static_cast<const unsigned short*>(kMlp ? a.b2 : a.b1);
-  const unsigned short* bias2_at = bias2p ? bias2p + own_hc : static_cast<const unsigned short*>(a.k_new);
+  const unsigned short* bias2_at = bias2p ? bias2p + hw : static_cast<const unsigned short*>(a.k_new);
   const unsigned short bias2_raw = *bias2_at;
   const unsigned short bias2 = bias2p ? bias2_raw : (unsigned short)0;
-  // MLP: the K-slices of the first projection (two adjacent units per thread and round), the
-  // first bias, the second projection's weights (8 units per lane and round, heads by wavefront)
-  float2 part[kUnitRounds][kMaxKSplit];
-  unsigned int bias1[kUnitRounds];
-  u32x4 w2[kHeadsPerWave][kUnitRounds];
-  // linear: per-thread sums over its 8-input chunks
+
+  const int kq = tid / kPairs, pr = tid - kq * kPairs;
+  float2 part[kUnitRounds][4];
+  unsigned int bias1 = 0;
+  u32x4 w2[kUnitRounds];
   float dot[16];
   if constexpr (kMlp) {
     const float* partial = static_cast<const float*>(a.workspace);
@@ -191,53 +190,45 @@ __global__ __launch_bounds__(kFThreads) void decode_finish_kernel(DecodeArgs a, 
     const unsigned short* W2 = static_cast<const unsigned short*>(a.W2);
 #pragma unroll
     for (int r = 0; r < kUnitRounds; ++r) {
-      if (r == 0 || M > r * 2 * kFThreads) {
-        int m0 = 2 * tid + r * 2 * kFThreads;
+      if (r == 0 || M > r * 2 * kPairs) {
+        int m0 = 2 * pr + r * 2 * kPairs;
         if (m0 > M - 2) m0 = M - 2;
 #pragma unroll
-        for (int ks = 0; ks < kMaxKSplit; ++ks) {
+        for (int j = 0; j < 4; ++j) {
+          const int ks = 4 * kq + j;
           const int kc = ks < ksplit ? ks : ksplit - 1;
-          part[r][ks] = *reinterpret_cast<const float2*>(partial + ((size_t)kc * a.B + b) * M + m0);
+          part[r][j] = *reinterpret_cast<const float2*>(partial + ((size_t)kc * a.B + b) * M + m0);
         }
-        const unsigned int raw = *reinterpret_cast<const unsigned int*>(b1 ? b1 + m0 : static_cast<const unsigned short*>(a.k_new));
-        bias1[r] = b1 ? raw : 0u;
       }
       if (r == 0 || M > r * 512) {
         int u0 = (r * 64 + lane) * 8;
         if (u0 > M - 8) u0 = M - 8;
-#pragma unroll
-        for (int j = 0; j < kHeadsPerWave; ++j) {
-          int h = j * kFWaves + wv;
-          if (h > H - 1) h = H - 1;
-          w2[j][r] = *reinterpret_cast<const u32x4*>(W2 + (size_t)h * M + u0);
-        }
+        w2[r] = *reinterpret_cast<const u32x4*>(W2 + (size_t)hw * M + u0);
       }
     }
+    // the first bias of the pair this thread finishes after the first barrier (pair = tid)
+    int mb = 2 * tid;
+    if (mb > M - 2) mb = M - 2;
+    const unsigned int raw = *reinterpret_cast<const unsigned int*>(b1 ? b1 + mb : static_cast<const unsigned short*>(a.k_new));
+    bias1 = b1 ? raw : 0u;
   } else {
     const u32x4* hid = reinterpret_cast<const u32x4*>(static_cast<const unsigned short*>(a.hidden_new) + (size_t)b * Dh);
     const u32x4* W = static_cast<const u32x4*>(a.W1);
     const int nchunk = Dh / 8;
 #pragma unroll
     for (int h = 0; h < 16; ++h) dot[h] = 0.f;
-    for (int c0 = 0; c0 < nchunk; c0 += 2 * kFThreads) {
-      // two rounds of loads in flight
-      u32x4 x[2], wt[2][16];
-      bool ok[2];
+    for (int c0 = 0; c0 < nchunk; c0 += kFThreads) {
+      int ch = c0 + tid;
+      const bool ok = ch < nchunk;
+      if (!ok) ch = nchunk - 1;
+      const u32x4 x = hid[ch];
+      u32x4 wt[16];
 #pragma unroll
-      for (int r = 0; r < 2; ++r) {
-        int ch = c0 + r * kFThreads + tid;
-        ok[r] = ch < nchunk;
-        if (!ok[r]) ch = nchunk - 1;
-        x[r] = hid[ch];
+      for (int h = 0; h < 16; ++h)
+        if (h < H) wt[h] = W[(size_t)h * nchunk + ch];
 #pragma unroll
-        for (int h = 0; h < 16; ++h)
-          if (h < H) wt[r][h] = W[(size_t)h * nchunk + ch];
-      }
-#pragma unroll
-      for (int r = 0; r < 2; ++r)
-#pragma unroll
-        for (int h = 0; h < 16; ++h)
-          if (h < H) dot[h] += ok[r] ? dot8_bf16(x[r], wt[r][h]) : 0.f;
+      for (int h = 0; h < 16; ++h)
+        if (h < H) dot[h] += ok ? dot8_bf16(x, wt[h]) : 0.f;
     }
   }
 
@@ -247,50 +238,41 @@ __global__ __launch_bounds__(kFThreads) void decode_finish_kernel(DecodeArgs a, 
   const int q = p - w;
   const int slot = (w > 0) ? (p % w) : 0;
   float s_q = 0.f;
+  u32x4 k_old = k_in, v_old = v_in;                      // no window: the new token itself may be kept
   if (w > 0) {
-#pragma unroll
-    for (int c = 0; c < NPER; ++c) {
-      const size_t ring_at = ((size_t)(b * H + head_r[c]) * w + slot) * lpr + piece_r[c];
-      k_old[c] = Kr[ring_at];
-      v_old[c] = Vr[ring_at];
-    }
-    s_q = a.score_ring[(size_t)(b * H + own_hc) * w + slot];
+    const size_t ring_at = ((size_t)bh_r * w + slot) * lpr + piece_r;
+    k_old = Kr[ring_at];
+    v_old = Vr[ring_at];
+    s_q = a.score_ring[(size_t)(b * H + hw) * w + slot];
   }
   if (a.block_table) {
-#pragma unroll
-    for (int c = 0; c < NPER; ++c) {
-      // paged prefix: the next row is row len % page_rows of the page in table slot
-      // len / page_rows.  Expressed as a slab whose row `len` is that row, with room for
-      // exactly one more row if the slot holds a page of the pool.
-      const int len = len_r[c] < 0 ? 0 : len_r[c];
-      const int pslot = len >> a.log_page;
-      const int pc = pslot < a.max_pages ? pslot : a.max_pages - 1;
-      const int entry = a.block_table[(size_t)(b * H + head_r[c]) * a.max_pages + pc];
-      const int page = pslot < a.max_pages ? entry : -1;
-      const bool ok = page >= 0 && page < a.num_pages;
-      cap_r[c] = ok ? len_r[c] + 1 : len_r[c];
-      slab_r[c] = (((long long)(ok ? page : 0)) << a.log_page) + (len & ((1 << a.log_page) - 1)) - len_r[c];
-    }
+    // paged prefix: the next row is row len % page_rows of the page in table slot
+    // len / page_rows.  Expressed as a slab whose row `len` is that row, with room for
+    // exactly one more row if the slot holds a page of the pool.
+    const int len = len_r < 0 ? 0 : len_r;
+    const int pslot = len >> a.log_page;
+    const int pc = pslot < a.max_pages ? pslot : a.max_pages - 1;
+    const int entry = a.block_table[(size_t)bh_r * a.max_pages + pc];
+    const int page = pslot < a.max_pages ? entry : -1;
+    const bool ok = page >= 0 && page < a.num_pages;
+    cap_r = ok ? len_r + 1 : len_r;
+    slab_r = (((long long)(ok ? page : 0)) << a.log_page) + (len & ((1 << a.log_page) - 1)) - len_r;
   }
 
-  // ---- 1. hidden activations (MLP) or per-wavefront sums (linear) into LDS; keep flags ----
+  // ---- 1. partial sums (MLP) or per-wavefront sums (linear) into LDS; keep flags ----
   if constexpr (kMlp) {
 #pragma unroll
     for (int r = 0; r < kUnitRounds; ++r) {
-      if (r == 0 || M > r * 2 * kFThreads) {
-        const int m0 = 2 * tid + r * 2 * kFThreads;
-        float z0 = 0.f, z1 = 0.f;                      // K-slices in a fixed order
+      if (r == 0 || M > r * 2 * kPairs) {
+        const int m0 = 2 * pr + r * 2 * kPairs;
+        float2 z = {0.f, 0.f};                             // this group's K-slices in order
 #pragma unroll
-        for (int ks = 0; ks < kMaxKSplit; ++ks) {
-          z0 += ks < ksplit ? part[r][ks].x : 0.f;
-          z1 += ks < ksplit ? part[r][ks].y : 0.f;
+        for (int j = 0; j < 4; ++j) {
+          const bool on = 4 * kq + j < ksplit;
+          z.x += on ? part[r][j].x : 0.f;
+          z.y += on ? part[r][j].y : 0.f;
         }
-        z0 += bf16_lo(bias1[r]);
-        z1 += bf16_hi(bias1[r]);
-        float2 gv;
-        gv.x = 0.5f * z0 * (1.0f + erff(z0 * 0.70710678118654752f));
-        gv.y = 0.5f * z1 * (1.0f + erff(z1 * 0.70710678118654752f));
-        if (m0 < M) *reinterpret_cast<float2*>(g + m0) = gv;
+        if (m0 < M) *reinterpret_cast<float2*>(zpart + (size_t)kq * M + m0) = z;
       }
     }
   } else {
@@ -302,76 +284,82 @@ __global__ __launch_bounds__(kFThreads) void decode_finish_kernel(DecodeArgs a, 
       }
     }
   }
-  if (w > 0 && owner) s_keep[own_h] = (q >= 0) && (s_q >= a.tau);
+  if (w > 0 && owner) s_keep[wv] = (q >= 0) && (s_q >= a.tau);
   __syncthreads();
 
   // ring -> prefix tail (kept), new -> ring slot, and the head's bookkeeping by the thread
   // that owns piece 0
   auto move_rows = [&]() {
-#pragma unroll
-    for (int c = 0; c < NPER; ++c) {
-      const int i = tid + c * kFThreads;
-      if (i < npieces) {
-        const int h = head_r[c], piece = piece_r[c], bh = b * H + h;
-        const bool keep = s_keep[h] != 0;
-        if (keep && len_r[c] < cap_r[c]) {
-          const size_t dst = ((size_t)slab_r[c] + len_r[c]) * lpr + piece;
-          Kp[dst] = (w > 0) ? k_old[c] : k_in[c];
-          Vp[dst] = (w > 0) ? v_old[c] : v_in[c];
-        }
-        if (w > 0) {
-          const size_t ring_at = ((size_t)bh * w + slot) * lpr + piece;
-          Kr[ring_at] = k_in[c];
-          Vr[ring_at] = v_in[c];
-        }
-        if (piece == 0 && keep) {
-          if (len_r[c] < cap_r[c]) {
-            a.prefix_pos[(size_t)slab_r[c] + len_r[c]] = q;
-            a.lengths[bh] = len_r[c] + 1;
-          } else if (a.error_flag) {
-            *a.error_flag = 1;
-          }
+    if (tid < npieces) {
+      const bool keep = s_keep[head_r] != 0;
+      if (keep && len_r < cap_r) {
+        const size_t dst = ((size_t)slab_r + len_r) * lpr + piece_r;
+        Kp[dst] = k_old;
+        Vp[dst] = v_old;
+      }
+      if (w > 0) {
+        const size_t ring_at = ((size_t)bh_r * w + slot) * lpr + piece_r;
+        Kr[ring_at] = k_in;
+        Vr[ring_at] = v_in;
+      }
+      if (piece_r == 0 && keep) {
+        if (len_r < cap_r) {
+          a.prefix_pos[(size_t)slab_r + len_r] = q;
+          a.lengths[bh_r] = len_r + 1;
+        } else if (a.error_flag) {
+          *a.error_flag = 1;
         }
       }
     }
   };
   if (w > 0) move_rows();
 
-  // ---- 2. scores of the new token: head 4j + wv by this wavefront, result in lane j ----
+  // ---- 2. scores of the new token: head wv by this wavefront, result in its lane 0 ----
   float s_new = 0.f;
   if constexpr (kMlp) {
+    // the groups' sums in a fixed order, bias, GELU: pair `tid`
+    if (2 * tid < M) {
+      float2 z = *reinterpret_cast<const float2*>(zpart + 2 * tid);
 #pragma unroll
-    for (int j = 0; j < kHeadsPerWave; ++j) {
-      if (j * kFWaves + wv < H) {
-        float acc = 0.f;
+      for (int x = 1; x < kKGroups; ++x) {
+        const float2 t = *reinterpret_cast<const float2*>(zpart + (size_t)x * M + 2 * tid);
+        z.x += t.x;
+        z.y += t.y;
+      }
+      float2 gv;
+      gv.x = gelu_erf(z.x + bf16_lo(bias1));
+      gv.y = gelu_erf(z.y + bf16_hi(bias1));
+      *reinterpret_cast<float2*>(g + 2 * tid) = gv;
+    }
+    __syncthreads();
+    if (wv < H) {
+      float acc = 0.f;
 #pragma unroll
-        for (int r = 0; r < kUnitRounds; ++r) {
-          if (r == 0 || M > r * 512) {
-            const int u0 = (r * 64 + lane) * 8;
-            if (u0 < M) {
-              const floatx4 g0 = *reinterpret_cast<const floatx4*>(g + u0);
-              const floatx4 g1 = *reinterpret_cast<const floatx4*>(g + u0 + 4);
-              const u32x4 wq = w2[j][r];
-              acc += g0[0] * bf16_lo(wq[0]) + g0[1] * bf16_hi(wq[0]) + g0[2] * bf16_lo(wq[1]) +
-                     g0[3] * bf16_hi(wq[1]) + g1[0] * bf16_lo(wq[2]) + g1[1] * bf16_hi(wq[2]) +
-                     g1[2] * bf16_lo(wq[3]) + g1[3] * bf16_hi(wq[3]);
-            }
+      for (int r = 0; r < kUnitRounds; ++r) {
+        if (r == 0 || M > r * 512) {
+          const int u0 = (r * 64 + lane) * 8;
+          if (u0 < M) {
+            const floatx4 g0 = *reinterpret_cast<const floatx4*>(g + u0);
+            const floatx4 g1 = *reinterpret_cast<const floatx4*>(g + u0 + 4);
+            const u32x4 wq = w2[r];
+            acc += g0[0] * bf16_lo(wq[0]) + g0[1] * bf16_hi(wq[0]) + g0[2] * bf16_lo(wq[1]) +
+                   g0[3] * bf16_hi(wq[1]) + g1[0] * bf16_lo(wq[2]) + g1[1] * bf16_hi(wq[2]) +
+                   g1[2] * bf16_lo(wq[3]) + g1[3] * bf16_hi(wq[3]);
           }
         }
-        acc = wave_sum(acc);
-        if (lane == j) s_new = acc;
       }
+      s_new = wave_sum(acc);
     }
   } else if (owner) {
 #pragma unroll
-    for (int x = 0; x < kFWaves; ++x) s_new += s_red[own_h][x];
+    for (int x = 0; x < kFWaves; ++x) s_new += s_red[wv][x];
   }
   s_new += bf16_bits_to_float(bias2);
   if (w > 0) {
-    if (owner) a.score_ring[(size_t)(b * H + own_h) * w + slot] = s_new;
+    if (owner) a.score_ring[(size_t)(b * H + wv) * w + slot] = s_new;
   } else {
     // no window: the new token itself is tested
-    if (owner) s_keep[own_h] = (q >= 0) && (s_new >= a.tau);
+    if (owner) s_keep[wv] = (q >= 0) && (s_new >= a.tau);
     __syncthreads();
     move_rows();
   }
@@ -396,15 +384,9 @@ int launch_decode_evict(const DecodeArgs& a, hipStream_t stream) {
         static_cast<const unsigned short*>(a.W1), static_cast<float*>(a.workspace), a.B,
         a.Dh, a.M, a.Dh / ks);
   }
-  const size_t lds = (size_t)(a.M > 0 ? a.M : 4) * sizeof(float);
-  const bool small = a.H * (a.D / 8) <= kFThreads;
-  if (a.M > 0) {
-    if (small) decode_finish_kernel<1, true><<<a.B, kFThreads, lds, stream>>>(a, ks);
-    else       decode_finish_kernel<4, true><<<a.B, kFThreads, lds, stream>>>(a, ks);
-  } else {
-    if (small) decode_finish_kernel<1, false><<<a.B, kFThreads, lds, stream>>>(a, ks);
-    else       decode_finish_kernel<4, false><<<a.B, kFThreads, lds, stream>>>(a, ks);
-  }
+  const size_t lds = (size_t)(a.M > 0 ? (1 + kKGroups) * a.M : 4) * sizeof(float);
+  if (a.M > 0) decode_finish_kernel<true><<<a.B, kFThreads, lds, stream>>>(a, ks);
+  else         decode_finish_kernel<false><<<a.B, kFThreads, lds, stream>>>(a, ks);
   return hipGetLastError() == hipSuccess ? KVZAP_OK : KVZAP_ERR_RUNTIME;
 }
 
