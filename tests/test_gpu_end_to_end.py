@@ -94,3 +94,69 @@ def test_compress_is_the_three_calls(name, T, padded):
     assert torch.equal(got[1][:kept], want[1][:kept])
     assert torch.equal(got[4][:kept].view(torch.int16), want[4][:kept].view(torch.int16))
     assert torch.equal(got[5][:kept].view(torch.int16), want[5][:kept].view(torch.int16))
+
+
+def test_compress_replayed_from_a_hip_graph_matches_eager():
+    """kvzap_compress (MLP scorer, top of Algorithm 1 to the gathered cache) captured once in
+    a HIP graph and replayed with new inputs in the same buffers; eager work and
+    synchronisation sit between the replays, and every replay equals the eager call bit for bit."""
+    wl = synth.with_size(synth.CONFIGS["c2_llama8b_32k_mlp"], T=3000 + 7, L=64)   # L > 1: a seed per "layer"
+    B, H, T, D, Dh, M = wl.B, wl.H, wl.T, wl.D, wl.Dh, wl.M
+    w = {k: (None if v is None else v.to(DEV)) for k, v in synth.make_weights(wl).items()}
+    L = binding.lib()
+    bf = torch.bfloat16
+    hid = torch.zeros((B, T, Dh), dtype=bf, device=DEV)
+    K = torch.zeros((B, H, T, D), dtype=bf, device=DEV)
+    V = torch.zeros_like(K)
+
+    def buffers():
+        return dict(scores=torch.zeros((B, H, T), dtype=torch.float32, device=DEV),
+                    idx=torch.zeros(B * H * T, dtype=torch.int32, device=DEV),
+                    n=torch.zeros((B, H), dtype=torch.int32, device=DEV),
+                    off=torch.zeros(B * H + 1, dtype=torch.int64, device=DEV),
+                    Ko=torch.zeros((B * H * T, D), dtype=bf, device=DEV),
+                    Vo=torch.zeros((B * H * T, D), dtype=bf, device=DEV),
+                    ws=torch.empty(binding.kvzap_workspace_bytes(binding.CALL_COMPRESS, B, T, Dh, M, H),
+                                   dtype=torch.uint8, device=DEV))
+
+    def call(o):
+        p = lambda t: None if t is None else t.data_ptr()
+        rc = L.kvzap_compress(p(hid), p(w["W1"]), p(w["b1"]), p(w["W2"]), p(w["b2"]), p(K), p(V),
+                              0.1, wl.window, None, p(o["scores"]), p(o["idx"]), p(o["n"]), p(o["off"]),
+                              p(o["Ko"]), p(o["Vo"]), B * H * T, B, T, Dh, M, H, D, p(o["ws"]),
+                              o["ws"].numel(), torch.cuda.current_stream().cuda_stream)
+        assert rc == 0
+
+    def set_inputs(i):
+        hid.copy_(synth.make_hidden(wl, 40 + i, DEV))
+        k, v = synth.make_kv(wl, 50 + i, DEV)
+        K.copy_(k); V.copy_(v)
+
+    eager, graphed = buffers(), buffers()
+    set_inputs(0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call(graphed)                                    # warm-up outside capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        call(graphed)
+    torch.cuda.synchronize()
+    kept_seen = set()
+    for i in range(4):
+        set_inputs(i)
+        call(eager)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        kept = int(eager["off"][-1])
+        kept_seen.add(kept)
+        assert 0 < kept < B * H * T
+        assert torch.equal(graphed["scores"], eager["scores"])
+        assert torch.equal(graphed["n"], eager["n"]) and torch.equal(graphed["off"], eager["off"])
+        assert torch.equal(graphed["idx"][:kept], eager["idx"][:kept])
+        assert torch.equal(graphed["Ko"][:kept].view(torch.int16), eager["Ko"][:kept].view(torch.int16))
+        assert torch.equal(graphed["Vo"][:kept].view(torch.int16), eager["Vo"][:kept].view(torch.int16))
+    assert len(kept_seen) > 1                            # the replays really saw different inputs
