@@ -363,14 +363,16 @@ __global__ __launch_bounds__(256) void attend_combine_kernel(
 }  // namespace
 
 // Chunks per split (one split = one wave).  Long splits amortise a wave's start-up (its
-// first loads are not overlapped with anything) and the partial result it writes; short
-// ones fill the chip when there are few heads.  Aim at ~8192 waves if every head were at
-// the bound, within 4..64 chunks (128..2048 rows); measured on 512 heads of 4k..32k rows:
-// 16 chunks 5.62, 32: 5.76, 64: 5.87, 128: 5.54 TB/s.
+// first loads are not overlapped with anything), the partial result it writes and the work
+// of the combine kernel, which folds every split of a head in one block; short ones fill
+// the chip when there are few heads.  Aim at ~2048 waves if every head were at the bound,
+// within 4..64 chunks (128..2048 rows).  Measured on 512 heads of 4k..32k rows: 16 chunks
+// 5.62, 32: 5.76, 64: 5.87, 128: 5.54 TB/s; on 8 heads of 131072 rows a target of 8192
+// waves (1025 splits per head) gives 4.4 TB/s, 2048 waves 5.2, 1024 waves 5.0.
 int attend_split_chunks(int BH, int max_rows, int window) {
   const long long ct = (max_rows + kChunkRows - 1) / kChunkRows +
                        ((window > 0 ? window : 0) + kChunkRows - 1) / kChunkRows;
-  long long want = ct * BH / 8192;
+  long long want = ct * BH / 2048;
   int spc = 4;
   while (spc < 64 && spc < want) spc *= 2;
   return spc;
