@@ -144,9 +144,11 @@ int kvzap_mask(const float* scores, float tau, int window,
  * App. B Eq. 5) whose weights do not change between calls: kvzap_score re-orders W1 into the
  * matrix cores' operand order in its workspace on every call; kvzap_prepare_scorer does that
  * once, into a buffer the caller keeps (W1_prepared: device, 256-byte aligned, at least
- * kvzap_workspace_bytes(KVZAP_CALL_SCORE, ...) bytes, not overlapping W1), and
+ * M * Dh * 2 bytes rounded up to 256, not overlapping W1), and
  * kvzap_score_prepared takes that buffer in place of W1 and needs no workspace.  Scores are
- * bit-identical to kvzap_score's.  M > 0 only (the linear surrogate has nothing to prepare);
+ * bit-identical to kvzap_score's for more than 1024 tokens (B*T); up to 1024 tokens
+ * kvzap_score splits the first projection over K (it has the workspace for the partial
+ * sums) and the two agree within fp32 rounding.  M > 0 only (the linear surrogate has nothing to prepare);
  * other arguments, layouts and errors as kvzap_score.  The prepared layout is private to
  * the library version that wrote it.
  */

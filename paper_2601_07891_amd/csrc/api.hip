@@ -73,10 +73,11 @@ size_t kvzap_workspace_bytes(int which_call, int B, int T, int Dh, int M, int H)
       return kvzap::decode_workspace_bytes(B, Dh, M, H);
     case KVZAP_CALL_SCORE:
       if (check_scorer_shape(Dh, M, H) != KVZAP_OK) return 0;
-      return M > 0 ? kvzap::align_up((size_t)M * Dh * 2, 256) : 0;   // W1 in fragment order
+      // W1 in fragment order, or the first projection's partial sums of a short prompt
+      return M > 0 ? kvzap::score_mlp_workspace_bytes((long long)(B > 0 ? B : 0) * (T > 0 ? T : 0), Dh, M) : 0;
     case KVZAP_CALL_COMPRESS: {
       if (check_scorer_shape(Dh, M, H) != KVZAP_OK || (long long)B * H > 65535) return 0;
-      const size_t a = M > 0 ? kvzap::align_up((size_t)M * Dh * 2, 256) : 0;
+      const size_t a = M > 0 ? kvzap::score_mlp_workspace_bytes((long long)(B > 0 ? B : 0) * (T > 0 ? T : 0), Dh, M) : 0;
       const size_t b = mask_workspace(B, H, T);
       return a > b ? a : b;
     }
@@ -115,7 +116,7 @@ int check_score(const void* hidden, const void* W1, const void* b1, const void* 
       !aligned16(b1) || !aligned16(b2))
     return KVZAP_ERR_ALIGN;
   if (M > 0) {
-    const size_t need = kvzap::align_up((size_t)M * Dh * 2, 256);
+    const size_t need = kvzap::score_mlp_workspace_bytes((long long)B * T, Dh, M);
     if (!workspace || !aligned256(workspace) || workspace_bytes < need) return KVZAP_ERR_WORKSPACE;
   }
   return KVZAP_OK;
@@ -197,7 +198,7 @@ int kvzap_score_prepared(const void* hidden, const void* W1_prepared, const void
   if (M <= 0) return KVZAP_ERR_SHAPE;
   // as kvzap_score, with the workspace requirement replaced by the prepared copy's alignment
   int rc = check_score(hidden, W1_prepared, b1, W2, b2, scores, B, T, Dh, M, H,
-                       W1_prepared, kvzap::align_up((size_t)M * Dh * 2, 256));
+                       W1_prepared, ~(size_t)0);
   if (rc != KVZAP_OK) return rc == KVZAP_ERR_WORKSPACE ? KVZAP_ERR_ALIGN : rc;
   if ((long long)B * T == 0) return KVZAP_OK;
   return kvzap::launch_score_mlp(hidden, W1_prepared, b1, W2, b2, scores, B, T, Dh, M, H, nullptr,

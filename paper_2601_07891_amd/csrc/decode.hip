@@ -368,6 +368,29 @@ __global__ __launch_bounds__(kFThreads) void decode_finish_kernel(DecodeArgs a, 
 
 }  // namespace
 
+// The skinny first projection on its own (the prefill scorer uses it for short prompts):
+// partial[ks][rows][M] fp32, ks = skinny_ksplit(rows, Dh, M, target_blocks).
+int skinny_ksplit(long long rows, int Dh, int M, int target_blocks) {
+  const long long nub = M / 32, ntb = (rows + 63) / 64;
+  long long target = target_blocks / (nub * ntb);
+  if (target < 1) target = 1;
+  if (target > kMaxKSplit) target = kMaxKSplit;
+  const int units = Dh / 64;               // a slice is a multiple of 64 inputs
+  int ks = 1;
+  for (int d = 1; d <= units && d <= target; ++d)
+    if (units % d == 0) ks = d;
+  return ks;
+}
+
+int launch_skinny_gemm(const void* hidden, const void* W1, float* partial, long long rows, int Dh,
+                       int M, int ks, hipStream_t stream) {
+  const dim3 grid(M / 32, ks, (unsigned)((rows + 63) / 64));
+  decode_partial_kernel<<<grid, kPThreads, 0, stream>>>(
+      static_cast<const unsigned short*>(hidden), static_cast<const unsigned short*>(W1), partial,
+      (int)rows, Dh, M, Dh / ks);
+  return hipGetLastError() == hipSuccess ? KVZAP_OK : KVZAP_ERR_RUNTIME;
+}
+
 size_t decode_workspace_bytes(int B, int Dh, int M, int H) {
   (void)H;
   if (M == 0) return 0;

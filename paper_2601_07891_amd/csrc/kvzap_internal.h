@@ -99,6 +99,11 @@ int launch_compact(const void* K, const void* V, const int32_t* keep_idx,
 int launch_score_linear(const void* hidden, const void* W, const void* b, float* scores,
                         int B, int T, int Dh, int H, hipStream_t stream);
 
+int skinny_ksplit(long long rows, int Dh, int M, int target_blocks);
+int launch_skinny_gemm(const void* hidden, const void* W1, float* partial, long long rows, int Dh,
+                       int M, int ks, hipStream_t stream);
+// bytes kvzap_score's workspace needs for an MLP surrogate on `rows` tokens
+size_t score_mlp_workspace_bytes(long long rows, int Dh, int M);
 int launch_prepare_w1(const void* W1, int Dh, int M, void* out, hipStream_t stream);
 // workspace == nullptr: W1 is the copy made by launch_prepare_w1
 int launch_score_mlp(const void* hidden, const void* W1, const void* b1, const void* W2,

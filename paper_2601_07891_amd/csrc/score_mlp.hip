@@ -539,6 +539,66 @@ int launch_one(const void* hidden, const void* W1, const void* b1, const void* W
   return hipGetLastError() == hipSuccess ? KVZAP_OK : KVZAP_ERR_RUNTIME;
 }
 
+// ---- very short prompts ----
+// One block of the kernels above walks all of K for its tokens, which takes 50-85 us however
+// few blocks there are.  Up to kTwoStageRows tokens the first projection is instead cut over
+// (unit block x K-slice x 64 tokens) blocks (the decode path's skinny GEMM, fp32 partial
+// sums in the workspace) and this kernel finishes: K-slices in a fixed order, bias, GELU,
+// second projection in fp32.  One wavefront per token, 8 hidden units per lane and round.
+// Measured (D_h 4096, M 512; this path / one kernel): 256 tokens 26 / 85 us, 1024: 49 / 85,
+// 2048: 74 / 85, 4096: 120 / 86 -- the skinny GEMM reads its operands from global memory in
+// 32-byte pieces and re-reads W1 per 64 tokens, so it loses beyond ~2000 tokens.
+constexpr long long kTwoStageRows = 1024;
+constexpr int kTwoStageBlocks = 2048;
+
+__global__ __launch_bounds__(256) void score_finish_kernel(
+    const float* __restrict__ partial, const unsigned short* __restrict__ b1,
+    const unsigned short* __restrict__ W2, const unsigned short* __restrict__ b2,
+    float* __restrict__ scores, long long rows, int T, int M, int H, int ks) {
+  const int lane = threadIdx.x & 63;
+  const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;                                  // uniform per wavefront; no barrier below
+  float acc[16];
+#pragma unroll
+  for (int h = 0; h < 16; ++h) acc[h] = 0.f;
+  for (int u0 = lane * 8; u0 < M; u0 += 512) {
+    floatx4 z0 = {0.f, 0.f, 0.f, 0.f}, z1 = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < ks; ++s) {
+      const float* p = partial + ((size_t)s * rows + row) * M + u0;
+      z0 += *reinterpret_cast<const floatx4*>(p);
+      z1 += *reinterpret_cast<const floatx4*>(p + 4);
+    }
+    u32x4 bb = {0u, 0u, 0u, 0u};
+    if (b1) bb = *reinterpret_cast<const u32x4*>(b1 + u0);
+    float g[8];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      g[2 * e] = gelu_exact((e < 2 ? z0[2 * e] : z1[2 * e - 4]) + __uint_as_float(bb[e] << 16));
+      g[2 * e + 1] = gelu_exact((e < 2 ? z0[2 * e + 1] : z1[2 * e - 3]) + __uint_as_float(bb[e] & 0xffff0000u));
+    }
+#pragma unroll
+    for (int h = 0; h < 16; ++h) {
+      if (h < H) {
+        const u32x4 w = *reinterpret_cast<const u32x4*>(W2 + (size_t)h * M + u0);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          acc[h] += g[2 * e] * __uint_as_float(w[e] << 16) + g[2 * e + 1] * __uint_as_float(w[e] & 0xffff0000u);
+      }
+    }
+  }
+  const long long bidx = row / T;
+  const int t = (int)(row - bidx * T);
+#pragma unroll
+  for (int h = 0; h < 16; ++h) {
+    if (h < H) {
+      float v = acc[h];
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+      if (lane == 0) scores[((size_t)bidx * H + h) * T + t] = v + (b2 ? bf16_bits_to_float(b2[h]) : 0.f);
+    }
+  }
+}
+
 __global__ __launch_bounds__(256) void copy_w1_kernel(const u32x4* __restrict__ W1,
                                                       u32x4* __restrict__ out, int n) {
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x)
@@ -560,10 +620,29 @@ int launch_prepare_w1(const void* W1, int Dh, int M, void* out, hipStream_t stre
   return hipGetLastError() == hipSuccess ? KVZAP_OK : KVZAP_ERR_RUNTIME;
 }
 
+size_t score_mlp_workspace_bytes(long long rows, int Dh, int M) {
+  size_t need = align_up((size_t)M * Dh * 2, 256);                 // W1 in fragment order
+  if (rows > 0 && rows <= kTwoStageRows) {
+    const size_t part = align_up((size_t)skinny_ksplit(rows, Dh, M, kTwoStageBlocks) * rows * M * sizeof(float), 256);
+    need = need > part ? need : part;
+  }
+  return need;
+}
+
 int launch_score_mlp(const void* hidden, const void* W1, const void* b1, const void* W2,
                      const void* b2, float* scores, int B, int T, int Dh, int M, int H,
                      void* workspace, hipStream_t stream) {
   const long long rows = (long long)B * T;
+  if (workspace && rows <= kTwoStageRows) {        // short prompt and the original W1 at hand
+    const int ks = skinny_ksplit(rows, Dh, M, kTwoStageBlocks);
+    const int rc = launch_skinny_gemm(hidden, W1, static_cast<float*>(workspace), rows, Dh, M, ks, stream);
+    if (rc != KVZAP_OK) return rc;
+    score_finish_kernel<<<dim3((unsigned)((rows + 3) / 4)), 256, 0, stream>>>(
+        static_cast<const float*>(workspace), static_cast<const unsigned short*>(b1),
+        static_cast<const unsigned short*>(W2), static_cast<const unsigned short*>(b2), scores,
+        rows, T, M, H, ks);
+    return hipGetLastError() == hipSuccess ? KVZAP_OK : KVZAP_ERR_RUNTIME;
+  }
   const bool frag = (Dh / kBK) >= kPD + 1;     // the main variant needs at least kPD+1 K tiles
 #define KVZAP_MLP_CASE(UBV)                                                                     \
   case UBV:                                                                                     \

@@ -49,7 +49,10 @@ def test_status_strings(lib):
 
 def test_workspace_queries(lib):
     q = lib.kvzap_workspace_bytes
-    assert q(binding.CALL_SCORE, 1, 1024, 4096, 512, 8) == 512 * 4096 * 2   # re-ordered copy of W1
+    assert q(binding.CALL_SCORE, 1, 131072, 4096, 512, 8) == 512 * 4096 * 2   # re-ordered copy of W1
+    # a short prompt takes the split first projection: fp32 partial sums of up to 16 K-slices
+    n = q(binding.CALL_SCORE, 1, 1024, 4096, 512, 8)
+    assert 1024 * 512 * 4 <= n <= 16 * 1024 * 512 * 4 and n % 256 == 0
     assert q(binding.CALL_SCORE, 1, 1024, 4096, 0, 8) == 0
     assert q(binding.CALL_COMPACT, 1, 1024, 0, 0, 8) == 0
     n = q(binding.CALL_MASK, 1, 131072, 0, 0, 8)
@@ -87,7 +90,7 @@ def test_score_argument_errors(lib):
 
 def test_prepared_scorer_argument_errors(lib):
     f = lib.kvzap_prepare_scorer
-    need = lib.kvzap_workspace_bytes(binding.CALL_SCORE, 1, 1, 4096, 512, 8)
+    need = lib.kvzap_workspace_bytes(binding.CALL_SCORE, 1, 131072, 4096, 512, 8)
     Q = 0x4000000
     assert f(None, 4096, 512, Q, need, None) == ERR["null"]
     assert f(P, 4096, 512, None, need, None) == ERR["null"]
