@@ -146,9 +146,9 @@ int kvzap_mask(const float* scores, float tau, int window,
  * once, into a buffer the caller keeps (W1_prepared: device, 256-byte aligned, at least
  * M * Dh * 2 bytes rounded up to 256, not overlapping W1), and
  * kvzap_score_prepared takes that buffer in place of W1 and needs no workspace.  Scores are
- * bit-identical to kvzap_score's for more than 1024 tokens (B*T); up to 1024 tokens
- * kvzap_score splits the first projection over K (it has the workspace for the partial
- * sums) and the two agree within fp32 rounding.  M > 0 only (the linear surrogate has nothing to prepare);
+ * bit-identical to kvzap_score's when that runs the same single kernel (from about 16k
+ * tokens); for shorter inputs kvzap_score splits the first projection over K (it has the
+ * workspace for the partial sums) and the two agree within fp32 rounding.  M > 0 only (the linear surrogate has nothing to prepare);
  * other arguments, layouts and errors as kvzap_score.  The prepared layout is private to
  * the library version that wrote it.
  */

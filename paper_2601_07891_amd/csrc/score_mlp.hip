@@ -244,12 +244,14 @@ __global__ __launch_bounds__(256) void arrange_w1_kernel(const u32x4* __restrict
   }
 }
 
-template <int UB, int TB>   // UB 32-unit blocks per wavefront, TB 32-token blocks per block
+// UB 32-unit blocks per wavefront, TB 32-token blocks per block; kSplit: the block covers one
+// K-slice (blockIdx.y) and writes its part of the first projection to `partial`
+template <int UB, int TB, bool kSplit>
 __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
     const unsigned short* hidden, const unsigned char* W1f,   // not __restrict__: their loads must stay ordered w.r.t. the waits
     const unsigned short* __restrict__ b1, const unsigned short* __restrict__ W2,
     const unsigned short* __restrict__ b2, float* __restrict__ scores,
-    long long rows, int T, int Dh, int H) {
+    long long rows, int T, int Dh, int H, int nk, float* __restrict__ partial) {
   constexpr int U = 128 * UB;
   constexpr int TOK = 32 * TB;               // tokens per block
   constexpr int STAGE = TOK * 128;           // bytes per LDS stage (TOK rows of one K tile)
@@ -284,7 +286,9 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
 
   // hidden load-to-LDS: instruction j (0..3) of wavefront w fills LDS chunk j*4+w of a
   // stage = rows (j*4+w)*8 + lane/8, physical piece lane%8 <- logical piece (lane%8) ^ (row%8)
-  const unsigned char* hb = reinterpret_cast<const unsigned char*>(hidden + (size_t)row0 * Dh);
+  // blockIdx.y: the K-slice of nk tiles this block covers (one slice unless `partial` is set)
+  const int kt0 = kSplit ? blockIdx.y * nk : 0;
+  const unsigned char* hb = reinterpret_cast<const unsigned char*>(hidden + (size_t)row0 * Dh) + (size_t)kt0 * (kBK * 2);
   unsigned h_off[NDJ];
 #pragma unroll
   for (int j = 0; j < NDJ; ++j) {
@@ -299,7 +303,7 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
                      lds0 + (unsigned)((tile % kNS) * STAGE + (j * 4 + wid) * 1024));
   };
   // A fragments of this wavefront: unit blocks rb = wid*UB + ub
-  const unsigned char* abase = W1f + ((size_t)wid * UB * 4) * 1024 + lane * 16;
+  const unsigned char* abase = W1f + ((size_t)kt0 * (U / 32) * 4 + (size_t)wid * UB * 4) * 1024 + lane * 16;
   auto aload = [&](int tile, int ub, int kk) -> bf16x8 {
     return *reinterpret_cast<const bf16x8*>(abase + ((size_t)(tile * (U / 32) + ub) * 4 + kk) * 1024);
   };
@@ -312,7 +316,7 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[ub][tb][e] = 0.0f;
 
-  const int nk = Dh / kBK;                 // >= kPD + 1 (checked by the launcher)
+  // nk >= kPD + 1 tiles (checked by the launcher)
   bf16x8 a[4][UB];                         // a[kk]: step kk of the current tile, then of the next
   bf16x8 b[2][TB];
   // ---- prologue: hidden tiles 0..kPD-1 in flight, A fragments of tile 0 ----
@@ -412,6 +416,27 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
   for (; t + kPD < nk; ++t) tile_body(t, std::true_type{}, std::true_type{});
   for (; t + 1 < nk; ++t) tile_body(t, std::true_type{}, std::false_type{});
   tile_body(t, std::false_type{}, std::false_type{});
+  if constexpr (kSplit) {
+    // split-K launch: the slice's part of the first projection goes to partial[slice][row][unit]
+    // as it is; bias, GELU and the second projection follow in score_finish_kernel
+    float* out = partial + ((size_t)blockIdx.y * rows + row0) * U + wid * (32 * UB) + 4 * kg;
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) {
+      const int r = 32 * tb + l32;
+      if (r < rows_here) {
+#pragma unroll
+        for (int ub = 0; ub < UB; ++ub)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            floatx4 v4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v4[e] = acc[ub][tb][4 * q + e];
+            *reinterpret_cast<floatx4*>(out + (size_t)r * U + 32 * ub + 8 * q) = v4;
+          }
+      }
+    }
+    return;
+  }
   __syncthreads();      // LDS is reused for the reduction below
 
   // ---- epilogue: bias + GELU, then the M -> H projection as a second MFMA ----
@@ -494,61 +519,18 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
   }
 }
 
-template <int UB, int TB>
-int launch_frag(const void* hidden, const void* W1, const void* b1, const void* W2,
-                const void* b2, float* scores, long long rows, int T, int Dh, int H,
-                void* workspace, hipStream_t stream) {
-  constexpr int TOK = 32 * TB;
-  constexpr size_t ring = (size_t)kNS * TOK * 128;
-  static_assert(ring >= (size_t)4 * 16 * TOK * sizeof(float), "reduction buffer fits");
-  constexpr size_t lds = ring + (size_t)16 * (128 * UB) * 2 + (size_t)(128 * UB) * 4;   // + W2, b1
-  // once per process, which drives one GPU (thread-safe: a function-local static)
-  static const hipError_t attr_rc =
-      hipFuncSetAttribute(reinterpret_cast<const void*>(score_mlp_frag_kernel<UB, TB>),
-      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  if (attr_rc != hipSuccess) return KVZAP_ERR_RUNTIME;
-  const int M = 128 * UB;
-  // workspace == nullptr: W1 already is the fragment-ordered copy (launch_prepare_w1)
-  if (workspace)
-    arrange_w1_kernel<<<512, 256, 0, stream>>>(static_cast<const u32x4*>(W1),
-                                               static_cast<u32x4*>(workspace), M, Dh);
-  const void* w1f = workspace ? workspace : W1;
-  const long long blocks = (rows + TOK - 1) / TOK;
-  score_mlp_frag_kernel<UB, TB><<<dim3((unsigned)blocks), 256, lds, stream>>>(
-      static_cast<const unsigned short*>(hidden), static_cast<const unsigned char*>(w1f),
-      static_cast<const unsigned short*>(b1), static_cast<const unsigned short*>(W2),
-      static_cast<const unsigned short*>(b2), scores, rows, T, Dh, H);
-  return hipGetLastError() == hipSuccess ? KVZAP_OK : KVZAP_ERR_RUNTIME;
-}
-
-template <int UB>
-int launch_one(const void* hidden, const void* W1, const void* b1, const void* W2,
-               const void* b2, float* scores, long long rows, int T, int Dh, int H,
-               hipStream_t stream) {
-  constexpr size_t lds = (size_t)(128 * UB + kTok) * 128;
-  // once per process, which drives one GPU (thread-safe: a function-local static)
-  static const hipError_t attr_rc =
-      hipFuncSetAttribute(reinterpret_cast<const void*>(score_mlp_kernel<UB>),
-      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  if (attr_rc != hipSuccess) return KVZAP_ERR_RUNTIME;
-  const long long blocks = (rows + kTok - 1) / kTok;
-  score_mlp_kernel<UB><<<dim3((unsigned)blocks), kThreads, lds, stream>>>(
-      static_cast<const unsigned short*>(hidden), static_cast<const unsigned short*>(W1),
-      static_cast<const unsigned short*>(b1), static_cast<const unsigned short*>(W2),
-      static_cast<const unsigned short*>(b2), scores, rows, T, Dh, H);
-  return hipGetLastError() == hipSuccess ? KVZAP_OK : KVZAP_ERR_RUNTIME;
-}
-
-// ---- very short prompts ----
+// ---- short prompts ----
 // One block of the kernels above walks all of K for its tokens, which takes 50-85 us however
-// few blocks there are.  Up to kTwoStageRows tokens the first projection is instead cut over
-// (unit block x K-slice x 64 tokens) blocks (the decode path's skinny GEMM, fp32 partial
-// sums in the workspace) and this kernel finishes: K-slices in a fixed order, bias, GELU,
-// second projection in fp32.  One wavefront per token, 8 hidden units per lane and round.
-// Measured (D_h 4096, M 512; this path / one kernel): 256 tokens 26 / 85 us, 1024: 49 / 85,
-// 2048: 74 / 85, 4096: 120 / 86 -- the skinny GEMM reads its operands from global memory in
-// 32-byte pieces and re-reads W1 per 64 tokens, so it loses beyond ~2000 tokens.
-constexpr long long kTwoStageRows = 1024;
+// few blocks there are.  Two remedies, both with the first projection's partial sums in the
+// workspace and this kernel to finish (K-slices in a fixed order, bias, GELU, second
+// projection in fp32; one wavefront per token, 8 hidden units per lane and round):
+//  * while the token blocks do not fill the chip, the main kernel is cut over K as well
+//    (frag_ksplit): 37-50 us from 640 to 4096 tokens, 68 us at 8192, against 85-88 us;
+//  * up to kTwoStageRows tokens the decode path's skinny GEMM over (unit block x K-slice x
+//    64 tokens) blocks is faster still (128 tokens 20 us, 256: 26 us); it reads its operands
+//    from global memory in 32-byte pieces and re-reads W1 per 64 tokens, so it loses beyond
+//    a few hundred tokens (512: 38 us, 1024: 49 us, 4096: 120 us).
+constexpr long long kTwoStageRows = 384;
 constexpr int kTwoStageBlocks = 2048;
 
 __global__ __launch_bounds__(256) void score_finish_kernel(
@@ -599,6 +581,81 @@ __global__ __launch_bounds__(256) void score_finish_kernel(
   }
 }
 
+// K-slices for a launch of `blocks` token blocks over nk_total K tiles: enough blocks for the
+// chip's 256 CUs, slices of at least kPD + 1 tiles that divide K evenly, at most 8.
+inline int frag_ksplit(long long blocks, int nk_total) {
+  int ks = 1;
+  for (int d = 2; d <= 8; ++d)
+    if (nk_total % d == 0 && nk_total / d >= kPD + 1 && blocks * d <= 256 && blocks <= 112) ks = d;
+  return ks;
+}
+
+template <int UB, int TB>
+int launch_frag(const void* hidden, const void* W1, const void* b1, const void* W2,
+                const void* b2, float* scores, long long rows, int T, int Dh, int H,
+                void* workspace, hipStream_t stream) {
+  constexpr int TOK = 32 * TB;
+  constexpr size_t ring = (size_t)kNS * TOK * 128;
+  static_assert(ring >= (size_t)4 * 16 * TOK * sizeof(float), "reduction buffer fits");
+  constexpr size_t lds = ring + (size_t)16 * (128 * UB) * 2 + (size_t)(128 * UB) * 4;   // + W2, b1
+  // once per process, which drives one GPU (thread-safe: a function-local static)
+  static const hipError_t attr_rc =
+      hipFuncSetAttribute(reinterpret_cast<const void*>(score_mlp_frag_kernel<UB, TB, false>),
+      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  static const hipError_t attr_rc_split =
+      hipFuncSetAttribute(reinterpret_cast<const void*>(score_mlp_frag_kernel<UB, TB, true>),
+      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (attr_rc != hipSuccess || attr_rc_split != hipSuccess) return KVZAP_ERR_RUNTIME;
+  const int M = 128 * UB;
+  // workspace == nullptr: W1 already is the fragment-ordered copy (launch_prepare_w1)
+  if (workspace)
+    arrange_w1_kernel<<<512, 256, 0, stream>>>(static_cast<const u32x4*>(W1),
+                                               static_cast<u32x4*>(workspace), M, Dh);
+  const void* w1f = workspace ? workspace : W1;
+  const long long blocks = (rows + TOK - 1) / TOK;
+  // Few blocks (mid-length prompts): a block needs 50-85 us for all of K whatever the grid,
+  // so K is cut over blockIdx.y and the epilogue moves to score_finish_kernel; the partial
+  // sums live behind the fragment copy in the workspace (only with a workspace).
+  const int ks = workspace ? frag_ksplit(blocks, Dh / kBK) : 1;
+  float* partial = ks > 1 ? reinterpret_cast<float*>(static_cast<char*>(workspace) +
+                                                     align_up((size_t)M * Dh * 2, 256))
+                          : nullptr;
+  if (ks > 1)
+    score_mlp_frag_kernel<UB, TB, true><<<dim3((unsigned)blocks, ks), 256, lds, stream>>>(
+        static_cast<const unsigned short*>(hidden), static_cast<const unsigned char*>(w1f),
+        static_cast<const unsigned short*>(b1), static_cast<const unsigned short*>(W2),
+        static_cast<const unsigned short*>(b2), scores, rows, T, Dh, H, Dh / kBK / ks, partial);
+  else
+    score_mlp_frag_kernel<UB, TB, false><<<dim3((unsigned)blocks), 256, lds, stream>>>(
+        static_cast<const unsigned short*>(hidden), static_cast<const unsigned char*>(w1f),
+        static_cast<const unsigned short*>(b1), static_cast<const unsigned short*>(W2),
+        static_cast<const unsigned short*>(b2), scores, rows, T, Dh, H, Dh / kBK, nullptr);
+  if (hipGetLastError() != hipSuccess) return KVZAP_ERR_RUNTIME;
+  if (ks > 1)
+    score_finish_kernel<<<dim3((unsigned)((rows + 3) / 4)), 256, 0, stream>>>(
+        partial, static_cast<const unsigned short*>(b1), static_cast<const unsigned short*>(W2),
+        static_cast<const unsigned short*>(b2), scores, rows, T, M, H, ks);
+  return hipGetLastError() == hipSuccess ? KVZAP_OK : KVZAP_ERR_RUNTIME;
+}
+
+template <int UB>
+int launch_one(const void* hidden, const void* W1, const void* b1, const void* W2,
+               const void* b2, float* scores, long long rows, int T, int Dh, int H,
+               hipStream_t stream) {
+  constexpr size_t lds = (size_t)(128 * UB + kTok) * 128;
+  // once per process, which drives one GPU (thread-safe: a function-local static)
+  static const hipError_t attr_rc =
+      hipFuncSetAttribute(reinterpret_cast<const void*>(score_mlp_kernel<UB>),
+      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (attr_rc != hipSuccess) return KVZAP_ERR_RUNTIME;
+  const long long blocks = (rows + kTok - 1) / kTok;
+  score_mlp_kernel<UB><<<dim3((unsigned)blocks), kThreads, lds, stream>>>(
+      static_cast<const unsigned short*>(hidden), static_cast<const unsigned short*>(W1),
+      static_cast<const unsigned short*>(b1), static_cast<const unsigned short*>(W2),
+      static_cast<const unsigned short*>(b2), scores, rows, T, Dh, H);
+  return hipGetLastError() == hipSuccess ? KVZAP_OK : KVZAP_ERR_RUNTIME;
+}
+
 __global__ __launch_bounds__(256) void copy_w1_kernel(const u32x4* __restrict__ W1,
                                                       u32x4* __restrict__ out, int n) {
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x)
@@ -625,6 +682,11 @@ size_t score_mlp_workspace_bytes(long long rows, int Dh, int M) {
   if (rows > 0 && rows <= kTwoStageRows) {
     const size_t part = align_up((size_t)skinny_ksplit(rows, Dh, M, kTwoStageBlocks) * rows * M * sizeof(float), 256);
     need = need > part ? need : part;
+  } else if (rows > 0 && (Dh / kBK) >= kPD + 1) {
+    // mid-length prompts: the main kernel split over K, partial sums behind the fragment copy
+    const int tok = 32 * (M / 128 <= 4 ? 4 : 3);
+    const int ks = frag_ksplit((rows + tok - 1) / tok, Dh / kBK);
+    if (ks > 1) need += align_up((size_t)ks * rows * M * sizeof(float), 256);
   }
   return need;
 }

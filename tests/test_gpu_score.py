@@ -72,8 +72,9 @@ MLP_SHAPES = [(1, 300, 256, 128, 8), (2, 129, 1024, 128, 8), (1, 1000, 4096, 512
               (1, 97, 256, 640, 8), (1, 500, 192, 512, 8)]                          # 4 tiles; D_h < 256
 
 
-# kvzap_score takes the split first projection up to 1024 tokens; kvzap_score_prepared always
-# the one-kernel path, so both see every shape
+# kvzap_score splits the first projection of short and mid-length prompts (a skinny GEMM up
+# to 384 tokens, the main kernel cut over K while its token blocks do not fill the chip);
+# kvzap_score_prepared always takes the one-kernel path, so both see every shape
 @pytest.mark.parametrize("entry", ["score", "prepared"])
 @pytest.mark.parametrize("B,T,Dh,M,H", MLP_SHAPES)
 def test_mlp_random(B, T, Dh, M, H, entry):
@@ -97,8 +98,9 @@ def test_mlp_random(B, T, Dh, M, H, entry):
 
 @pytest.mark.parametrize("B,T,Dh,M,H", [(1, 1024 + 77, 4096, 512, 8), (3, 731, 1024, 128, 8),
                                         (1, 1025, 5120, 640, 8)])
-def test_mlp_one_kernel_path_through_kvzap_score(B, T, Dh, M, H):
-    # just past the short-prompt limit, ragged last block, several sequences
+def test_mlp_split_k_path_through_kvzap_score(B, T, Dh, M, H):
+    # just past the short-prompt limit: the main kernel cut over K, ragged last block,
+    # several sequences
     wl = synth.Workload("t", L=1, B=B, T=T, Dh=Dh, H=H, scorer="mlp", seed=T, bias_std=0.1)
     w = synth.make_weights(wl); hid = synth.make_hidden(wl)
     assert B * T > 1024
@@ -144,13 +146,16 @@ def test_scores_deterministic():
     assert torch.equal(a, b)
 
 
-@pytest.mark.parametrize("B,T,Dh,M,H", [(1, 3000, 4096, 512, 8), (1, 1024 + 257, 5120, 640, 8),
-                                        (2, 700, 320, 256, 4), (1, 1500, 192, 512, 8),
-                                        (1, 1000, 4096, 512, 8)])
-def test_prepared_weights_give_the_same_scores(B, T, Dh, M, H):
+# exact: kvzap_score runs the same single kernel as kvzap_score_prepared (enough token blocks
+# to fill the chip, or too few K tiles to split); otherwise it splits K and finishes in fp32
+@pytest.mark.parametrize("B,T,Dh,M,H,exact", [(1, 17000, 4096, 512, 8, True), (1, 3000, 4096, 512, 8, False),
+                                              (1, 1024 + 257, 5120, 640, 8, False),
+                                              (2, 700, 320, 256, 4, True), (1, 1500, 192, 512, 8, True),
+                                              (1, 1000, 4096, 512, 8, False)])
+def test_prepared_weights_give_the_same_scores(B, T, Dh, M, H, exact):
     # W1 re-ordered once and reused, also after the original W1 is gone and on repeated calls:
-    # the scores of kvzap_score bit for bit where both run the same kernel (more than 1024
-    # tokens), within rounding for a short prompt (kvzap_score then splits the first projection)
+    # the scores of kvzap_score, bit for bit where both run the same kernel, within rounding
+    # where kvzap_score uses its workspace to split the first projection
     wl = synth.Workload("t", L=1, B=B, T=T, Dh=Dh, H=H, scorer="mlp", seed=T + M, bias_std=0.1)
     g = torch.Generator().manual_seed(T)
     w = _dev({"W1": (torch.randn((M, Dh), generator=g) * Dh ** -0.5).bfloat16(),
@@ -165,7 +170,7 @@ def test_prepared_weights_give_the_same_scores(B, T, Dh, M, H):
     for _ in range(2):
         got = binding.kvzap_score_prepared(hid, prep, w["b1"], w["W2"], w["b2"])
         torch.cuda.synchronize()
-        if B * T > 1024:
+        if exact:
             assert torch.equal(got, want)
         else:
             assert (got - want).abs().max().item() < 1e-3
