@@ -9,6 +9,11 @@
 // are then fused into the epilogue without moving data between lanes, and the
 // [tokens x M] activation never exists in memory.
 //
+// Which kernel runs (launch_score_mlp): D_h >= 256 takes score_mlp_frag_kernel (below, the
+// one the throughput figures are about) -- cut over K as well while its token blocks do not
+// fill the chip, and replaced by the decode path's skinny GEMM for a few hundred tokens
+// (both finish in score_finish_kernel); D_h < 256 takes score_mlp_kernel, described here:
+//
 // Block = 512 threads (8 wavefronts) = all M units x 128 tokens, so `hidden` is
 // read from HBM exactly once and W1 (<= 6.6 MB, L2 resident) once per block.
 // Wavefront (wu, wt): units [wu*M/4, (wu+1)*M/4) x tokens [wt*64, wt*64+64):
@@ -211,9 +216,10 @@ __global__ __launch_bounds__(kThreads) void score_mlp_kernel(
 
 
 // ---------------------------------------------------------------------------
-// Main variant (D_h >= 256).  What bounds the first projection on this chip is
-// not the matrix cores but feeding them: 5 GB of L2 -> CU operand traffic per
-// 128k-token launch.  So W1 never passes through LDS here:
+// Main variant (D_h >= 256).  A 128k-token launch moves 4.3 TB of W1 operands from L2 to
+// the CUs and 1 GB of hidden states from HBM; the structure keeps both off the matrix
+// cores' critical path (timing-only variants without either stream are 0-2 % and 6 %
+// faster), and W1 never passes through LDS:
 //   * a tiny pre-pass copies W1 into the workspace in MFMA A-fragment order
 //     ([k-tile][32-unit block][k-step][lane] x 16 B), so that every A fragment
 //     is ONE fully coalesced 1 KB load straight into registers;
