@@ -23,9 +23,10 @@
 namespace kvzap {
 namespace {
 
-constexpr int kUnroll = 8;             // independent 16-byte loads in flight per lane
-
-template <int kThreads>                // wavefronts of a block share one copy of W in LDS
+// kThreads: wavefronts of a block share one copy of W in LDS; kUnroll: independent 16-byte
+// loads in flight per lane (8 when the chip is full of wavefronts; 32 for short inputs, where
+// a wavefront's walk over D_h is a chain of D_h / (32 kUnroll) memory round trips)
+template <int kThreads, int kUnroll>
 __global__ __launch_bounds__(kThreads) void score_linear_kernel(
     const unsigned short* __restrict__ hidden, const unsigned short* __restrict__ W,
     const unsigned short* __restrict__ bias, float* __restrict__ scores,
@@ -37,9 +38,25 @@ __global__ __launch_bounds__(kThreads) void score_linear_kernel(
   u32x4* sW = reinterpret_cast<u32x4*>(smem);
   const int pieces_per_row = Dh / 8;
   const int lds_stride = pieces_per_row + 4;
-  for (int i = threadIdx.x; i < H * pieces_per_row; i += kThreads) {
-    const int h = i / pieces_per_row, p = i % pieces_per_row;
-    sW[h * lds_stride + p] = reinterpret_cast<const u32x4*>(W + (size_t)h * Dh)[p];
+  // W is contiguous ([H][Dh]): piece i of the whole matrix goes to row i / pieces_per_row.
+  // Eight loads in flight per thread: one at a time, this staging was a chain of memory
+  // round trips that took most of a short call (16 us of 20).
+  const int total_pieces = H * pieces_per_row;
+  for (int base = 0; base < total_pieces; base += kThreads * 8) {
+    u32x4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int i = base + u * kThreads + (int)threadIdx.x;
+      v[u] = reinterpret_cast<const u32x4*>(W)[i < total_pieces ? i : total_pieces - 1];
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int i = base + u * kThreads + (int)threadIdx.x;
+      if (i < total_pieces) {
+        const int h = i / pieces_per_row, p = i - h * pieces_per_row;
+        sW[h * lds_stride + p] = v[u];
+      }
+    }
   }
   __syncthreads();
 
@@ -97,7 +114,7 @@ __global__ __launch_bounds__(kThreads) void score_linear_kernel(
   }
 }
 
-template <int kThreads>
+template <int kThreads, int kUnroll>
 int launch_linear(const void* hidden, const void* W, const void* b, float* scores, long long rows,
                   int T, int Dh, int H, long long want_blocks, hipStream_t stream) {
   constexpr int kWaves = kThreads / 64;
@@ -108,10 +125,10 @@ int launch_linear(const void* hidden, const void* W, const void* b, float* score
   const size_t lds = (size_t)H * ((size_t)Dh * 2 + 64);   // validated <= 160 KB by the caller
   // once per process, which drives one GPU (thread-safe: a function-local static)
   static const hipError_t attr_rc =
-      hipFuncSetAttribute(reinterpret_cast<const void*>(score_linear_kernel<kThreads>),
+      hipFuncSetAttribute(reinterpret_cast<const void*>(score_linear_kernel<kThreads, kUnroll>),
       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
   if (attr_rc != hipSuccess) return KVZAP_ERR_RUNTIME;
-  score_linear_kernel<kThreads><<<dim3((unsigned)blocks), kThreads, lds, stream>>>(
+  score_linear_kernel<kThreads, kUnroll><<<dim3((unsigned)blocks), kThreads, lds, stream>>>(
       static_cast<const unsigned short*>(hidden), static_cast<const unsigned short*>(W),
       static_cast<const unsigned short*>(b), scores, rows, T, Dh, H, (int)gpb);
   return hipGetLastError() == hipSuccess ? KVZAP_OK : KVZAP_ERR_RUNTIME;
@@ -127,8 +144,10 @@ int launch_score_linear(const void* hidden, const void* W, const void* b, float*
   // loads in flight per block are what the HBM stream needs: 128k tokens 194 us against
   // 205 us with small blocks); shorter inputs: 4-wavefront blocks so that more CUs take part
   // (32k tokens: 60 us against 69 us)
-  if (ngroups >= 4096) return launch_linear<1024>(hidden, W, b, scores, rows, T, Dh, H, 1024, stream);
-  return launch_linear<256>(hidden, W, b, scores, rows, T, Dh, H, 1024, stream);
+  if (ngroups >= 4096) return launch_linear<1024, 8>(hidden, W, b, scores, rows, T, Dh, H, 1024, stream);
+  if (ngroups > 1024) return launch_linear<256, 8>(hidden, W, b, scores, rows, T, Dh, H, 1024, stream);
+  // up to 16k tokens: at most one group per wavefront, so only the length of its chain counts
+  return launch_linear<256, 32>(hidden, W, b, scores, rows, T, Dh, H, 1024, stream);
 }
 
 }  // namespace kvzap
