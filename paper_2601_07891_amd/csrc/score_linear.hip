@@ -24,8 +24,7 @@ namespace kvzap {
 namespace {
 
 // kThreads: wavefronts of a block share one copy of W in LDS; kUnroll: independent 16-byte
-// loads in flight per lane (8 when the chip is full of wavefronts; 32 for short inputs, where
-// a wavefront's walk over D_h is a chain of D_h / (32 kUnroll) memory round trips)
+// loads in flight per lane
 template <int kThreads, int kUnroll>
 __global__ __launch_bounds__(kThreads) void score_linear_kernel(
     const unsigned short* __restrict__ hidden, const unsigned short* __restrict__ W,
@@ -85,12 +84,20 @@ __global__ __launch_bounds__(kThreads) void score_linear_kernel(
 #pragma unroll
       for (int u = 0; u < kUnroll; ++u)
         b[u] = hrow[(size_t)(i0 + u) * 4];
+      // the W fragments of the whole batch are read from LDS while the global loads are in
+      // flight: read one by one in front of their MFMAs, each exposed its LDS latency when a
+      // wavefront is alone on its SIMD (13 of the 18 us of a short call)
+      u32x4 a[kUnroll];
 #pragma unroll
       for (int u = 0; u < kUnroll; ++u) {
-        const u32x4 a = head_ok ? sWrow[(size_t)(i0 + u) * 4] : zero4;
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-            __builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b[u]), acc, 0, 0, 0);
+        const u32x4 w = sWrow[(size_t)(i0 + u) * 4];
+        a[u] = head_ok ? w : zero4;
       }
+      __builtin_amdgcn_sched_barrier(0);               // keep the reads ahead of the MFMAs
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+            __builtin_bit_cast(bf16x8, a[u]), __builtin_bit_cast(bf16x8, b[u]), acc, 0, 0, 0);
     }
     for (int i = steps_main; i < steps; ++i) {
       const u32x4 b = hrow[(size_t)i * 4];
@@ -109,6 +116,62 @@ __global__ __launch_bounds__(kThreads) void score_linear_kernel(
           const float bv = bias ? bf16_bits_to_float(bias[h]) : 0.0f;
           scores[((size_t)bidx * H + h) * T + t] = acc[e] + bv;
         }
+      }
+    }
+  }
+}
+
+// Short inputs (up to 512 groups of 16 tokens; 1024 tokens: 10 us against 18 us): with one group per wavefront the walk over
+// D_h above is what a call costs (13 us at D_h = 4096: 128 operand loads through one CU's
+// texture path per wavefront, however many are in flight).  Here the four wavefronts of a
+// block share ONE group and take a quarter of D_h each, W comes straight from global memory
+// (L2) like the tokens, so there is no staging and a single batch of loads; the four partial
+// accumulators are added in a fixed order through LDS.
+__global__ __launch_bounds__(256) void score_linear_short_kernel(
+    const unsigned short* __restrict__ hidden, const unsigned short* __restrict__ W,
+    const unsigned short* __restrict__ bias, float* __restrict__ scores,
+    long long rows, int T, int Dh, int H) {
+  __shared__ floatx4 red[4][64];
+  const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+  const int col = lane & 15, kg = lane >> 4;
+  long long r = (long long)blockIdx.x * 16 + col;
+  const bool valid = r < rows;
+  if (!valid) r = rows - 1;
+  const bool head_ok = col < H;
+  const int per = Dh / 128;                              // MFMA steps per wavefront (D_h % 128 == 0)
+  const u32x4* hrow = reinterpret_cast<const u32x4*>(hidden + (size_t)r * Dh) + kg + (size_t)wid * per * 4;
+  const u32x4* wrow = reinterpret_cast<const u32x4*>(W + (size_t)(col % H) * Dh) + kg + (size_t)wid * per * 4;
+  const u32x4 zero4 = {0u, 0u, 0u, 0u};
+  floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+  constexpr int kBatch = 16;
+  for (int i0 = 0; i0 < per; i0 += kBatch) {
+    u32x4 a[kBatch], b[kBatch];
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int i = i0 + u < per ? i0 + u : per - 1;     // clamped; the surplus is not accumulated
+      b[u] = hrow[(size_t)i * 4];
+      a[u] = wrow[(size_t)i * 4];
+    }
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      if (i0 + u < per)                                  // uniform
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+            __builtin_bit_cast(bf16x8, head_ok ? a[u] : zero4), __builtin_bit_cast(bf16x8, b[u]),
+            acc, 0, 0, 0);
+    }
+  }
+  red[wid][lane] = acc;
+  __syncthreads();
+  if (wid == 0 && valid) {
+    const floatx4 s = ((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane];
+    const long long bidx = r / T;
+    const long long t = r - bidx * T;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int h = 4 * kg + e;
+      if (h < H) {
+        const float bv = bias ? bf16_bits_to_float(bias[h]) : 0.0f;
+        scores[((size_t)bidx * H + h) * T + t] = s[e] + bv;
       }
     }
   }
@@ -145,9 +208,12 @@ int launch_score_linear(const void* hidden, const void* W, const void* b, float*
   // 205 us with small blocks); shorter inputs: 4-wavefront blocks so that more CUs take part
   // (32k tokens: 60 us against 69 us)
   if (ngroups >= 4096) return launch_linear<1024, 8>(hidden, W, b, scores, rows, T, Dh, H, 1024, stream);
-  if (ngroups > 1024) return launch_linear<256, 8>(hidden, W, b, scores, rows, T, Dh, H, 1024, stream);
-  // up to 16k tokens: at most one group per wavefront, so only the length of its chain counts
-  return launch_linear<256, 32>(hidden, W, b, scores, rows, T, Dh, H, 1024, stream);
+  if (ngroups > 512 || Dh % 128 != 0)       // 16k tokens: 26 us with the kernel above, 32 us here
+    return launch_linear<256, 8>(hidden, W, b, scores, rows, T, Dh, H, 1024, stream);
+  score_linear_short_kernel<<<dim3((unsigned)ngroups), 256, 0, stream>>>(
+      static_cast<const unsigned short*>(hidden), static_cast<const unsigned short*>(W),
+      static_cast<const unsigned short*>(b), scores, rows, T, Dh, H);
+  return hipGetLastError() == hipSuccess ? KVZAP_OK : KVZAP_ERR_RUNTIME;
 }
 
 }  // namespace kvzap

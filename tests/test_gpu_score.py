@@ -34,8 +34,11 @@ def _gpu_scores(hid, w):
     return s
 
 
+# up to 8192 tokens (and D_h a multiple of 128) the short-input kernel runs, above it or with
+# other widths the one that stages W in LDS
 LINEAR_SHAPES = [(1, 1024, 4096, 8), (2, 333, 5120, 8), (1, 1, 64, 1), (3, 17, 192, 5),
-                 (1, 4099, 4096, 8), (1, 50, 1024, 16)]
+                 (1, 4099, 4096, 8), (1, 50, 1024, 16), (1, 8192, 4096, 8), (1, 9001, 4096, 8),
+                 (2, 5003, 5120, 8), (1, 8200, 1024, 16)]
 
 
 @pytest.mark.parametrize("B,T,Dh,H", LINEAR_SHAPES)
