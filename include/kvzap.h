@@ -80,7 +80,9 @@ const char* kvzap_version(void);
  * pass T = 1 (one new token per sequence).  Returns 0 for calls that need no
  * workspace and for invalid arguments.  Pure host function.
  * KVZAP_CALL_SCORE with M > 0 needs M*Dh*2 bytes: every call copies W1 there in
- * the order the matrix-core loads want it (a few microseconds).
+ * the order the matrix-core loads want it (a few microseconds); for inputs too short
+ * to fill the chip (B*T up to about 16k tokens) it needs more, for the fp32 partial sums
+ * of a first projection that is split over K -- so query with the B and T of the call.
  */
 size_t kvzap_workspace_bytes(int which_call, int B, int T, int Dh, int M, int H);
 
@@ -106,8 +108,10 @@ size_t kvzap_workspace_bytes(int which_call, int B, int T, int Dh, int M, int H)
  *
  * Arithmetic: bf16 products accumulated in fp32 on the matrix cores; GELU in
  * fp32; the GELU output enters the second projection as a bf16 pair (high part
- * plus residual), i.e. to about 16 mantissa bits.  The sum order is fixed, so
- * results are run-to-run deterministic.  B*T == 0 is a no-op.
+ * plus residual), i.e. to about 16 mantissa bits; short inputs (see the workspace query)
+ * take a split first projection whose second projection is plain fp32.  The sum order is
+ * fixed for a given shape, so results are run-to-run deterministic; the same token scored
+ * in calls of different B*T may differ in the last bits.  B*T == 0 is a no-op.
  */
 int kvzap_score(const void* hidden, const void* W1, const void* b1,
                 const void* W2, const void* b2, float* scores,
