@@ -36,6 +36,18 @@ MEASURED_HBM_TRAFFIC = {
 }
 
 
+def _host_numerics() -> dict:
+    """What the oracle's timing depends on: the cores this process may use and the BLAS behind
+    numpy's float64 GEMM (the mask and the gather are single-threaded numpy)."""
+    info = {"affinity_cores": len(os.sched_getaffinity(0)), "numpy": np.__version__}
+    try:
+        blas = np.__config__.show(mode="dicts").get("Build Dependencies", {}).get("blas", {})
+        info["blas"] = f"{blas.get('name')} {blas.get('version')}"
+    except Exception:
+        info["blas"] = "unknown"
+    return info
+
+
 def _oracle_sample(wl, layer0, sample_tokens):
     """Run the float64 oracle on the first `sample_tokens` tokens of every sequence
     of layer 0 (all of them, window included, when sample_tokens == T).
@@ -73,7 +85,8 @@ def _oracle_sample(wl, layer0, sample_tokens):
             "sample": f"layer 0 of {wl.name}: {what} {sample_tokens} tokens of each of {B} "
                       f"sequence(s); float64 numpy score + mask + compact, one pass",
             "score_s": t1 - t0, "mask_compact_s": t3 - t2,
-            "kept_fraction": float(res.lengths.sum()) / (B * wl.H * sample_tokens)}
+            "kept_fraction": float(res.lengths.sum()) / (B * wl.H * sample_tokens),
+            "host": _host_numerics()}
     return tau, info, S
 
 
