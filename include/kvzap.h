@@ -28,8 +28,10 @@
  *     launched and no output is written.  No call throws or aborts.
  *   - Supported shapes: H (KV heads) in [1, 16]; D (head dim) a multiple of 8
  *     with D <= 512 (rows are moved in 16-byte pieces); D_h a multiple of 64;
- *     the MLP width M a multiple of 128 with M <= 640.  Anything else returns
- *     KVZAP_ERR_UNSUPPORTED; there is no fallback path.
+ *     the MLP width M a multiple of 128 with M <= 640; at most 65535 (sequence, head)
+ *     rows per call (B*H) and T <= 2^31 - 2^20 - 1 positions in the calls that index
+ *     positions (mask, top-k, compaction).  Anything else returns KVZAP_ERR_UNSUPPORTED;
+ *     there is no fallback path.
  *   - Weight storage is output-major, the way a PyTorch linear module stores
  *     it: the paper's W1 in R^{D_h x M} (App. B) is passed as its transpose
  *     [M, D_h], W2 in R^{M x H} as [H, M], the linear surrogate's D_h x H matrix

@@ -15,6 +15,9 @@ constexpr int kMaxH = 16;
 constexpr int kMaxD = 512;
 constexpr int kMaxM = 640;
 constexpr size_t kLdsBytes = 160 * 1024;
+// positions are 32-bit in the kernels and a block may step up to a few tiles past the end
+// before it clamps: keep that arithmetic away from INT_MAX
+constexpr int kMaxT = INT_MAX - (1 << 20);
 
 // shape rules shared by kvzap_score and kvzap_decode_evict
 int check_attend_shape(int B, int H, int HQ, int max_rows, int window) {
@@ -127,7 +130,7 @@ int check_mask(const float* scores, float tau, int window, const int32_t* seq_le
                const void* workspace, size_t workspace_bytes) {
   if (B <= 0 || H <= 0 || T <= 0 || window < 0) return KVZAP_ERR_SHAPE;
   if (tau != tau) return KVZAP_ERR_SHAPE;                 // NaN threshold
-  if ((long long)B * H > 65535) return KVZAP_ERR_UNSUPPORTED;
+  if ((long long)B * H > 65535 || T > kMaxT) return KVZAP_ERR_UNSUPPORTED;
   if (!scores || !keep_idx || !lengths || !offsets) return KVZAP_ERR_NULL;
   if (!aligned16(scores) || !aligned16(keep_idx) || !aligned16(lengths) ||
       !aligned16(offsets) || !aligned16(seq_lens))
@@ -141,7 +144,7 @@ int check_compact(const void* K, const void* V, const int32_t* keep_idx, const i
                   const int64_t* offsets, const void* K_out, const void* V_out, int64_t cap_rows,
                   int B, int H, int T, int D) {
   if (B <= 0 || H <= 0 || T <= 0 || D <= 0 || cap_rows < 0) return KVZAP_ERR_SHAPE;
-  if (D % 8 != 0 || D > kMaxD || (long long)B * H > 65535) return KVZAP_ERR_UNSUPPORTED;
+  if (D % 8 != 0 || D > kMaxD || (long long)B * H > 65535 || T > kMaxT) return KVZAP_ERR_UNSUPPORTED;
   if (!K || !V || !keep_idx || !lengths || !offsets || !K_out || !V_out) return KVZAP_ERR_NULL;
   if (!aligned16(K) || !aligned16(V) || !aligned16(keep_idx) || !aligned16(lengths) ||
       !aligned16(offsets) || !aligned16(K_out) || !aligned16(V_out))
@@ -220,7 +223,7 @@ int kvzap_mask_per_head(const float* scores, const float* tau, int window,
                         int32_t* lengths, int64_t* offsets, void* workspace,
                         size_t workspace_bytes, void* stream) {
   if (B <= 0 || H <= 0 || T <= 0 || window < 0) return KVZAP_ERR_SHAPE;
-  if ((long long)B * H > 65535) return KVZAP_ERR_UNSUPPORTED;
+  if ((long long)B * H > 65535 || T > kMaxT) return KVZAP_ERR_UNSUPPORTED;
   if (!scores || !tau || !keep_idx || !lengths || !offsets) return KVZAP_ERR_NULL;
   if (!aligned16(scores) || !aligned16(tau) || !aligned16(keep_idx) || !aligned16(lengths) ||
       !aligned16(offsets) || !aligned16(seq_lens))
@@ -235,7 +238,7 @@ int kvzap_topk_threshold(const float* scores, int window, const int32_t* seq_len
                          int per_layer, int B, int H, int T, float* tau_out, void* workspace,
                          size_t workspace_bytes, void* stream) {
   if (B <= 0 || H <= 0 || T <= 0 || window < 0) return KVZAP_ERR_SHAPE;
-  if ((long long)B * H > 65535) return KVZAP_ERR_UNSUPPORTED;
+  if ((long long)B * H > 65535 || T > kMaxT) return KVZAP_ERR_UNSUPPORTED;
   if ((long long)H * T > 0xFFFFFFFFll) return KVZAP_ERR_UNSUPPORTED;     // 32-bit histogram bins
   if (!scores || !tau_out) return KVZAP_ERR_NULL;
   if (!aligned16(scores) || !aligned16(tau_out) || !aligned16(seq_lens)) return KVZAP_ERR_ALIGN;
@@ -433,7 +436,7 @@ int kvzap_compact_paged(const void* K, const void* V, const int32_t* keep_idx,
                         void* V_pool, int num_pages, int B, int H, int T, int D, void* stream) {
   if (B <= 0 || H <= 0 || T <= 0 || D <= 0 || max_pages <= 0 || num_pages < 0) return KVZAP_ERR_SHAPE;
   if (!valid_page_rows(page_rows)) return KVZAP_ERR_SHAPE;
-  if ((D != 64 && D != 128 && D != 256) || (long long)B * H > 65535) return KVZAP_ERR_UNSUPPORTED;
+  if ((D != 64 && D != 128 && D != 256) || (long long)B * H > 65535 || T > kMaxT) return KVZAP_ERR_UNSUPPORTED;
   if (!K || !V || !keep_idx || !lengths || !offsets || !block_table) return KVZAP_ERR_NULL;
   if (num_pages > 0 && (!K_pool || !V_pool)) return KVZAP_ERR_NULL;
   const void* ptrs[] = {K, V, keep_idx, lengths, offsets, block_table, K_pool, V_pool};

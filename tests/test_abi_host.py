@@ -125,6 +125,7 @@ def test_mask_argument_errors(lib):
     assert call(T=0) == ERR["shape"]
     assert call(tau=float("nan")) == ERR["shape"]
     assert call(B=10000, H=8) == ERR["unsupported"]
+    assert call(T=2 ** 31 - 1) == ERR["unsupported"]          # positions are 32-bit with headroom
     assert call(scores=P + 4) == ERR["align"]
     assert call(ws=None) == ERR["workspace"]
     assert call(wsb=ws - 1) == ERR["workspace"]
