@@ -147,6 +147,15 @@ def test_decode_linear_random_and_other_dims():
     _run_case("linear", False, B=2, H=3, D=64, Dh=512, M=0, w=16, T0=40, steps=40, tau=0.0, seed=3)
 
 
+@pytest.mark.parametrize("scorer,B,H,D,Dh,M", [("mlp", 3, 16, 512, 5120, 640),     # widest of everything
+                                               ("mlp", 2, 1, 8, 1024, 384),        # one head, 16-byte rows
+                                               ("mlp", 70, 8, 128, 2048, 256),     # more than one 64-token block
+                                               ("linear", 2, 16, 512, 4096, 0),
+                                               ("linear", 3, 5, 96, 192, 0)])      # D_h not a multiple of 128
+def test_decode_shape_corners(scorer, B, H, D, Dh, M):
+    _run_case(scorer, False, B=B, H=H, D=D, Dh=Dh, M=M, w=8, T0=20, steps=30, tau=0.0, seed=B + H)
+
+
 def test_decode_full_slab_sets_error_flag():
     B, H, D, Dh, w = 1, 2, 128, 256, 2
     hid, wts = synth.make_exact_case(8, Dh, H, 0, seed=1)
