@@ -1,0 +1,57 @@
+"""The contract of bench.py's output: ONE JSON line with the agreed keys, for the default
+workload (few layers and steps so that the test stays short) and for the decode stages."""
+import json
+import os
+import subprocess
+import sys
+
+import pytest
+
+pytestmark = pytest.mark.gpu
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _bench(*args):
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), *args], cwd=ROOT,
+                       capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [ln for ln in r.stdout.splitlines() if ln.startswith("{")]
+    assert len(lines) == 1, r.stdout[-2000:]
+    return json.loads(lines[0])
+
+
+def _common(d, steps, warmup):
+    assert d["n_gpus"] == 1 and d["steps"] == steps and d["warmup"] == warmup
+    assert d["value"] > 0 and d["ms_per_step"] > 0
+    assert d["higher_is_better"] is True and d["scaling"] == "weak"
+    assert d["vs_baseline"] is None and d["dtype"] == "bf16" and d["data"] == "synthetic"
+    assert isinstance(d["config"]["workload"], str) and "model" not in d["config"]
+
+
+def test_default_workload_line():
+    d = _bench("--layers", "2", "--steps", "2", "--warmup", "1")
+    _common(d, 2, 1)
+    assert d["unit"] == "tokens/s" and d["config"]["workload"] == "c3_qwen8b_128k_mlp"
+    r = d["roofline"]
+    assert r["bound"] == "mfma" and r["unit"] == "TFLOP/s" and r["peak"] == 2500.0
+    assert abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-12 and 0.2 < r["frac"] < 1.0
+    assert "traffic" in r
+    rc = d["roofline_compact"]
+    assert rc["bound"] == "hbm" and rc["unit"] == "GB/s" and rc["peak"] == 8000.0 and 0.3 < rc["frac"] < 1.0
+    c = d["cpu_baseline"]
+    assert c["kind"] == "oracle" and c["value"] > 0 and c["cores"] >= 1 and c["unit"] == "tokens/s"
+    assert isinstance(c["sample"], str) and c["sample"]
+    assert d["score_max_rel_err_vs_oracle_sample"] < 1e-2
+    st = d["stages_ms_per_layer"]
+    assert st["score"] > st["compact"] > st["mask"] > 0
+
+
+def test_decode_lines():
+    d = _bench("--config", "c5_qwen8b_decode", "--layers", "2", "--steps", "4", "--warmup", "2", "--graph")
+    _common(d, 4, 2)
+    assert d["us_per_layer_step"] > 0 and d["hip_graph"]["us_per_layer_step"] > 0
+    d = _bench("--config", "c5_qwen8b_decode", "--stage", "attend", "--layers", "1", "--steps", "2",
+               "--warmup", "1")
+    _common(d, 2, 1)
+    assert d["roofline"]["bound"] == "hbm" and 0.3 < d["roofline"]["frac"] < 1.0
+    assert d["cpu_baseline"]["kind"] == "oracle"
