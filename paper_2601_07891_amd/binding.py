@@ -118,11 +118,20 @@ def _check(t: Optional[torch.Tensor], dtype, name: str, optional: bool = False):
         raise ValueError(f"{name} must be contiguous")
 
 
-def _workspace(nbytes: int, device, workspace: Optional[torch.Tensor]):
+def _workspace(nbytes: int, device, workspace: Optional[torch.Tensor], stream=None):
     if nbytes == 0:
         return workspace, (0 if workspace is None else workspace.numel() * workspace.element_size())
     if workspace is None:
         workspace = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        # A temporary allocated here goes back to torch's caching allocator when the wrapper
+        # returns, while the kernels enqueued on `stream` may still be using it: tell the
+        # allocator, so that the block is not handed out again before that stream gets there
+        # (a no-op cost when `stream` is the current stream)
+        if stream is not None:
+            if not isinstance(stream, torch.cuda.Stream):
+                stream = torch.cuda.ExternalStream(int(stream), device=device) if int(stream) \
+                    else torch.cuda.default_stream(device)
+            workspace.record_stream(stream)
     return workspace, workspace.numel() * workspace.element_size()
 
 
@@ -156,7 +165,7 @@ def kvzap_score(hidden: torch.Tensor, W1: torch.Tensor, b1: Optional[torch.Tenso
     if scores.shape != (B, H, T):
         raise ValueError("scores must be [B,H,T]")
     ws, ws_bytes = _workspace(kvzap_workspace_bytes(CALL_SCORE, B, T, Dh, M, H), hidden.device,
-                              workspace)
+                              workspace, stream)
     rc = lib().kvzap_score(_ptr(hidden), _ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2), _ptr(scores),
                            B, T, Dh, M, H, _ptr(ws), ws_bytes, _stream(stream))
     if rc != 0:
@@ -187,7 +196,7 @@ def kvzap_mask(scores: torch.Tensor, tau: float, window: int,
     _check(offsets, torch.int64, "offsets")
     if keep_idx.numel() < B * H * T or lengths.numel() != B * H or offsets.numel() != B * H + 1:
         raise ValueError("output buffers have the wrong size")
-    ws, ws_bytes = _workspace(kvzap_workspace_bytes(CALL_MASK, B, T, 0, 0, H), dev, workspace)
+    ws, ws_bytes = _workspace(kvzap_workspace_bytes(CALL_MASK, B, T, 0, 0, H), dev, workspace, stream)
     rc = lib().kvzap_mask(_ptr(scores), float(tau), int(window), _ptr(seq_lens), B, H, T,
                           _ptr(keep_idx), _ptr(lengths), _ptr(offsets), _ptr(ws), ws_bytes,
                           _stream(stream))
@@ -267,7 +276,7 @@ def kvzap_decode_evict(hidden_new: torch.Tensor, W1: torch.Tensor, b1, W2, b2,
     if (B, st.H, st.D) != tuple(k_new.shape) or k_new.shape != v_new.shape or B != st.B:
         raise ValueError("k_new / v_new must be [B,H,D] matching the state")
     ws, ws_bytes = _workspace(
-        kvzap_workspace_bytes(CALL_DECODE_EVICT, B, 1, Dh, M, st.H), hidden_new.device, workspace)
+        kvzap_workspace_bytes(CALL_DECODE_EVICT, B, 1, Dh, M, st.H), hidden_new.device, workspace, stream)
     ring = st.window > 0
     rc = lib().kvzap_decode_evict(
         _ptr(hidden_new), _ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2), Dh, M,
@@ -316,7 +325,7 @@ def kvzap_attend_decode(q: torch.Tensor, K_rows: torch.Tensor, V_rows: torch.Ten
             raise ValueError("out must be [B,HQ,D]")
     ws, ws_bytes = _workspace(
         kvzap_workspace_bytes(CALL_ATTEND_DECODE, B, int(max_rows), HQ, int(window), H),
-        q.device, workspace)
+        q.device, workspace, stream)
     ring = window > 0
     total_rows = K_rows.shape[0]
     rc = lib().kvzap_attend_decode(
@@ -350,7 +359,7 @@ def kvzap_assign_pages(lengths: torch.Tensor, page_rows: int, free_pages: torch.
     else:
         _check(result, torch.int32, "result")
     ws, ws_bytes = _workspace(kvzap_workspace_bytes(CALL_ASSIGN_PAGES, B, 1, 0, 0, H),
-                              lengths.device, workspace)
+                              lengths.device, workspace, stream)
     n_free = free_pages.numel()
     rc = lib().kvzap_assign_pages(_ptr(lengths), B, H, int(page_rows), int(reserve_rows),
                                   _ptr(free_pages) if n_free else None, n_free,
@@ -417,7 +426,7 @@ def kvzap_attend_decode_paged(q: torch.Tensor, K_pool: torch.Tensor, V_pool: tor
         _check(out, bf, "out")
     ws, ws_bytes = _workspace(
         kvzap_workspace_bytes(CALL_ATTEND_DECODE, B, int(max_rows), HQ, int(window), H),
-        q.device, workspace)
+        q.device, workspace, stream)
     ring = window > 0
     num_pages = K_pool.shape[0]
     rc = lib().kvzap_attend_decode_paged(
@@ -445,7 +454,7 @@ def kvzap_extend_pages(lengths: torch.Tensor, page_counts: torch.Tensor, page_ro
     if result is None:
         result = torch.empty(4, dtype=torch.int32, device=lengths.device)
     ws, ws_bytes = _workspace(kvzap_workspace_bytes(CALL_ASSIGN_PAGES, B, 1, 0, 0, H),
-                              lengths.device, workspace)
+                              lengths.device, workspace, stream)
     n_free = free_pages.numel()
     rc = lib().kvzap_extend_pages(_ptr(lengths), _ptr(page_counts), B, H, int(page_rows),
                                   int(reserve_rows), _ptr(free_pages) if n_free else None, n_free,
@@ -495,7 +504,7 @@ def kvzap_decode_evict_paged(hidden_new: torch.Tensor, W1: torch.Tensor, b1, W2,
     if (B, st.H, st.D) != tuple(k_new.shape) or k_new.shape != v_new.shape or B != st.B:
         raise ValueError("k_new / v_new must be [B,H,D] matching the state")
     ws, ws_bytes = _workspace(
-        kvzap_workspace_bytes(CALL_DECODE_EVICT, B, 1, Dh, M, st.H), hidden_new.device, workspace)
+        kvzap_workspace_bytes(CALL_DECODE_EVICT, B, 1, Dh, M, st.H), hidden_new.device, workspace, stream)
     ring = st.window > 0
     rc = lib().kvzap_decode_evict_paged(
         _ptr(hidden_new), _ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2), Dh, M,
@@ -523,7 +532,7 @@ def kvzap_topk_threshold(scores: torch.Tensor, window: int, k: int, per_layer: b
         _check(tau_out, torch.float32, "tau_out")
     ws, ws_bytes = _workspace(
         kvzap_workspace_bytes(CALL_TOPK_THRESHOLD, B, T, 0, 1 if per_layer else 0, H),
-        scores.device, workspace)
+        scores.device, workspace, stream)
     rc = lib().kvzap_topk_threshold(_ptr(scores), int(window), _ptr(seq_lens), int(k),
                                     1 if per_layer else 0, B, H, T, _ptr(tau_out), _ptr(ws),
                                     ws_bytes, _stream(stream))
@@ -551,7 +560,7 @@ def kvzap_mask_per_head(scores: torch.Tensor, tau: torch.Tensor, window: int,
         lengths = torch.empty((B, H), dtype=torch.int32, device=dev)
     if offsets is None:
         offsets = torch.empty(B * H + 1, dtype=torch.int64, device=dev)
-    ws, ws_bytes = _workspace(kvzap_workspace_bytes(CALL_MASK, B, T, 0, 0, H), dev, workspace)
+    ws, ws_bytes = _workspace(kvzap_workspace_bytes(CALL_MASK, B, T, 0, 0, H), dev, workspace, stream)
     rc = lib().kvzap_mask_per_head(_ptr(scores), _ptr(tau), int(window), _ptr(seq_lens), B, H, T,
                                    _ptr(keep_idx), _ptr(lengths), _ptr(offsets), _ptr(ws),
                                    ws_bytes, _stream(stream))
@@ -583,7 +592,7 @@ def kvzap_teacher_scores(q: torch.Tensor, k: torch.Tensor, T: int, scale: float,
     else:
         _check(log_s, torch.float32, "log_s")
     ws, ws_bytes = _workspace(kvzap_workspace_bytes(CALL_TEACHER_SCORES, 1, int(T), HQ, Tq, H),
-                              q.device, workspace)
+                              q.device, workspace, stream)
     rc = lib().kvzap_teacher_scores(_ptr(q), _ptr(k), _ptr(vnorm), _ptr(hnorm), float(scale),
                                     _ptr(log_s), H, HQ, Tq, Tk, int(T), D, _ptr(ws), ws_bytes,
                                     _stream(stream))
@@ -616,7 +625,7 @@ def kvzap_compress(hidden: torch.Tensor, W1: torch.Tensor, b1, W2, b2, K: torch.
     K_out = torch.empty((B * H * T, D), dtype=bf, device=dev)
     V_out = torch.empty((B * H * T, D), dtype=bf, device=dev)
     ws, ws_bytes = _workspace(max(kvzap_workspace_bytes(CALL_COMPRESS, B, T, Dh, M, H), 256), dev,
-                              workspace)
+                              workspace, stream)
     rc = lib().kvzap_compress(_ptr(hidden), _ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2), _ptr(K), _ptr(V),
                               float(tau), int(window), _ptr(seq_lens), _ptr(scores), _ptr(keep_idx),
                               _ptr(lengths), _ptr(offsets), _ptr(K_out), _ptr(V_out), B * H * T,

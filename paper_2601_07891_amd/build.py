@@ -41,15 +41,26 @@ def build(verbose: bool = True) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
-    # stand-alone calibration program (practical MFMA / HBM ceilings of the GPU it runs on)
+    if verbose:
+        print(f"built {LIB_PATH}")
+    return LIB_PATH
+
+
+def build_ceilings(verbose: bool = True) -> str:
+    """On request only (`python -m paper_2601_07891_amd.build --ceilings`): the stand-alone
+    calibration program that measures the practical MFMA / HBM ceilings of the GPU it runs on.
+    It is not part of the library and the default build leaves it out."""
     cmd = [HIPCC, *FLAGS, os.path.join(CSRC, "ceilings.hip"), "-o", CEILINGS_PATH]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed for ceilings.hip:\n{r.stdout}\n{r.stderr}")
     if verbose:
-        print(f"built {LIB_PATH} and {CEILINGS_PATH}")
-    return LIB_PATH
+        print(f"built {CEILINGS_PATH}")
+    return CEILINGS_PATH
 
 
 if __name__ == "__main__":
-    build()
+    if "--ceilings" in sys.argv[1:]:
+        build_ceilings()
+    else:
+        build()

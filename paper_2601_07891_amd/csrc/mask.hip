@@ -21,7 +21,13 @@ constexpr int kThreads = 256;            // 4 wavefronts
 constexpr int kPerThread = kMaskChunk / kThreads;  // 4 consecutive tokens
 static_assert(kPerThread == 4, "one float4 per thread");
 
-struct Flags4 { unsigned bits; };
+// A sequence's own length, clamped into [0, T]: positions at or beyond T do not exist whatever
+// the caller's array says (it lives on the device, so the host cannot reject it)
+__device__ __forceinline__ int seq_len_of(const int32_t* __restrict__ seq_lens, int b, int T) {
+  if (!seq_lens) return T;
+  const int n = seq_lens[b];
+  return n < 0 ? 0 : (n > T ? T : n);
+}
 
 // keep flags of tokens t0..t0+3 of one (b,h) row
 __device__ __forceinline__ unsigned keep_bits4(const float* __restrict__ row, int t0, int T,
@@ -51,7 +57,7 @@ __global__ __launch_bounds__(kThreads) void mask_count_kernel(
     int32_t* __restrict__ chunk_counts) {
   const int chunk = blockIdx.x, bh = blockIdx.y;
   const float tau = tau_head ? tau_head[bh] : tau_all;     // one threshold, or one per head
-  const int Tb = seq_lens ? seq_lens[bh / H] : T;
+  const int Tb = seq_len_of(seq_lens, bh / H, T);
   const float* row = scores + (size_t)bh * T;
   const bool vec_ok = (T % 4) == 0;
   const int t0 = chunk * kMaskChunk + threadIdx.x * kPerThread;
@@ -158,7 +164,7 @@ __global__ __launch_bounds__(kThreads) void mask_emit_kernel(
     my_prefix = chunk_prefix[(size_t)bh * nchunks + chunk];
   }
   const float tau = tau_head ? tau_head[bh] : tau_all;
-  const int Tb = seq_lens ? seq_lens[bh / H] : T;
+  const int Tb = seq_len_of(seq_lens, bh / H, T);
   const float* row = scores + (size_t)bh * T;
   const bool vec_ok = (T % 4) == 0;
   const int t0 = chunk * kMaskChunk + threadIdx.x * kPerThread;

@@ -95,6 +95,27 @@ def test_seq_lens_right_padded():
     assert (parity.to_np(n)[3] == 0).all()
 
 
+@pytest.mark.parametrize("window,tau", [(128, 0.1), (0, -1.0), (5000, 0.0)])
+def test_seq_lens_beyond_T_mean_T(window, tau):
+    # a length above T (or below 0) names positions that do not exist: the result is the one for
+    # a length of T (resp. 0), and nothing is written behind the B*H*T capacity of keep_idx
+    B, H, T, D = 3, 8, 2100, 128            # T is not a multiple of the 1024-token chunk
+    scores = synth.make_scores(B, H, T, seed=31)
+    K, V = _kv(B, H, T, D, 32)
+    given = [T + 1000, 2 ** 31 - 1, -5]
+    meant = [T, T, 0]
+    s = scores.to(DEV)
+    sl = torch.tensor(given, dtype=torch.int32, device=DEV)
+    guard = 4096
+    idx_buf = torch.full((B * H * T + guard,), -7, dtype=torch.int32, device=DEV)
+    idx, n, off = binding.kvzap_mask(s, tau, window, sl, idx_buf[:B * H * T])
+    Ko, Vo = binding.kvzap_compact(K.to(DEV), V.to(DEV), idx, n, off)
+    torch.cuda.synchronize()
+    assert (idx_buf[B * H * T:] == -7).all()
+    parity.assert_prune_matches(idx, n, off, Ko, Vo, K, V, scores.double().numpy(), tau, window,
+                                seq_lens=meant)
+
+
 def test_cap_rows_is_respected():
     B, H, T, D, w = 1, 8, 2048, 128, 128
     scores = synth.make_scores(B, H, T, seed=4)

@@ -70,6 +70,39 @@ def test_non_default_stream_and_back_to_back_calls():
     assert torch.equal(V0[:tot].view(torch.int16), V1[:tot].view(torch.int16))
 
 
+def test_explicit_stream_that_is_not_current():
+    # stream= names a side stream while torch's current stream stays the default one: the
+    # wrappers' temporary workspaces are allocated on the current stream and must not be
+    # recycled (and overwritten by the allocations below) before the side stream has run
+    wl = synth.with_size(synth.CONFIGS["c2_llama8b_32k_mlp"], T=6000)
+    w = synth.make_weights(wl, 0, DEV); hid = synth.make_hidden(wl, 0, DEV)
+    K, V = synth.make_kv(wl, 0, DEV)
+    s0 = binding.kvzap_score(hid, w["W1"], w["b1"], w["W2"], w["b2"])
+    i0, n0, o0 = binding.kvzap_mask(s0, 0.1, wl.window)
+    K0, V0 = binding.kvzap_compact(K, V, i0, n0, o0)
+    torch.cuda.synchronize()
+    tot = int(o0[-1])
+    side = torch.cuda.Stream()
+    big = torch.empty(1 << 28, dtype=torch.uint8, device=DEV)
+    for rep in range(3):
+        with torch.cuda.stream(side):
+            for _ in range(4):
+                big.fill_(rep)                   # the side stream is busy when our kernels arrive
+        s1 = binding.kvzap_score(hid, w["W1"], w["b1"], w["W2"], w["b2"], stream=side)
+        # what a recycled workspace block would be overwritten by, on the current stream
+        junk = [torch.full((n,), 255, dtype=torch.uint8, device=DEV) for n in (1 << 22, 1 << 23, 1 << 16)]
+        i1, n1, o1 = binding.kvzap_mask(s1, 0.1, wl.window, stream=side)
+        junk += [torch.full((n,), 255, dtype=torch.uint8, device=DEV) for n in (1 << 12, 1 << 16, 1 << 20)]
+        K1, V1 = binding.kvzap_compact(K, V, i1, n1, o1, stream=side)
+        side.synchronize()
+        torch.cuda.synchronize()
+        del junk
+        assert torch.equal(s0, s1) and torch.equal(n0, n1) and torch.equal(o0, o1)
+        assert torch.equal(i0[:tot], i1[:tot])
+        assert torch.equal(K0[:tot].view(torch.int16), K1[:tot].view(torch.int16))
+        assert torch.equal(V0[:tot].view(torch.int16), V1[:tot].view(torch.int16))
+
+
 def test_bitwise_repeatability_and_poisoned_workspaces():
     wl = synth.with_size(synth.CONFIGS["c3_qwen8b_128k_mlp"], L=1, T=9000)
     w = synth.make_weights(wl, 0, DEV); hid = synth.make_hidden(wl, 0, DEV)
