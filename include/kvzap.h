@@ -55,7 +55,8 @@ typedef enum kvzap_status {
   KVZAP_ERR_UNSUPPORTED = -4, /* legal but outside the supported shapes        */
   KVZAP_ERR_CAPACITY = -5,    /* an output buffer is too small for the worst case */
   KVZAP_ERR_WORKSPACE = -6,   /* workspace missing, misaligned or too small    */
-  KVZAP_ERR_RUNTIME = -7      /* a HIP launch failed (see hipGetLastError)     */
+  KVZAP_ERR_RUNTIME = -7,     /* a HIP launch failed (see hipGetLastError)     */
+  KVZAP_ERR_STATIC_LIMIT = -8 /* input larger than kvzap_mask_static's built-in scratch */
 } kvzap_status;
 
 /* Which call a workspace query is for. */
@@ -144,6 +145,29 @@ int kvzap_mask(const float* scores, float tau, int window,
                const int32_t* seq_lens, int B, int H, int T,
                int32_t* keep_idx, int32_t* lengths, int64_t* offsets,
                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * kvzap_mask_static -- kvzap_mask for callers that cannot allocate device memory or hand over
+ * a workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments (minus the workspace), same kernels, same result bit for bit.
+ * The scratch kvzap_mask keeps in its workspace lives in a buffer built into the library
+ * instead (KVZAP_MASK_STATIC_MAX_CHUNKS * 12 bytes = 768 KiB per GPU, held until the process
+ * ends), so the call allocates nothing and frees nothing.
+ *
+ * Limit: B * H * ceil(T / 1024) <= KVZAP_MASK_STATIC_MAX_CHUNKS (64 Mi score entries, e.g.
+ * 8 heads of 8 Mi positions); beyond it KVZAP_ERR_STATIC_LIMIT, nothing launched.
+ * All calls on one GPU share that GPU's buffer: calls whose kernels may overlap on one GPU
+ * (different streams, no dependency between them) race; calls on one stream, or ordered by
+ * events, are fine.  Nothing in the buffer needs clearing between calls.  The first call on a
+ * device looks up the buffer's address on that device (hipGetSymbolAddress, with that device
+ * current); make that call once outside any stream capture.  KVZAP_ERR_RUNTIME if the lookup
+ * fails or the device ordinal is 64 or more.
+ */
+#define KVZAP_MASK_STATIC_MAX_CHUNKS 65536
+int kvzap_mask_static(const float* scores, float tau, int window,
+                      const int32_t* seq_lens, int B, int H, int T,
+                      int32_t* keep_idx, int32_t* lengths, int64_t* offsets,
+                      void* stream);
 
 /*
  * kvzap_prepare_scorer / kvzap_score_prepared -- kvzap_score for MLP surrogates (Sec. 3.3,

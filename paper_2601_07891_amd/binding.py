@@ -31,6 +31,8 @@ SIGNATURES = {
     "kvzap_score": (_c_int, [_c_void_p] * 6 + [_c_int] * 5 + [_c_void_p, _c_size_t, _c_void_p]),
     "kvzap_mask": (_c_int, [_c_void_p, _c_float, _c_int, _c_void_p, _c_int, _c_int, _c_int,
                             _c_void_p, _c_void_p, _c_void_p, _c_void_p, _c_size_t, _c_void_p]),
+    "kvzap_mask_static": (_c_int, [_c_void_p, _c_float, _c_int, _c_void_p, _c_int, _c_int, _c_int,
+                                   _c_void_p, _c_void_p, _c_void_p, _c_void_p]),
     "kvzap_prepare_scorer": (_c_int, [_c_void_p, _c_int, _c_int, _c_void_p, _c_size_t, _c_void_p]),
     "kvzap_score_prepared": (_c_int, [_c_void_p] * 6 + [_c_int] * 5 + [_c_void_p]),
     "kvzap_compress": (_c_int, [_c_void_p] * 7 + [_c_float, _c_int] + [_c_void_p] * 7 + [_c_int64] +
@@ -203,6 +205,24 @@ def kvzap_mask(scores: torch.Tensor, tau: float, window: int,
     if rc != 0:
         raise KvzapError(rc, "kvzap_mask")
     return keep_idx, lengths, offsets
+
+
+def kvzap_mask_static(scores: torch.Tensor, tau: float, window: int,
+                      seq_lens: Optional[torch.Tensor], keep_idx: torch.Tensor,
+                      lengths: torch.Tensor, offsets: torch.Tensor, stream=None) -> None:
+    """kvzap_mask on the library's built-in scratch: the caller passes every output buffer and
+    this wrapper allocates nothing either."""
+    _check(scores, torch.float32, "scores")
+    _check(seq_lens, torch.int32, "seq_lens", True)
+    _check(keep_idx, torch.int32, "keep_idx"); _check(lengths, torch.int32, "lengths")
+    _check(offsets, torch.int64, "offsets")
+    B, H, T = scores.shape
+    if keep_idx.numel() < B * H * T or lengths.numel() != B * H or offsets.numel() != B * H + 1:
+        raise ValueError("output buffers have the wrong size")
+    rc = lib().kvzap_mask_static(_ptr(scores), float(tau), int(window), _ptr(seq_lens), B, H, T,
+                                 _ptr(keep_idx), _ptr(lengths), _ptr(offsets), _stream(stream))
+    if rc != 0:
+        raise KvzapError(rc, "kvzap_mask_static")
 
 
 def kvzap_compact(K: torch.Tensor, V: torch.Tensor, keep_idx: torch.Tensor,

@@ -57,6 +57,8 @@ const char* kvzap_status_string(int status) {
     case KVZAP_ERR_CAPACITY: return "output capacity too small";
     case KVZAP_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case KVZAP_ERR_RUNTIME: return "HIP launch failed";
+    case KVZAP_ERR_STATIC_LIMIT:
+      return "input larger than the built-in scratch of the allocation-free entry point";
     default: return "unknown status";
   }
 }
@@ -216,6 +218,17 @@ int kvzap_mask(const float* scores, float tau, int window, const int32_t* seq_le
   if (rc != KVZAP_OK) return rc;
   return kvzap::launch_mask(scores, tau, nullptr, window, seq_lens, B, H, T, keep_idx, lengths,
                             offsets, workspace, static_cast<hipStream_t>(stream));
+}
+
+int kvzap_mask_static(const float* scores, float tau, int window, const int32_t* seq_lens, int B,
+                      int H, int T, int32_t* keep_idx, int32_t* lengths, int64_t* offsets,
+                      void* stream) {
+  // kvzap_mask's checks, the workspace ones aside (the scratch is the library's own)
+  const int rc = check_mask(scores, tau, window, seq_lens, B, H, T, keep_idx, lengths, offsets,
+                            reinterpret_cast<const void*>(uintptr_t{256}), ~(size_t)0);
+  if (rc != KVZAP_OK) return rc;
+  return kvzap::launch_mask_static(scores, tau, window, seq_lens, B, H, T, keep_idx, lengths,
+                                   offsets, static_cast<hipStream_t>(stream));
 }
 
 int kvzap_mask_per_head(const float* scores, const float* tau, int window,

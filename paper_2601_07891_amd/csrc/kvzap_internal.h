@@ -10,6 +10,7 @@ namespace kvzap {
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
@@ -17,6 +18,9 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 constexpr int kMaskChunk = 1024;
 
 inline int mask_chunks(int T) { return (T + kMaskChunk - 1) / kMaskChunk; }
+
+// chunks (of all heads together) the built-in scratch of kvzap_mask_static has room for
+constexpr int kStaticMaskChunks = KVZAP_MASK_STATIC_MAX_CHUNKS;
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -80,6 +84,11 @@ __device__ __forceinline__ void load_to_lds_b32(const void* gptr, unsigned lds_b
 int launch_mask(const float* scores, float tau, const float* tau_head, int window,
                 const int32_t* seq_lens, int B, int H, int T, int32_t* keep_idx,
                 int32_t* lengths, int64_t* offsets, void* workspace, hipStream_t stream);
+
+// kvzap_mask on the library's own scratch (no workspace, nothing allocated)
+int launch_mask_static(const float* scores, float tau, int window, const int32_t* seq_lens, int B,
+                       int H, int T, int32_t* keep_idx, int32_t* lengths, int64_t* offsets,
+                       hipStream_t stream);
 
 int launch_topk_threshold(const float* scores, int window, const int32_t* seq_lens, long long k,
                           bool per_layer, int B, int H, int T, float* tau_out, void* workspace,

@@ -12,10 +12,44 @@
 //              also writes lengths and offsets; beyond that a single-block scan
 //              kernel runs between the two.
 // No block waits for another, so there is nothing that can spin.
+#include <mutex>
+
 #include "kvzap_internal.h"
 
 namespace kvzap {
 namespace {
+
+// Scratch of the allocation-free entry point (kvzap_mask_static): the chunk counts and chunk
+// prefixes that kvzap_mask keeps in its caller's workspace, for up to kStaticMaskChunks
+// 1024-token chunks.  One copy per GPU, at its own address on each, held until the process
+// ends; every call on a GPU shares it, so calls that overlap on one GPU race.  Nothing in it
+// has to start at zero: the count kernel writes every entry the later kernels read.
+constexpr size_t kStaticCountBytes = (size_t)kStaticMaskChunks * sizeof(int32_t);
+constexpr size_t kStaticScratchBytes = kStaticCountBytes + (size_t)kStaticMaskChunks * sizeof(int64_t);
+static_assert(kStaticCountBytes % 256 == 0, "the prefix part stays 256-byte aligned");
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// In host code `scratch` is only a stand-in for the symbol, not a device address: the address
+// on the current GPU is looked up once per device and kept here.
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void* scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return KVZAP_ERR_RUNTIME;
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (!scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return KVZAP_ERR_RUNTIME;
+    }
+    scratch_ptr[dev] = p;
+  }
+  *out = scratch_ptr[dev];
+  return KVZAP_OK;
+}
 
 constexpr int kThreads = 256;            // 4 wavefronts
 constexpr int kPerThread = kMaskChunk / kThreads;  // 4 consecutive tokens
@@ -217,6 +251,18 @@ int launch_mask(const float* scores, float tau, const float* tau_head, int windo
                                                            keep_idx, lengths, offsets);
   }
   return hipGetLastError() == hipSuccess ? KVZAP_OK : KVZAP_ERR_RUNTIME;
+}
+
+int launch_mask_static(const float* scores, float tau, int window, const int32_t* seq_lens, int B,
+                       int H, int T, int32_t* keep_idx, int32_t* lengths, int64_t* offsets,
+                       hipStream_t stream) {
+  if ((long long)B * H * mask_chunks(T) > (long long)kStaticMaskChunks) return KVZAP_ERR_STATIC_LIMIT;
+  void* ws = nullptr;
+  const int rc = static_scratch(&ws);
+  if (rc != KVZAP_OK) return rc;
+  // launch_mask splits its workspace at align_up(chunks * 4, 256) <= kStaticCountBytes
+  return launch_mask(scores, tau, nullptr, window, seq_lens, B, H, T, keep_idx, lengths, offsets,
+                     ws, stream);
 }
 
 }  // namespace kvzap

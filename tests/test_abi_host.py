@@ -38,11 +38,11 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_status_strings(lib):
     seen = set()
-    for code in range(0, -8, -1):
+    for code in range(0, -9, -1):
         s = lib.kvzap_status_string(code).decode()
         assert s and s != "unknown status"
         seen.add(s)
-    assert len(seen) == 8
+    assert len(seen) == 9
     assert lib.kvzap_status_string(-99).decode() == "unknown status"
     assert re.fullmatch(r"\d+\.\d+\.\d+", lib.kvzap_version().decode())
 
@@ -66,6 +66,24 @@ def test_workspace_queries(lib):
 
 P = 0x10000      # fake, aligned, never dereferenced: all calls below fail validation first
 ERR = dict(null=-1, shape=-2, align=-3, unsupported=-4, capacity=-5, workspace=-6)
+
+
+def test_mask_static_rejects_before_any_gpu_call(lib):
+    # the allocation-free mask: kvzap_mask's checks, then its own size limit -- all on the host
+    f = lib.kvzap_mask_static
+    assert f(None, 0.0, 128, None, 1, 8, 1024, P, P, P, None) == ERR["null"]
+    assert f(P, 0.0, 128, None, 1, 8, 1024, None, P, P, None) == ERR["null"]
+    assert f(P, 0.0, -1, None, 1, 8, 1024, P, P, P, None) == ERR["shape"]
+    assert f(P, float("nan"), 128, None, 1, 8, 1024, P, P, P, None) == ERR["shape"]
+    assert f(P + 4, 0.0, 128, None, 1, 8, 1024, P, P, P, None) == ERR["align"]
+    assert f(P, 0.0, 128, None, 8192, 8, 1024, P, P, P, None) == ERR["unsupported"]   # B*H > 65535
+    limit = 65536                                   # KVZAP_MASK_STATIC_MAX_CHUNKS
+    text = open(os.path.join(ROOT, "include", "kvzap.h")).read()
+    assert int(re.search(r"#define KVZAP_MASK_STATIC_MAX_CHUNKS (\d+)", text).group(1)) == limit
+    # one chunk too many: 8 heads x (limit/8 + 1) chunks of 1024 positions
+    assert f(P, 0.0, 128, None, 1, 8, (limit // 8) * 1024 + 1, P, P, P, None) == -8
+    assert f(P, 0.0, 128, None, 8, 16, 513 * 1024, P, P, P, None) == -8
+    assert "built-in scratch" in lib.kvzap_status_string(-8).decode()
 
 
 def test_score_argument_errors(lib):
