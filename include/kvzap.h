@@ -94,8 +94,8 @@ size_t kvzap_workspace_bytes(int which_call, int B, int T, int Dh, int M, int H)
  *
  *   M == 0 : KVzap-Linear   scores[b,h,t] = sum_k hidden[b,t,k] * W1[h,k] + b1[h]
  *   M  > 0 : KVzap-MLP      z = hidden[b,t,:] . W1[m,:] + b1[m]        (m < M)
- *                           g = GELU(z) = z * Phi(z)  (erf form, not the tanh one; fp32, erf
- *                               evaluated to 1.5e-7 absolute)
+ *                           g = GELU(z) = z * Phi(z)  (erf form, not the tanh one; evaluated in
+ *                               fp32 to 2.6e-5 absolute, see "Arithmetic")
  *                           scores[b,h,t] = sum_m g[m] * W2[h,m] + b2[h]
  *
  *   hidden  bf16 [B, T, Dh]
@@ -109,12 +109,16 @@ size_t kvzap_workspace_bytes(int which_call, int B, int T, int Dh, int M, int H)
  * workspace: see kvzap_workspace_bytes(KVZAP_CALL_SCORE, ...); may be NULL when
  * that is 0 (linear surrogate).  KVZAP_ERR_WORKSPACE if missing, misaligned or small.
  *
- * Arithmetic: bf16 products accumulated in fp32 on the matrix cores; GELU in
- * fp32; the GELU output enters the second projection as a bf16 pair (high part
- * plus residual), i.e. to about 16 mantissa bits; short inputs (see the workspace query)
- * take a split first projection whose second projection is plain fp32.  The sum order is
- * fixed for a given shape, so results are run-to-run deterministic; the same token scored
- * in calls of different B*T may differ in the last bits.  B*T == 0 is a no-op.
+ * Arithmetic: bf16 products accumulated in fp32 on the matrix cores (the accumulation starts
+ * from b1).  In the single-kernel path GELU is z * sigmoid(z * p(z^2)) with a fitted cubic p,
+ * within 2.6e-5 (absolute) of z * Phi(z) for every z, evaluated in fp32; its result is rounded
+ * to fp16 (relative 2^-11; values beyond 65504 become infinite) and W2 is converted to fp16
+ * (exact for bf16 magnitudes in [2^-14, 65504], subnormal or infinite beyond) for the second
+ * projection on the matrix cores, accumulated in fp32.  Short inputs (see the workspace
+ * query) take a split first projection whose GELU (erf to 1.5e-7) and second projection are
+ * plain fp32.  Both are far inside the 1e-2 score tolerance.  The sum order is fixed for a
+ * given shape, so results are run-to-run deterministic; the same token scored in calls of
+ * different B*T may differ in the last bits.  B*T == 0 is a no-op.
  */
 int kvzap_score(const void* hidden, const void* W1, const void* b1,
                 const void* W2, const void* b2, float* scores,

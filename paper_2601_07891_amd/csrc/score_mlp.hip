@@ -53,6 +53,22 @@ __device__ __forceinline__ float gelu_exact(float z) {
   return z * phi;
 }
 
+// The fused epilogue's GELU: z * sigmoid(z * (c0 + c1 z^2 + c2 z^4)), the coefficients fitted
+// to z * Phi(z) (the erf form) in the minimax sense: |error| <= 2.6e-5 absolute for every z
+// (z^2 is clamped at 64, beyond which the sigmoid is 0 or 1 to 1e-12).  Its result is rounded
+// to fp16 for the second projection (relative 4.9e-4), so the 1.5e-7 of gelu_exact would buy
+// nothing there; this form is seven plain operations, one exp2 and one rcp, half the vector
+// work of gelu_exact, and that work is not overlapped with matrix-core work.  The constants
+// carry the factor -log2(e): sigmoid(x) = 1 / (1 + 2^(-x log2 e)).  z -> -inf gives -0, NaN
+// stays NaN.
+__device__ __forceinline__ float gelu_fused(float z) {
+  const float z2 = fminf(z * z, 64.0f);
+  float q = fmaf(z2, 0.001014264184050262f, -0.10677573084831238f);
+  q = fmaf(z2, q, -2.301121234893799f);
+  const float e = __builtin_amdgcn_exp2f(z * q);
+  return z * __builtin_amdgcn_rcpf(1.0f + e);
+}
+
 __device__ __forceinline__ int lds_off(int row, int piece) {   // bytes
   return row * 128 + ((piece ^ (row & 7)) << 4);
 }
@@ -269,25 +285,29 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
   const long long row0 = (long long)blockIdx.x * TOK;
   const int rows_here = (rows - row0 < TOK) ? (int)(rows - row0) : TOK;
 
-  // The epilogue's operands (W2 and b1, a few KB) are staged in LDS behind the ring: read
-  // from global memory there, every one of its 64 small loads would expose a full memory
-  // round trip with nothing to overlap it.  The loads are issued here, ahead of the
-  // prologue's traffic, and written to LDS once the prologue has waited for hidden tile 0
-  // (vector-memory operations complete in issue order).
-  constexpr int kW2Pieces = U / 128;                    // 16-byte pieces of W2 per thread (H <= 16)
-  unsigned char* const sW2 = smem + kNS * STAGE;        // [H][U] bf16
-  float* const sB1 = reinterpret_cast<float*>(sW2 + 16 * U * 2);   // [U] fp32
+  // The epilogue's A operand (W2, a few KB) is staged in LDS behind the ring, converted to
+  // fp16 and zero-filled up to 16 heads: read from global memory in the epilogue, every one of
+  // its small loads would expose a full memory round trip with nothing to overlap it.  b1 is
+  // what the accumulators start from.  Both are loaded here, ahead of the prologue's traffic,
+  // and used once the prologue has waited for hidden tile 0 (vector-memory operations
+  // complete in issue order).
+  constexpr int kW2Pieces = U / 128;                    // 16-byte pieces of the 16 x U matrix per thread
+  unsigned char* const sW2 = smem + kNS * STAGE;        // [16][U] fp16
   u32x4 w2_stage[kW2Pieces];
-  unsigned short b1_stage[U / 256 + 1];
 #pragma unroll
   for (int i = 0; i < kW2Pieces; ++i) {
     const int piece = i * 256 + tid;
     w2_stage[i] = piece < H * (U / 8) ? reinterpret_cast<const u32x4*>(W2)[piece] : u32x4{0u, 0u, 0u, 0u};
   }
+  // accumulator register 4q+e of block (ub, .) is unit wid*32*UB + 32*ub + 8*q + 4*kg + e
+  uint2 b1_stage[UB][4];
+  if constexpr (!kSplit) {
 #pragma unroll
-  for (int i = 0; i < U / 256 + 1; ++i) {
-    const int u = i * 256 + tid;
-    b1_stage[i] = (b1 && u < U) ? b1[u] : (unsigned short)0;
+    for (int ub = 0; ub < UB; ++ub)
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        b1_stage[ub][q] = b1 ? *reinterpret_cast<const uint2*>(b1 + wid * (32 * UB) + 32 * ub + 8 * q + 4 * kg)
+                             : uint2{0u, 0u};
   }
 
   // hidden load-to-LDS: instruction j (0..3) of wavefront w fills LDS chunk j*4+w of a
@@ -315,12 +335,6 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
   };
 
   floatx16 acc[UB][TB];
-#pragma unroll
-  for (int ub = 0; ub < UB; ++ub)
-#pragma unroll
-    for (int tb = 0; tb < TB; ++tb)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[ub][tb][e] = 0.0f;
 
   // nk >= kPD + 1 tiles (checked by the launcher)
   bf16x8 a[4][UB];                         // a[kk]: step kk of the current tile, then of the next
@@ -345,14 +359,29 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
   block_barrier_no_drain();
 #pragma unroll
   for (int i = 0; i < kW2Pieces; ++i) {
-    const int piece = i * 256 + tid;
-    if (piece < H * (U / 8)) reinterpret_cast<u32x4*>(sW2)[piece] = w2_stage[i];
-  }
+    f16x8 w;
 #pragma unroll
-  for (int i = 0; i < U / 256 + 1; ++i) {
-    const int u = i * 256 + tid;
-    if (u < U) sB1[u] = bf16_bits_to_float(b1_stage[i]);
+    for (int e = 0; e < 4; ++e) {
+      w[2 * e] = (_Float16)__uint_as_float(w2_stage[i][e] << 16);
+      w[2 * e + 1] = (_Float16)__uint_as_float(w2_stage[i][e] & 0xffff0000u);
+    }
+    reinterpret_cast<f16x8*>(sW2)[i * 256 + tid] = w;
   }
+  // the first projection accumulates on top of b1 (a K-slice of a split launch: on zero)
+#pragma unroll
+  for (int ub = 0; ub < UB; ++ub)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      float v[4] = {0.f, 0.f, 0.f, 0.f};
+      if constexpr (!kSplit) {
+        v[0] = __uint_as_float(b1_stage[ub][q].x << 16); v[1] = __uint_as_float(b1_stage[ub][q].x & 0xffff0000u);
+        v[2] = __uint_as_float(b1_stage[ub][q].y << 16); v[3] = __uint_as_float(b1_stage[ub][q].y & 0xffff0000u);
+      }
+#pragma unroll
+      for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[ub][tb][4 * q + e] = v[e];
+    }
   auto read_b = [&](int buf, int tile, int kk, int tb) {
     b[buf][tb] = *reinterpret_cast<const bf16x8*>(
         smem + (tile % kNS) * STAGE + lds_off(32 * tb + l32, kk * 2 + kg));
@@ -400,10 +429,14 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
           for (int j = 0; j < NDJ; ++j)
             if (j * 2 * UB / NDJ == (kk - 2) * UB + ub) dma(j, t + kPD);
         }
+        // token blocks in alternating direction: the MFMA that opens a group then keeps the B
+        // operand of the one before it (both operands switch at once otherwise); measured 1-2 %
 #pragma unroll
-        for (int tb = 0; tb < TB; ++tb)
+        for (int i = 0; i < TB; ++i) {
+          const int tb = (ub & 1) ? TB - 1 - i : i;
           acc[ub][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk][ub], b[kk & 1][tb],
                                                                 acc[ub][tb], 0, 0, 0);
+        }
         // re-load the fragment of the PREVIOUS group: a load issued right behind the MFMAs
         // that still read its destination registers costs extra issue cycles
         if (more) {
@@ -445,7 +478,10 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
   }
   __syncthreads();      // LDS is reused for the reduction below
 
-  // ---- epilogue: bias + GELU, then the M -> H projection as a second MFMA ----
+  // ---- epilogue: GELU, then the M -> H projection as a second MFMA (fp16 operands) ----
+  // acc[ub][tb][r] is z of unit  ubase + 32*ub + 8*(r/4) + 4*kg + r%4  of token 32*tb + l32.
+  // Registers 8s..8s+7 form the B operand of MFMA step s; the matching A operand holds
+  // W2[head = l32][the same eight units] (zero for heads >= H).
   const int ubase = wid * (32 * UB);
   floatx16 acc2[TB];
 #pragma unroll
@@ -458,31 +494,18 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
     for (int s = 0; s < 2; ++s) {
       const int u0 = ubase + 32 * ub + 16 * s + 4 * kg;
       u32x4 w2 = {0u, 0u, 0u, 0u};
-      if (l32 < H) {
+      if (l32 < 16) {
         const uint2 p0 = *reinterpret_cast<const uint2*>(sW2 + ((size_t)l32 * U + u0) * 2);
         const uint2 p1 = *reinterpret_cast<const uint2*>(sW2 + ((size_t)l32 * U + u0 + 8) * 2);
         w2.x = p0.x; w2.y = p0.y; w2.z = p1.x; w2.w = p1.y;
       }
-      const floatx4 bias_lo = *reinterpret_cast<const floatx4*>(sB1 + u0);
-      const floatx4 bias_hi = *reinterpret_cast<const floatx4*>(sB1 + u0 + 8);
-      float bias[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) bias[e] = e < 4 ? bias_lo[e] : bias_hi[e - 4];
 #pragma unroll
       for (int tb = 0; tb < TB; ++tb) {
-        // GELU output as a bf16 pair: ghi = round(g), glo = round(g - ghi) (hardware RNE
-        // conversions, two values per instruction)
-        bf16x8 ghi, glo;
+        f16x8 g;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const float g = gelu_exact(acc[ub][tb][8 * s + e] + bias[e]);
-          ghi[e] = (__bf16)g;
-          glo[e] = (__bf16)(g - (float)ghi[e]);
-        }
-        acc2[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w2), ghi,
-                                                           acc2[tb], 0, 0, 0);
-        acc2[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w2), glo,
-                                                           acc2[tb], 0, 0, 0);
+        for (int e = 0; e < 8; ++e) g[e] = (_Float16)gelu_fused(acc[ub][tb][8 * s + e]);
+        acc2[tb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, w2), g,
+                                                          acc2[tb], 0, 0, 0);
       }
     }
   }
@@ -603,7 +626,7 @@ int launch_frag(const void* hidden, const void* W1, const void* b1, const void* 
   constexpr int TOK = 32 * TB;
   constexpr size_t ring = (size_t)kNS * TOK * 128;
   static_assert(ring >= (size_t)4 * 16 * TOK * sizeof(float), "reduction buffer fits");
-  constexpr size_t lds = ring + (size_t)16 * (128 * UB) * 2 + (size_t)(128 * UB) * 4;   // + W2, b1
+  constexpr size_t lds = ring + (size_t)16 * (128 * UB) * 2;   // + W2 as [16][M] fp16
   // once per process, which drives one GPU (thread-safe: a function-local static)
   static const hipError_t attr_rc =
       hipFuncSetAttribute(reinterpret_cast<const void*>(score_mlp_frag_kernel<UB, TB, false>),

@@ -133,6 +133,57 @@ def test_mlp_no_bias_and_unit_selectivity():
         assert np.abs(got - want).max() < 2e-4
 
 
+@pytest.mark.parametrize("Dh,M", [(512, 512), (1024, 640), (256, 128)])
+def test_fused_epilogue_unit_selectivity(Dh, M):
+    # The same one-hot W2 through kvzap_score_prepared, which always runs the single kernel with
+    # the fused epilogue (GELU fitted to 2.6e-5, result rounded to fp16 for the second matrix
+    # product): every unit position of a wavefront's accumulator blocks must reach the head
+    # that W2 names, and b1 must reach its unit through the accumulators' initial value.
+    T, H = 300, 8
+    wl = synth.Workload("t", L=1, B=1, T=T, Dh=Dh, H=H, scorer="mlp", seed=4)
+    hid = synth.make_hidden(wl)
+    g = torch.Generator().manual_seed(1)
+    W1 = (torch.randn((M, Dh), generator=g) * Dh ** -0.5).bfloat16()
+    b1 = (torch.randn((M,), generator=g)).bfloat16()
+    z = hid[0].double().numpy() @ W1.double().numpy().T + b1.double().numpy()
+    G = O.gelu(z)
+    prep = binding.kvzap_prepare_scorer(W1.to(DEV))
+    for base in range(0, 128, 8):
+        W2 = torch.zeros((H, M), dtype=torch.bfloat16)
+        units = [(base + h + 133 * h) % M for h in range(H)]
+        for h, u in enumerate(units):
+            W2[h, u] = 1.0
+        got = binding.kvzap_score_prepared(hid.to(DEV), prep, b1.to(DEV), W2.to(DEV), None)
+        torch.cuda.synchronize()
+        got = parity.to_np(got)[0].astype(np.float64)
+        want = G[:, units].T
+        assert (np.abs(got - want) <= 6e-4 * np.abs(want) + 6e-5).all(), np.abs(got - want).max()
+
+
+def test_fused_gelu_over_its_whole_range():
+    # z swept over [-12, 12] (and far beyond) through the fused kernel: identity weights pick
+    # hidden columns, so z is exact and the score is GELU(z) as the kernel evaluates it
+    T, Dh, M, H = 4096, 256, 128, 8
+    hid = torch.zeros((1, T, Dh), dtype=torch.bfloat16)
+    zs = torch.linspace(-12.0, 12.0, T).bfloat16()
+    zs[:8] = torch.tensor([-200.0, -50.0, -14.0, 14.0, 50.0, 200.0, 0.0, -0.0]).bfloat16()
+    for h in range(H):
+        hid[0, :, h] = zs * (1.0 if h % 2 == 0 else -1.0)
+    W1 = torch.zeros((M, Dh), dtype=torch.bfloat16)
+    W2 = torch.zeros((H, M), dtype=torch.bfloat16)
+    for h in range(H):
+        W1[17 * h + 3, h] = 1.0
+        W2[h, 17 * h + 3] = 1.0
+    prep = binding.kvzap_prepare_scorer(W1.to(DEV))
+    got = binding.kvzap_score_prepared(hid.to(DEV), prep, None, W2.to(DEV), None)
+    torch.cuda.synchronize()
+    got = parity.to_np(got)[0].astype(np.float64)
+    z = hid[0].double().numpy()[:, :H].T
+    want = O.gelu(z)
+    assert np.isfinite(got).all()
+    assert (np.abs(got - want) <= 6e-4 * np.abs(want) + 6e-5).all(), np.abs(got - want).max()
+
+
 def test_mlp_exact_first_projection():
     # integer inputs: z is exact, so the only error left is GELU + second projection
     T, Dh, M, H = 200, 256, 128, 8
