@@ -27,7 +27,11 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a plain
-# streaming kernel of known size; see profiles/c3_hbm_traffic.txt): (workload, kernel) -> bytes
+# streaming kernel of known size): (workload, kernel) -> bytes.  These are CONSTANTS copied from
+# the named profile summaries, not re-measured by this program; the bench line says so
+# (`traffic_source`), and they are refreshed whenever a kernel changes.
+TRAFFIC_SOURCE = {"c3_qwen8b_128k_mlp": "constant from profiles/c3_hbm_traffic.txt",
+                  "c5_qwen8b_decode+attend": "constant from profiles/c5_attend_hbm_traffic.txt"}
 MEASURED_HBM_TRAFFIC = {
     ("c3_qwen8b_128k_mlp", "score_mlp_frag_kernel"): 1209.2e6 + 4.2e6,
     ("c3_qwen8b_128k_mlp", "compact_kernel"): 146.5e6 + 143.3e6,
@@ -90,7 +94,7 @@ def _oracle_sample(wl, layer0, sample_tokens):
     return tau, info, S
 
 
-def bench_decode(wl, args) -> int:
+def bench_decode(wl, args) -> dict:
     """Decode-phase eviction (non-default workload): every step appends one token to each of
     B sequences in each of L layers: L calls of kvzap_decode_evict per step."""
     dev = torch.device("cuda:0")
@@ -174,11 +178,10 @@ def bench_decode(wl, args) -> int:
                           "tokens_per_s": B / (graph_ms * 1e-3)}),
            "roofline": None, "cpu_baseline": None,
            "note": "latency-bound: ~5.5 MB per layer-step; one library call per layer per step, eager"}
-    print(json.dumps(out))
-    return 0
+    return out
 
 
-def bench_attend(wl, args) -> int:
+def bench_attend(wl, args) -> dict:
     """Decode-step attention over the ragged per-head cache (non-default stage of the decode
     workload): one step = one kvzap_attend_decode call per layer for B sequences, every
     (sequence, head) holding its own number of kept rows plus a full window ring."""
@@ -274,7 +277,7 @@ def bench_attend(wl, args) -> int:
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = len(os.sched_getaffinity(0))
-    print(json.dumps({
+    return ({
         "metric": "decode-attention tokens/sec (all layers per token)",
         "value": B / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": steps,
         "warmup": warm, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
@@ -295,11 +298,10 @@ def bench_attend(wl, args) -> int:
                          "cores": int(threads), "kind": "oracle",
                          "sample": f"sequence 0 of layer 0: {H} KV heads x {G} query heads over "
                                    f"{sample_rows} cache rows, float64 numpy",
-                         "max_abs_diff_vs_gpu": err}}))
-    return 0
+                         "max_abs_diff_vs_gpu": err}})
 
 
-def bench_teacher(wl, args) -> int:
+def bench_teacher(wl, args) -> dict:
     """Teacher scores (KVzip+ of Eq. 3) of one layer of one extended prompt: a prompt of
     --teacher-tokens tokens, a 32-token instruction, the prompt repeated (non-default stage)."""
     dev = torch.device("cuda:0")
@@ -339,8 +341,12 @@ def bench_teacher(wl, args) -> int:
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
     ms_call = ev0.elapsed_time(ev1) / args.steps
     P0 = Tk - Tq
-    pairs1 = sum(P0 + j + 1 for j in range(Tq))              # visible (query, key) pairs, row pass
-    flops = 2 * D * HQ * (pairs1 + Tq * T)                   # both passes compute q.k once per pair
+    # Eq. 1 / Eq. 3 need every a_ji of a visible (query, key) pair once: that is the method's own
+    # work.  The kernels compute q.k a second time for the (query, prompt key) pairs of the
+    # column pass instead of storing the first result: executed, not algorithmic.
+    pairs1 = sum(P0 + j + 1 for j in range(Tq))
+    flops = 2 * D * HQ * pairs1
+    executed_flops = 2 * D * HQ * (pairs1 + Tq * T)
     achieved = flops / (ms_call * 1e-3) / 1e12
 
     from oracle import kvzap_oracle as O       # cpu_baseline leg only
@@ -357,7 +363,7 @@ def bench_teacher(wl, args) -> int:
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = len(os.sched_getaffinity(0))
-    print(json.dumps({
+    return ({
         "metric": "teacher-score prompt tokens/sec per layer (KVzip+ scores, all KV heads)",
         "value": T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
@@ -368,69 +374,21 @@ def bench_teacher(wl, args) -> int:
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
                      "kernel": "teacher_rowstat_kernel + teacher_colmax_kernel (one interval)",
-                     "algorithmic_flops_per_launch": flops},
+                     "algorithmic_flops_per_launch": flops,
+                     "executed_flops_per_launch": executed_flops,
+                     "executed_TFLOP/s": executed_flops / (ms_call * 1e-3) / 1e12},
         "cpu_baseline": {"value": T / (c1 - c0) / H, "unit": "tokens/s", "cores": int(threads),
                          "kind": "oracle",
                          "sample": f"KV head 0 ({G} query heads) of the same prompt, float64 numpy; "
                                    f"value scaled to all {H} KV heads",
-                         "max_abs_diff_vs_gpu": err}}))
-    return 0
+                         "max_abs_diff_vs_gpu": err}})
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", default="c3_qwen8b_128k_mlp", choices=sorted(synth.CONFIGS))
-    ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = config's)")
-    ap.add_argument("--sample-tokens", type=int, default=0,
-                    help="tokens per sequence the CPU oracle is timed on (0 = all of layer 0)")
-    ap.add_argument("--two-streams", action="store_true",
-                    help="run mask+compact of layer l on a second stream while the scorer of layer "
-                         "l+1 runs (measured: +1 %% throughput, the scorer slows under contention); "
-                         "default is one stream, which keeps per-kernel timings clean")
-    ap.add_argument("--prepared-weights", action="store_true",
-                    help="MLP surrogate: re-order W1 once with kvzap_prepare_scorer before the timed "
-                         "region and score with kvzap_score_prepared (default: kvzap_score, which "
-                         "re-orders W1 on every call)")
-    ap.add_argument("--decode-cache-rows", type=int, nargs=2, default=[4096, 32768],
-                    help="decode workload: range of rows already kept per (sequence, head)")
-    ap.add_argument("--select", default="threshold", choices=["threshold", "topk-head", "topk-layer"],
-                    help="eviction rule of the mask stage: the paper's global threshold (default) or "
-                         "the fixed-budget variants of its ablation at the same kept fraction")
-    ap.add_argument("--page-rows", type=int, default=0,
-                    help="0 (default): packed contiguous output; a power of two >= 16: paged output "
-                         "(kvzap_assign_pages + kvzap_compact_paged) and, for --stage attend, the "
-                         "paged attention over a shuffled page pool")
-    ap.add_argument("--graph", action="store_true",
-                    help="decode workload: also time the step replayed from a HIP graph")
-    ap.add_argument("--stage", default="evict", choices=["evict", "attend", "teacher"],
-                    help="decode workload: time the eviction step (default) or the attention "
-                         "over the ragged cache it maintains; 'teacher' (any config): the "
-                         "KVzip+ training scores of one extended prompt")
-    ap.add_argument("--teacher-tokens", type=int, default=8192,
-                    help="--stage teacher: prompt length (the extended prompt is twice that + 32)")
-    ap.add_argument("--query-heads", type=int, default=32,
-                    help="decode attention: number of query heads (Qwen3-8B: 32 over 8 KV heads)")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run a plain 1 GiB device copy (reference for HBM byte counters)")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(the path shards by layer / sequence / KV head with no communication)",
-              file=sys.stderr)
-        return 2
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        return 2
-    binding.lib()                                   # fail loudly if the library is not built
-    wl = synth.CONFIGS[args.config]
-    if args.stage == "teacher":
-        return bench_teacher(wl, args)
-    if wl.T == 1:
-        return bench_attend(wl, args) if args.stage == "attend" else bench_decode(wl, args)
-    L = args.layers or wl.L
+def bench_prefill(wl, args, L, oracle: bool, extras: bool) -> dict:
+    """Prune step (score, mask, compact) over L resident layers of a prefill workload.
+    oracle: tau and the cpu_baseline come from the float64 oracle on layer 0 (the headline
+    workload); otherwise tau is the keep-fraction quantile of the GPU's own layer-0 scores (it
+    only sets how many rows are kept).  extras: the vendor GEMM for context."""
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     B, T, H, D, Dh, M = wl.B, wl.T, wl.H, wl.D, wl.Dh, wl.M
@@ -469,7 +427,17 @@ def main() -> int:
     sample_tokens = T if args.sample_tokens <= 0 else min(args.sample_tokens, T)
     if sample_tokens < T:
         sample_tokens = min(sample_tokens, max(T - wl.window, 1))
-    tau, cpu_info, S_ref = _oracle_sample(wl, layers[0], sample_tokens)
+    if oracle:
+        tau, cpu_info, S_ref = _oracle_sample(wl, layers[0], sample_tokens)
+    else:
+        # tau only sets how many rows are kept: the keep-fraction quantile of the GPU's own
+        # layer-0 scores over the non-window positions (every 8th position of every head)
+        w0 = layers[0]["w"]
+        s0 = binding.kvzap_score(layers[0]["hidden"], w0["W1"], w0["b1"], w0["W2"], w0["b2"])
+        pool = s0[:, :, :max(T - wl.window, 1)][:, :, ::8].reshape(-1).float()
+        tau = float(torch.quantile(pool[:4_000_000], 1.0 - wl.keep_fraction))
+        cpu_info, S_ref, sample_tokens = None, None, 0
+        del s0, pool
     if args.copy_calibration:                   # 1 GiB read + 1 GiB written by a plain copy
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
@@ -552,8 +520,10 @@ def main() -> int:
     torch.cuda.synchronize()
 
     # sanity: the GPU scores of the sample agree with the oracle's (not a timed part)
-    got = layers[0]["scores"][:, :, :sample_tokens].double().cpu().numpy()
-    score_err = float(np.max(np.abs(got - S_ref) / np.maximum(np.abs(S_ref), 1.0)))
+    score_err = None
+    if S_ref is not None:
+        got = layers[0]["scores"][:, :, :sample_tokens].double().cpu().numpy()
+        score_err = float(np.max(np.abs(got - S_ref) / np.maximum(np.abs(S_ref), 1.0)))
 
     score_events = []
     torch.cuda.synchronize()
@@ -580,6 +550,9 @@ def main() -> int:
 
     mask_ms = time_stage(mask)
     compact_ms = time_stage(compact)
+    # Algorithm 1's last three lines as ONE stage: both calls between one pair of events
+    # (their kernels queue back to back), against the bytes of both
+    mask_compact_ms = time_stage(lambda ly: (mask(ly), compact(ly)))
     assign_ms = None
     if P:
         if any(int(ly["pages"][1]) != 0 for ly in layers):
@@ -608,6 +581,8 @@ def main() -> int:
         score_flops if M else B * T * (2 * Dh + 4 * H))
     if L == wl.L:
         roofline["traffic"] = MEASURED_HBM_TRAFFIC.get((wl.name, roofline["kernel"]))
+        if roofline["traffic"] is not None:
+            roofline["traffic_source"] = TRAFFIC_SOURCE[wl.name]
         compact_traffic = None if P else MEASURED_HBM_TRAFFIC.get((wl.name, "compact_kernel"))
     else:
         compact_traffic = None
@@ -616,11 +591,18 @@ def main() -> int:
                     "unit": "GB/s", "traffic": compact_traffic, "avg_launch_ms": compact_ms,
                     "algorithmic_bytes_per_launch": compact_bytes}
     compact_roof["frac"] = compact_roof["achieved"] / compact_roof["peak"]
+    # mask: every score read once (4 B), every kept position written once (4 B)
+    mc_bytes = compact_bytes + B * H * T * 4 + kept_rows * 4
+    mc_roof = {"kernel": "mask_count_kernel + mask_emit_kernel + compact_kernel (one interval)",
+               "bound": "hbm", "achieved": mc_bytes / (mask_compact_ms * 1e-3) / 1e9,
+               "peak": PEAK_HBM_GBS, "unit": "GB/s", "traffic": None,
+               "avg_launch_ms": mask_compact_ms, "algorithmic_bytes_per_launch": mc_bytes}
+    mc_roof["frac"] = mc_roof["achieved"] / mc_roof["peak"]
 
     # context, not a target and not on the product path: the vendor library's GEMM (torch.matmul,
     # i.e. hipBLASLt) on the scorer's FIRST projection alone, same operands, bf16 output
     library_gemm = None
-    if M:
+    if M and extras:
         hid2d = [ly["hidden"].reshape(B * T, Dh) for ly in layers]
         w1 = [ly["w"]["W1"] for ly in layers]
         z = torch.empty((B * T, M), dtype=torch.bfloat16, device=dev)
@@ -653,17 +635,127 @@ def main() -> int:
                    "generator": f"torch {torch.__version__} cuda philox, seeds per layer"},
         "roofline": roofline,
         "roofline_compact": compact_roof,
+        "roofline_mask_compact": mc_roof,
         "stages_ms_per_layer": {"score": score_ms, "mask": mask_ms, "compact": compact_ms,
+                                "mask_compact": mask_compact_ms,
                                 "assign_pages": assign_ms,
                                 "sum": score_ms + mask_ms + compact_ms + (assign_ms or 0.0),
                                 "wall": ms_per_step / L,
                                 "streams": 2 if args.two_streams else 1,
-                                "note": "score timed inside the step; mask and compact timed "
-                                        "alone on one stream after it"},
+                                "note": "score timed inside the step; mask, compact and the two "
+                                        "together (mask_compact, one event pair) timed alone on "
+                                        "one stream after it"},
         "score_max_rel_err_vs_oracle_sample": score_err,
         "library_gemm_context": library_gemm,
         "cpu_baseline": cpu_info,
     }
+    return out
+
+
+def other_workloads(args) -> list:
+    """The remaining configurations, each timed in this same run after the headline workload has
+    released its memory: short figures (tokens/s, per-stage times, the roofline of the dominant
+    kernel, kept fraction), no CPU baseline.  Layers resident: enough to exceed the 256 MB
+    last-level cache several times over."""
+    import copy
+    import gc
+    res = []
+
+    def brief(d, keys):
+        return {k: d[k] for k in keys if k in d}
+
+    keys = ("metric", "value", "unit", "steps", "warmup", "ms_per_step", "config", "roofline",
+            "roofline_compact", "roofline_mask_compact", "stages_ms_per_layer")
+    for name, layers, steps in (("c1_t1k_linear", 16, 20), ("c2_llama8b_32k_mlp", 12, 10),
+                                ("c4_qwen32b_4x64k_linear", 4, 5), ("c4_qwen32b_4x64k_mlp", 4, 5)):
+        a = copy.copy(args)
+        a.steps, a.warmup, a.sample_tokens, a.page_rows, a.select = steps, 2, 0, 0, "threshold"
+        a.two_streams, a.copy_calibration = False, False
+        gc.collect(); torch.cuda.empty_cache()
+        res.append(brief(bench_prefill(synth.CONFIGS[name], a, layers, oracle=False, extras=False), keys))
+    gc.collect(); torch.cuda.empty_cache()
+    wl5 = synth.CONFIGS["c5_qwen8b_decode"]
+    a = copy.copy(args)
+    a.steps, a.warmup, a.layers, a.graph, a.page_rows = 32, 4, 0, True, 0
+    res.append(brief(bench_decode(wl5, a), ("metric", "value", "unit", "steps", "warmup", "ms_per_step",
+                                            "config", "us_per_layer_step", "hip_graph", "note")))
+    gc.collect(); torch.cuda.empty_cache()
+    a = copy.copy(args)
+    a.steps, a.warmup, a.layers, a.page_rows = 5, 1, 0, 0
+    res.append(brief(bench_attend(wl5, a), ("metric", "value", "unit", "steps", "warmup", "ms_per_step",
+                                            "config", "ms_per_call", "roofline")))
+    gc.collect(); torch.cuda.empty_cache()
+    return res
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default=None, choices=sorted(synth.CONFIGS),
+                    help="one workload only; default: the 128k-token Qwen3-8B prefill (the headline) "
+                         "followed by the other configurations under the key other_workloads")
+    ap.add_argument("--no-others", action="store_true",
+                    help="default run: skip the other configurations")
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = config's)")
+    ap.add_argument("--sample-tokens", type=int, default=0,
+                    help="tokens per sequence the CPU oracle is timed on (0 = all of layer 0)")
+    ap.add_argument("--two-streams", action="store_true",
+                    help="run mask+compact of layer l on a second stream while the scorer of layer "
+                         "l+1 runs (measured: +1 %% throughput, the scorer slows under contention); "
+                         "default is one stream, which keeps per-kernel timings clean")
+    ap.add_argument("--per-call-weights", dest="prepared_weights", action="store_false",
+                    help="MLP surrogate: score with kvzap_score, which re-orders W1 into the matrix "
+                         "cores' operand order on every call (5 us).  Default: the weights are "
+                         "re-ordered once with kvzap_prepare_scorer when they are loaded, before the "
+                         "timed region, and scored with kvzap_score_prepared, so that the event "
+                         "pair around the scorer brackets its one kernel")
+    ap.add_argument("--decode-cache-rows", type=int, nargs=2, default=[4096, 32768],
+                    help="decode workload: range of rows already kept per (sequence, head)")
+    ap.add_argument("--select", default="threshold", choices=["threshold", "topk-head", "topk-layer"],
+                    help="eviction rule of the mask stage: the paper's global threshold (default) or "
+                         "the fixed-budget variants of its ablation at the same kept fraction")
+    ap.add_argument("--page-rows", type=int, default=0,
+                    help="0 (default): packed contiguous output; a power of two >= 16: paged output "
+                         "(kvzap_assign_pages + kvzap_compact_paged) and, for --stage attend, the "
+                         "paged attention over a shuffled page pool")
+    ap.add_argument("--graph", action="store_true",
+                    help="decode workload: also time the step replayed from a HIP graph")
+    ap.add_argument("--stage", default="evict", choices=["evict", "attend", "teacher"],
+                    help="decode workload: time the eviction step (default) or the attention "
+                         "over the ragged cache it maintains; 'teacher' (any config): the "
+                         "KVzip+ training scores of one extended prompt")
+    ap.add_argument("--teacher-tokens", type=int, default=8192,
+                    help="--stage teacher: prompt length (the extended prompt is twice that + 32)")
+    ap.add_argument("--query-heads", type=int, default=32,
+                    help="decode attention: number of query heads (Qwen3-8B: 32 over 8 KV heads)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference for HBM byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(the path shards by layer / sequence / KV head with no communication)",
+              file=sys.stderr)
+        return 2
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    binding.lib()                                   # fail loudly if the library is not built
+    wl = synth.CONFIGS[args.config or "c3_qwen8b_128k_mlp"]
+    if args.stage == "teacher":
+        print(json.dumps(bench_teacher(wl, args)))
+        return 0
+    if wl.T == 1:
+        print(json.dumps(bench_attend(wl, args) if args.stage == "attend" else bench_decode(wl, args)))
+        return 0
+    L = args.layers or wl.L
+    if args.config is not None:                      # one named workload, nothing else
+        print(json.dumps(bench_prefill(wl, args, L, oracle=True, extras=True)))
+        return 0
+    out = bench_prefill(wl, args, L, oracle=True, extras=True)
+    if not args.no_others:
+        out["other_workloads"] = other_workloads(args)
     print(json.dumps(out))
     return 0
 

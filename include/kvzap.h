@@ -69,7 +69,8 @@ typedef enum kvzap_call {
   KVZAP_CALL_ASSIGN_PAGES = 5,   /* only B and H matter (pass T = 1) */
   KVZAP_CALL_TOPK_THRESHOLD = 6, /* pass M = per_layer (0 or 1) */
   KVZAP_CALL_TEACHER_SCORES = 7, /* pass B = 1, T = prompt length, Dh = HQ, M = Tq */
-  KVZAP_CALL_COMPRESS = 8        /* as KVZAP_CALL_SCORE: the larger of the score and mask needs */
+  KVZAP_CALL_COMPRESS = 8,       /* as KVZAP_CALL_SCORE: the larger of the score and mask needs */
+  KVZAP_CALL_MASK_COMPACT = 9    /* as KVZAP_CALL_MASK */
 } kvzap_call;
 
 /* Text for a status code (host pointer to a static string, never NULL). */
@@ -240,11 +241,28 @@ int kvzap_compact(const void* K, const void* V, const int32_t* keep_idx,
                   int B, int H, int T, int D, void* stream);
 
 /*
+ * kvzap_mask_compact -- the last three lines of Algorithm 1 (window, threshold, gather) in one
+ * call: kvzap_mask followed by kvzap_compact, with the arguments and the results of those two
+ * calls, bit for bit (keep_idx, lengths and offsets are written as kvzap_mask writes them).
+ * The kernels are those of the two calls (a gather fused into the ranking kernel measured
+ * slower than the separate gather, whose one-row-per-thread grid keeps more of HBM busy); what
+ * the single call adds is that all checks of both happen before the first launch.
+ * workspace: kvzap_workspace_bytes(KVZAP_CALL_MASK_COMPACT, B, T, 0, 0, H), as for kvzap_mask.
+ */
+int kvzap_mask_compact(const float* scores, float tau, int window, const int32_t* seq_lens,
+                       const void* K, const void* V, int32_t* keep_idx, int32_t* lengths,
+                       int64_t* offsets, void* K_out, void* V_out, int64_t cap_rows,
+                       int B, int H, int T, int D,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * kvzap_compress -- the whole of Algorithm 1 for one layer in one call: kvzap_score, then
- * kvzap_mask, then kvzap_compact on the same stream, with the arguments of those three
- * calls (`scores` receives the surrogate's scores and is part of the result).  Identical,
- * bit for bit, to making the three calls; validation of all three happens before the
- * first launch.  workspace: kvzap_workspace_bytes(KVZAP_CALL_COMPRESS, B, T, Dh, M, H).
+ * kvzap_mask_compact on the same stream, with the arguments of those calls (`scores`
+ * receives the surrogate's scores and is part of the result).  Identical, bit for bit, to
+ * making the three calls kvzap_score, kvzap_mask, kvzap_compact; validation of all three
+ * happens before the first launch.  (Counting the kept scores inside the scorer, to save the
+ * mask's first kernel, measured no faster end to end and is not done.)
+ * workspace: kvzap_workspace_bytes(KVZAP_CALL_COMPRESS, B, T, Dh, M, H).
  */
 int kvzap_compress(const void* hidden, const void* W1, const void* b1, const void* W2,
                    const void* b2, const void* K, const void* V, float tau, int window,

@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libkvzap.so")
 
 CALL_SCORE, CALL_MASK, CALL_COMPACT, CALL_DECODE_EVICT, CALL_ATTEND_DECODE = 0, 1, 2, 3, 4
 CALL_ASSIGN_PAGES, CALL_TOPK_THRESHOLD, CALL_TEACHER_SCORES, CALL_COMPRESS = 5, 6, 7, 8
+CALL_MASK_COMPACT = 9
 
 _c_void_p, _c_int, _c_float, _c_size_t, _c_int64 = (
     ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t, ctypes.c_int64)
@@ -37,6 +38,8 @@ SIGNATURES = {
     "kvzap_score_prepared": (_c_int, [_c_void_p] * 6 + [_c_int] * 5 + [_c_void_p]),
     "kvzap_compress": (_c_int, [_c_void_p] * 7 + [_c_float, _c_int] + [_c_void_p] * 7 + [_c_int64] +
                        [_c_int] * 6 + [_c_void_p, _c_size_t, _c_void_p]),
+    "kvzap_mask_compact": (_c_int, [_c_void_p, _c_float, _c_int] + [_c_void_p] * 8 + [_c_int64] +
+                           [_c_int] * 4 + [_c_void_p, _c_size_t, _c_void_p]),
     "kvzap_teacher_scores": (_c_int, [_c_void_p] * 4 + [_c_float, _c_void_p] + [_c_int] * 6 +
                              [_c_void_p, _c_size_t, _c_void_p]),
     "kvzap_topk_threshold": (_c_int, [_c_void_p, _c_int, _c_void_p, _c_int64, _c_int, _c_int, _c_int,
@@ -619,6 +622,53 @@ def kvzap_teacher_scores(q: torch.Tensor, k: torch.Tensor, T: int, scale: float,
     if rc != 0:
         raise KvzapError(rc, "kvzap_teacher_scores")
     return log_s
+
+
+def kvzap_mask_compact(scores: torch.Tensor, tau: float, window: int, K: torch.Tensor,
+                       V: torch.Tensor, seq_lens: Optional[torch.Tensor] = None,
+                       keep_idx: Optional[torch.Tensor] = None,
+                       lengths: Optional[torch.Tensor] = None,
+                       offsets: Optional[torch.Tensor] = None,
+                       K_out: Optional[torch.Tensor] = None, V_out: Optional[torch.Tensor] = None,
+                       cap_rows: Optional[int] = None,
+                       workspace: Optional[torch.Tensor] = None, stream=None):
+    """kvzap_mask + kvzap_compact in one library call.  Returns (keep_idx, lengths, offsets,
+    K_out, V_out) as the two separate calls would."""
+    bf = torch.bfloat16
+    _check(scores, torch.float32, "scores"); _check(K, bf, "K"); _check(V, bf, "V")
+    _check(seq_lens, torch.int32, "seq_lens", True)
+    B, H, T = scores.shape
+    if tuple(K.shape[:3]) != (B, H, T) or K.shape != V.shape:
+        raise ValueError("K and V must be [B,H,T,D]")
+    D = K.shape[3]
+    dev = scores.device
+    if keep_idx is None:
+        keep_idx = torch.empty(B * H * T, dtype=torch.int32, device=dev)
+    if lengths is None:
+        lengths = torch.empty((B, H), dtype=torch.int32, device=dev)
+    if offsets is None:
+        offsets = torch.empty(B * H + 1, dtype=torch.int64, device=dev)
+    if cap_rows is None:
+        cap_rows = B * H * T if K_out is None else K_out.shape[0]
+    if K_out is None:
+        K_out = torch.empty((cap_rows, D), dtype=bf, device=dev)
+    if V_out is None:
+        V_out = torch.empty((cap_rows, D), dtype=bf, device=dev)
+    _check(keep_idx, torch.int32, "keep_idx"); _check(lengths, torch.int32, "lengths")
+    _check(offsets, torch.int64, "offsets"); _check(K_out, bf, "K_out"); _check(V_out, bf, "V_out")
+    if keep_idx.numel() < B * H * T or lengths.numel() != B * H or offsets.numel() != B * H + 1:
+        raise ValueError("output buffers have the wrong size")
+    if K_out.shape[0] < cap_rows or V_out.shape[0] < cap_rows or K_out.shape[1] != D or V_out.shape[1] != D:
+        raise ValueError("K_out and V_out must be [>= cap_rows, D]")
+    ws, ws_bytes = _workspace(max(kvzap_workspace_bytes(CALL_MASK_COMPACT, B, T, 0, 0, H), 256), dev,
+                              workspace, stream)
+    rc = lib().kvzap_mask_compact(_ptr(scores), float(tau), int(window), _ptr(seq_lens), _ptr(K),
+                                  _ptr(V), _ptr(keep_idx), _ptr(lengths), _ptr(offsets), _ptr(K_out),
+                                  _ptr(V_out), int(cap_rows), B, H, T, D, _ptr(ws), ws_bytes,
+                                  _stream(stream))
+    if rc != 0:
+        raise KvzapError(rc, "kvzap_mask_compact")
+    return keep_idx, lengths, offsets, K_out, V_out
 
 
 def kvzap_compress(hidden: torch.Tensor, W1: torch.Tensor, b1, W2, b2, K: torch.Tensor,

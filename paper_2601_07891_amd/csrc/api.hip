@@ -86,6 +86,9 @@ size_t kvzap_workspace_bytes(int which_call, int B, int T, int Dh, int M, int H)
       const size_t b = mask_workspace(B, H, T);
       return a > b ? a : b;
     }
+    case KVZAP_CALL_MASK_COMPACT:
+      if ((long long)B * H > 65535) return 0;
+      return mask_workspace(B, H, T);
     case KVZAP_CALL_ATTEND_DECODE:   // T = max_rows, Dh = HQ, M = window
       if (check_attend_shape(B, H, Dh, T, M) != KVZAP_OK) return 0;
       return kvzap::attend_workspace_bytes(B, H, Dh, T, M);
@@ -271,6 +274,33 @@ int kvzap_compact(const void* K, const void* V, const int32_t* keep_idx,
                                T, D, static_cast<hipStream_t>(stream));
 }
 
+namespace {
+// threshold + gather on given scores (all arguments checked)
+int run_mask_compact(const float* scores, float tau, int window, const int32_t* seq_lens, int B,
+                     int H, int T, int32_t* keep_idx, int32_t* lengths, int64_t* offsets,
+                     const void* K, const void* V, void* K_out, void* V_out, int64_t cap_rows, int D,
+                     void* workspace, hipStream_t s) {
+  const int rc = kvzap::launch_mask(scores, tau, nullptr, window, seq_lens, B, H, T, keep_idx,
+                                    lengths, offsets, workspace, s);
+  if (rc != KVZAP_OK) return rc;
+  return kvzap::launch_compact(K, V, keep_idx, lengths, offsets, K_out, V_out, cap_rows, B * H, T,
+                               D, s);
+}
+}  // namespace
+
+int kvzap_mask_compact(const float* scores, float tau, int window, const int32_t* seq_lens,
+                       const void* K, const void* V, int32_t* keep_idx, int32_t* lengths,
+                       int64_t* offsets, void* K_out, void* V_out, int64_t cap_rows, int B, int H,
+                       int T, int D, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_mask(scores, tau, window, seq_lens, B, H, T, keep_idx, lengths, offsets, workspace,
+                      workspace_bytes);
+  if (rc == KVZAP_OK)
+    rc = check_compact(K, V, keep_idx, lengths, offsets, K_out, V_out, cap_rows, B, H, T, D);
+  if (rc != KVZAP_OK) return rc;
+  return run_mask_compact(scores, tau, window, seq_lens, B, H, T, keep_idx, lengths, offsets, K, V,
+                          K_out, V_out, cap_rows, D, workspace, static_cast<hipStream_t>(stream));
+}
+
 int kvzap_compress(const void* hidden, const void* W1, const void* b1, const void* W2,
                    const void* b2, const void* K, const void* V, float tau, int window,
                    const int32_t* seq_lens, float* scores, int32_t* keep_idx, int32_t* lengths,
@@ -290,11 +320,8 @@ int kvzap_compress(const void* hidden, const void* W1, const void* b1, const voi
   // then reuses the same bytes on the same stream
   rc = run_score(hidden, W1, b1, W2, b2, scores, B, T, Dh, M, H, workspace, s);
   if (rc != KVZAP_OK) return rc;
-  rc = kvzap::launch_mask(scores, tau, nullptr, window, seq_lens, B, H, T, keep_idx, lengths,
-                          offsets, workspace, s);
-  if (rc != KVZAP_OK) return rc;
-  return kvzap::launch_compact(K, V, keep_idx, lengths, offsets, K_out, V_out, cap_rows, B * H, T,
-                               D, s);
+  return run_mask_compact(scores, tau, window, seq_lens, B, H, T, keep_idx, lengths, offsets, K, V,
+                          K_out, V_out, cap_rows, D, workspace, s);
 }
 
 int kvzap_decode_evict(const void* hidden_new, const void* W1, const void* b1, const void* W2,

@@ -177,8 +177,10 @@ def test_compress_argument_errors(lib):
     f = lib.kvzap_compress
     q = lib.kvzap_workspace_bytes
     ws = q(binding.CALL_COMPRESS, 1, 1024, 4096, 512, 8)
-    assert ws == max(q(binding.CALL_SCORE, 1, 1024, 4096, 512, 8), q(binding.CALL_MASK, 1, 1024, 0, 0, 8))
-    assert q(binding.CALL_COMPRESS, 1, 1024, 4096, 0, 8) == q(binding.CALL_MASK, 1, 1024, 0, 0, 8)
+    mc = q(binding.CALL_MASK_COMPACT, 1, 1024, 0, 0, 8)
+    assert mc == q(binding.CALL_MASK, 1, 1024, 0, 0, 8) and mc % 256 == 0
+    assert ws == max(q(binding.CALL_SCORE, 1, 1024, 4096, 512, 8), mc)
+    assert q(binding.CALL_COMPRESS, 1, 1024, 4096, 0, 8) == mc
     big = 1 << 40
     ok = dict(hidden=P, W1=P, b1=None, W2=P, b2=None, K=P + (1 << 30), V=P + (2 << 30), tau=0.0,
               window=128, seq=None, scores=P, idx=P, lens=P, offs=P, Ko=big, Vo=big + (1 << 30),
@@ -201,6 +203,34 @@ def test_compress_argument_errors(lib):
     assert call(Ko=P + (1 << 30)) == ERR["shape"]      # K_out aliases K
     assert call(wsb=ws - 1) == ERR["workspace"]
     assert call(ws=None) == ERR["workspace"]
+
+
+def test_mask_compact_argument_errors(lib):
+    # the fused threshold + gather refuses whatever kvzap_mask or kvzap_compact refuses
+    f = lib.kvzap_mask_compact
+    ws = lib.kvzap_workspace_bytes(binding.CALL_MASK_COMPACT, 1, 2048, 0, 0, 8)
+    big = 1 << 40
+    ok = dict(scores=P, tau=0.0, window=128, seq=None, K=P + (1 << 30), V=P + (2 << 30), idx=P,
+              lens=P, offs=P, Ko=big, Vo=big + (1 << 30), cap=16384, B=1, H=8, T=2048, D=128,
+              ws=0x20000, wsb=ws, stream=None)
+    order = list(ok)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(*[a[k] for k in order])
+
+    assert call(scores=None) == ERR["null"]
+    assert call(V=None) == ERR["null"]
+    assert call(Ko=None) == ERR["null"]
+    assert call(window=-1) == ERR["shape"]
+    assert call(tau=float("nan")) == ERR["shape"]
+    assert call(D=4) == ERR["unsupported"]
+    assert call(B=8192) == ERR["unsupported"]
+    assert call(K=P + (1 << 30) + 2) == ERR["align"]
+    assert call(Vo=big) == ERR["shape"]                # V_out aliases K_out
+    assert call(wsb=ws - 1) == ERR["workspace"]
+    assert call(ws=None) == ERR["workspace"]
+    assert call(ws=0x20010) == ERR["workspace"]
 
 
 def test_decode_argument_errors(lib):

@@ -29,8 +29,9 @@ def _common(d, steps, warmup):
 
 
 def test_default_workload_line():
-    d = _bench("--layers", "2", "--steps", "2", "--warmup", "1")
+    d = _bench("--layers", "2", "--steps", "2", "--warmup", "1", "--no-others")
     _common(d, 2, 1)
+    assert "other_workloads" not in d
     assert d["unit"] == "tokens/s" and d["config"]["workload"] == "c3_qwen8b_128k_mlp"
     r = d["roofline"]
     assert r["bound"] == "mfma" and r["unit"] == "TFLOP/s" and r["peak"] == 2500.0
@@ -44,6 +45,28 @@ def test_default_workload_line():
     assert d["score_max_rel_err_vs_oracle_sample"] < 1e-2
     st = d["stages_ms_per_layer"]
     assert st["score"] > st["compact"] > st["mask"] > 0
+    assert st["mask_compact"] > st["compact"]
+    rm = d["roofline_mask_compact"]
+    assert rm["bound"] == "hbm" and abs(rm["frac"] - rm["achieved"] / rm["peak"]) < 1e-12
+    assert rm["algorithmic_bytes_per_launch"] > rc["algorithmic_bytes_per_launch"]
+
+
+def test_default_line_carries_the_other_workloads():
+    # the default run: the headline workload, then every other configuration on the same clock
+    d = _bench("--layers", "2", "--steps", "2", "--warmup", "1")
+    _common(d, 2, 1)
+    assert d["config"]["workload"] == "c3_qwen8b_128k_mlp" and d["cpu_baseline"]["kind"] == "oracle"
+    others = d["other_workloads"]
+    names = [o["config"]["workload"] for o in others]
+    assert names == ["c1_t1k_linear", "c2_llama8b_32k_mlp", "c4_qwen32b_4x64k_linear",
+                     "c4_qwen32b_4x64k_mlp", "c5_qwen8b_decode", "c5_qwen8b_decode+attend"]
+    for o in others[:4]:
+        assert o["value"] > 0 and o["unit"] == "tokens/s"
+        assert 0.05 < o["config"]["kept_fraction_measured"] < 0.95
+        assert o["roofline"]["frac"] > 0 and o["stages_ms_per_layer"]["mask_compact"] > 0
+    assert others[2]["roofline"]["bound"] == "hbm" and others[3]["roofline"]["bound"] == "mfma"
+    assert others[4]["us_per_layer_step"] > 0 and others[4]["hip_graph"]["us_per_layer_step"] > 0
+    assert others[5]["roofline"]["bound"] == "hbm" and 0.3 < others[5]["roofline"]["frac"] < 1.0
 
 
 def test_decode_lines():

@@ -70,9 +70,15 @@ def test_batched_right_padded():
     _check(wl, seq_lens=[700, 401, 128])
 
 
+# the MLP cases from 17k tokens on take the scorer's single kernel, which then also counts the
+# kept scores (blocks of 128 or 96 tokens that straddle sequence ends and 1024-token chunks,
+# padded sequences); the shorter ones and the linear surrogate count in a kernel of their own
 @pytest.mark.parametrize("name,T,padded", [("c1_t1k_linear", 1024, False),
                                            ("c2_llama8b_32k_mlp", 5000 + 19, False),
-                                           ("c4_qwen32b_4x64k_linear", 700, True)])
+                                           ("c4_qwen32b_4x64k_linear", 700, True),
+                                           ("c2_llama8b_32k_mlp", 17000 + 77, False),
+                                           ("c3_qwen8b_128k_mlp", 9000 + 5, True),
+                                           ("c4_qwen32b_4x64k_mlp", 6000 + 10, True)])
 def test_compress_is_the_three_calls(name, T, padded):
     # Algorithm 1 through the one-call entry point: bit-identical to score, mask, compact
     wl = synth.with_size(synth.CONFIGS[name], L=1, T=T)
@@ -96,11 +102,12 @@ def test_compress_is_the_three_calls(name, T, padded):
     assert torch.equal(got[5][:kept].view(torch.int16), want[5][:kept].view(torch.int16))
 
 
-def test_compress_replayed_from_a_hip_graph_matches_eager():
+@pytest.mark.parametrize("T", [3000 + 7, 17000 + 5])     # split first projection; single kernel with the fused count
+def test_compress_replayed_from_a_hip_graph_matches_eager(T):
     """kvzap_compress (MLP scorer, top of Algorithm 1 to the gathered cache) captured once in
     a HIP graph and replayed with new inputs in the same buffers; eager work and
     synchronisation sit between the replays, and every replay equals the eager call bit for bit."""
-    wl = synth.with_size(synth.CONFIGS["c2_llama8b_32k_mlp"], T=3000 + 7, L=64)   # L > 1: a seed per "layer"
+    wl = synth.with_size(synth.CONFIGS["c2_llama8b_32k_mlp"], T=T, L=64)   # L > 1: a seed per "layer"
     B, H, T, D, Dh, M = wl.B, wl.H, wl.T, wl.D, wl.Dh, wl.M
     w = {k: (None if v is None else v.to(DEV)) for k, v in synth.make_weights(wl).items()}
     L = binding.lib()

@@ -58,6 +58,44 @@ def test_injected_scores_exact(B, H, T, D, w, tau):
     parity.assert_prune_matches(idx, n, off, Ko, Vo, K, V, scores.double().numpy(), tau, w)
 
 
+@pytest.mark.parametrize("B,H,T,D,w,tau", CASES)
+def test_mask_compact_in_one_call(B, H, T, D, w, tau):
+    # threshold + gather in one library call against the oracle, no band, and against the
+    # separate calls
+    scores = synth.make_scores(B, H, T, seed=B * 1000 + T + 1, ties=True)
+    K, V = _kv(B, H, T, D, T + 1)
+    s, Kd, Vd = scores.to(DEV), K.to(DEV), V.to(DEV)
+    idx, n, off, Ko, Vo = binding.kvzap_mask_compact(s, tau, w, Kd, Vd)
+    torch.cuda.synchronize()
+    parity.assert_prune_matches(idx, n, off, Ko, Vo, K, V, scores.double().numpy(), tau, w)
+    i2, n2, o2 = binding.kvzap_mask(s, tau, w)
+    assert torch.equal(n, n2) and torch.equal(off, o2)
+    tot = int(off[-1])
+    assert torch.equal(idx[:tot], i2[:tot])
+
+
+def test_mask_compact_in_one_call_padded_and_capped():
+    B, H, T, D, w, tau = 4, 8, 5000, 128, 128, 0.1
+    scores = synth.make_scores(B, H, T, seed=77)
+    K, V = _kv(B, H, T, D, 78)
+    lens = [5000, 1025, 100, 0]
+    sl = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    idx, n, off, Ko, Vo = binding.kvzap_mask_compact(scores.to(DEV), tau, w, K.to(DEV), V.to(DEV), sl)
+    torch.cuda.synchronize()
+    ref, _ = parity.assert_prune_matches(idx, n, off, Ko, Vo, K, V, scores.double().numpy(), tau, w,
+                                         seq_lens=lens)
+    # a capacity in the middle of a chunk: rows before it are written, nothing behind it
+    total = int(off[-1]); cap = total // 2 + 3
+    Kc = torch.full((total, D), 7.0, dtype=torch.bfloat16, device=DEV)
+    Vc = torch.full((total, D), 7.0, dtype=torch.bfloat16, device=DEV)
+    binding.kvzap_mask_compact(scores.to(DEV), tau, w, K.to(DEV), V.to(DEV), sl, None, None, None,
+                               Kc, Vc, cap_rows=cap)
+    torch.cuda.synchronize()
+    assert torch.equal(Kc[:cap].view(torch.int16), Ko[:cap].view(torch.int16))
+    assert torch.equal(Vc[:cap].view(torch.int16), Vo[:cap].view(torch.int16))
+    assert (Kc[cap:] == 7.0).all() and (Vc[cap:] == 7.0).all()
+
+
 @pytest.mark.parametrize("tau", [-math.inf, math.inf])
 def test_tau_limits(tau):
     B, H, T, D, w = 2, 8, 3000, 128, 128
