@@ -253,10 +253,12 @@ class DecodeOracle:
 
     One step for sequence b at position p (reading of the caption):
       1. s = surrogate(h_new)                       (H scores)
-      2. q = p - w is the position that leaves the window once p is appended;
-         if q >= 0 and not (score[q] >= tau) the pair at q is removed from the
-         head (for w = 0 this is the new token itself: q = p);
-      3. the new pair is appended at position p and its score remembered.
+      2. the new pair is appended at position p and its score remembered;
+      3. q = p - w is the position that has left the window now that p is in
+         it; if q >= 0 and not (score[q] >= tau) the pair at q is removed from
+         the head (for w = 0 this is the token just appended: q = p).
+    Appending first and evicting second is the order step() takes; evicting
+    first gives the same state for w > 0 (q != p), and is undefined for w = 0.
     After the step the kept set equals Algorithm 1 applied to the p+1 scores.
     """
 

@@ -53,6 +53,24 @@ def test_several_tiles_splits_and_groups():
     _check(H=1, G=8, T=260, instr=40, Tq=513, seed=3)
 
 
+def test_the_benchmark_shape():
+    # bench.py's --stage teacher shape: an 8192-token prompt, 32 instruction tokens, the prompt
+    # repeated, 8 KV heads x 4 query heads -- query splits and the longest-block-first order in
+    # play.  The oracle recomputes the first and the last KV head (a few seconds each).
+    H, G, T, instr = 8, 4, 8192, 32
+    q, k, vn, hn = _inputs(H, G, T, instr, T, seed=11)
+    scale = D ** -0.5
+    got = binding.kvzap_teacher_scores(q.to(DEV), k.to(DEV), T, scale, vn.to(DEV), hn.to(DEV))
+    torch.cuda.synchronize()
+    got = got.double().cpu().numpy()
+    assert np.isfinite(got).all()
+    for h in (0, H - 1):
+        ref = O.teacher_log_scores(synth.f64(q[h * G:(h + 1) * G]), synth.f64(k[h:h + 1]), scale, T,
+                                   vn[h:h + 1].double().numpy(), hn.double().numpy())
+        err = np.abs(got[h:h + 1] - ref)
+        assert (err <= 2e-3 + 1e-4 * np.abs(ref)).all(), (h, err.max())
+
+
 def test_kvzip_without_norms_is_the_unit_norm_case():
     ref = _check(H=2, G=2, T=300, instr=10, Tq=300, seed=4, norms=False)
     assert (ref <= 1e-9).all()                                   # attention weights are <= 1
