@@ -21,7 +21,9 @@ Parity pins (tests/test_oracle_*.py): tau=-inf identity, tau=+inf window only,
 nested kept sets in tau, brute-force mask enumeration at tiny T, hand loops vs
 the library GEMM / erf / nonzero, exact-integer inputs, GELU identities and the
 second moment E[GELU(z)^2], the closed forms and printed percentages of App. B,
-decode == prefill on the grown prefix, conservation of lengths/offsets.
+decode == prefill on the grown prefix, conservation of lengths/offsets; the
+row normalisation against a hand loop, its unit-mean-square, scale-invariance
+and identity cases (tests/test_oracle_rmsnorm.py).
 Absolute score values for real prompts are "parity unpinned": the paper prints
 none and its trained weights are not available here.
 """
@@ -88,6 +90,44 @@ def score_mlp(hidden: np.ndarray, W1: np.ndarray, b1: Optional[np.ndarray],
     if b2 is not None:
         S = S + np.asarray(b2, dtype=np.float64)[None, :]
     return np.ascontiguousarray(S.T)
+
+
+# --------------------------------------------------------------------------
+# surrogate on the un-normalised residual stream (Sec. 3: the surrogate reads the
+# layer's *input hidden states*; Sec. 5: what an engine has to fuse)
+# --------------------------------------------------------------------------
+def rmsnorm(x: np.ndarray, gain: np.ndarray, eps: float) -> np.ndarray:
+    """Root-mean-square layer normalisation of every row (the input norm of a
+    decoder layer in the models of App. B):
+
+        y[t, k] = x[t, k] / sqrt(mean_k x[t, k]^2 + eps) * gain[k]
+
+    x float64 [T, D_h], gain float64 [D_h].  Reading: the paper does not say
+    whether its "input hidden states" are taken before or after this norm; the
+    fused entry point serves a caller that holds the residual stream and wants
+    the surrogate applied to the normalised states, as the layer's own
+    projections are.
+    """
+    x = np.asarray(x, dtype=np.float64)
+    gain = np.asarray(gain, dtype=np.float64)
+    ms = np.mean(x * x, axis=-1, keepdims=True)
+    return x / np.sqrt(ms + float(eps)) * gain
+
+
+def rstd(x: np.ndarray, eps: float) -> np.ndarray:
+    """1 / sqrt(mean_k x[t, k]^2 + eps) per row: what a consumer needs to apply
+    the norm itself (float64 [T])."""
+    x = np.asarray(x, dtype=np.float64)
+    return 1.0 / np.sqrt(np.mean(x * x, axis=-1) + float(eps))
+
+
+def score_mlp_rmsnorm(x: np.ndarray, gain: np.ndarray, eps: float, W1: np.ndarray,
+                      b1: Optional[np.ndarray], W2: np.ndarray,
+                      b2: Optional[np.ndarray]) -> np.ndarray:
+    """KVzap-MLP applied to rmsnorm(x): scores [H, T].  No rounding of the
+    normalised states in between (a bf16 model would round them; the GPU path
+    does not materialise them for the surrogate at all)."""
+    return score_mlp(rmsnorm(x, gain, eps), W1, b1, W2, b2)
 
 
 # --------------------------------------------------------------------------
