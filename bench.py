@@ -384,6 +384,92 @@ def bench_teacher(wl, args) -> dict:
                          "max_abs_diff_vs_gpu": err}})
 
 
+def bench_fused_norm(wl, args) -> dict:
+    """The MLP surrogate fused into the layer's input RMSNorm (--stage fused-norm, a prefill
+    workload): kvzap_score_rmsnorm reading the residual stream, with and without the normalised
+    states as an output, next to kvzap_score_prepared on states normalised beforehand -- the
+    scorer's cost when the norm is a kernel of its own, whose output it has to read again."""
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    B, T, H, Dh, M = wl.B, wl.T, wl.H, wl.Dh, wl.M
+    L = args.layers or 6
+    eps = 1e-6
+    layers = []
+    for l in range(L):
+        w = synth.make_weights(wl, l, dev)
+        x = synth.make_hidden(wl, l, dev)                 # stands for the residual stream
+        g = torch.Generator(device=dev).manual_seed(900 + l)
+        gain = (1.0 + 0.3 * torch.randn((Dh,), generator=g, device=dev)).bfloat16()
+        layers.append(dict(w=w, x=x, gain=gain, normed=torch.empty_like(x),
+                           prep=binding.kvzap_prepare_scorer(w["W1"]),
+                           prep_n=binding.kvzap_prepare_scorer_rmsnorm(w["W1"], gain),
+                           scores=torch.empty((B, H, T), dtype=torch.float32, device=dev),
+                           rstd=torch.empty((B, T), dtype=torch.float32, device=dev)))
+    torch.cuda.synchronize()
+
+    def plain(ly):      # the norm ran as its own kernel before: its output is read here
+        w = ly["w"]
+        binding.kvzap_score_prepared(ly["normed"], ly["prep"], w["b1"], w["W2"], w["b2"], ly["scores"])
+
+    def fused(ly):
+        w = ly["w"]
+        binding.kvzap_score_rmsnorm(ly["x"], ly["prep_n"], ly["gain"], eps, w["b1"], w["W2"], w["b2"],
+                                    False, ly["scores"], ly["rstd"])
+
+    def fused_normed(ly):
+        w = ly["w"]
+        binding.kvzap_score_rmsnorm(ly["x"], ly["prep_n"], ly["gain"], eps, w["b1"], w["W2"], w["b2"],
+                                    True, ly["scores"], ly["rstd"], ly["normed"])
+
+    def torch_norm(ly):  # context only: the framework's own RMSNorm kernel, bf16 in and out
+        torch.nn.functional.rms_norm(ly["x"], (Dh,), ly["gain"], eps)
+
+    def timed(fn):
+        for ly in layers:
+            fn(ly)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(args.steps):
+            for ly in layers:
+                fn(ly)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / (args.steps * L), (time.perf_counter() - t0) * 1e3 / args.steps
+
+    for ly in layers:
+        fused_normed(ly)                                  # fills `normed` for the plain variant
+    ms_plain, _ = timed(plain)
+    ms_fused, ms_step = timed(fused)
+    ms_fused_normed, _ = timed(fused_normed)
+    ms_torch, _ = timed(torch_norm)
+    row = B * T * Dh * 2                                  # bytes of one [B,T,Dh] bf16 tensor
+    flops = (2 * Dh * M + 2 * M * H) * B * T
+    return {
+        "metric": "fused-norm scorer tokens/sec per layer (scores + row scales from the residual stream)",
+        "value": L * B * T / (ms_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": 1, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name + "+fused-norm", "layers": L, "batch": B, "seq_len": T,
+                   "d_model": Dh, "mlp_width": M, "kv_heads": H, "eps": eps},
+        "ms_per_layer": {"kvzap_score_prepared on normalised states": ms_plain,
+                         "kvzap_score_rmsnorm (scores + rstd)": ms_fused,
+                         "kvzap_score_rmsnorm (scores + rstd + normalised states)": ms_fused_normed,
+                         "context: torch rms_norm kernel alone": ms_torch},
+        "hbm_bytes_per_layer": {
+            "separate norm, then scorer": {"norm": 2 * row, "scorer": row, "total": 3 * row},
+            "fused, consumer applies rstd itself": {"scorer": row, "total": row,
+                                                    "saved_vs_separate_scorer_read": row},
+            "fused, normalised states written": {"scorer": 3 * row, "total": 3 * row}},
+        "roofline": {"kernel": "score_mlp_frag_kernel (normalising form)", "bound": "mfma",
+                     "achieved": flops / (ms_fused * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": flops / (ms_fused * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                     "traffic": None, "avg_launch_ms": ms_fused,
+                     "algorithmic_flops_per_launch": flops},
+        "cpu_baseline": None}
+
+
 def bench_prefill(wl, args, L, oracle: bool, extras: bool) -> dict:
     """Prune step (score, mask, compact) over L resident layers of a prefill workload.
     oracle: tau and the cpu_baseline come from the float64 oracle on layer 0 (the headline
@@ -685,6 +771,12 @@ def other_workloads(args) -> list:
     res.append(brief(bench_attend(wl5, a), ("metric", "value", "unit", "steps", "warmup", "ms_per_step",
                                             "config", "ms_per_call", "roofline")))
     gc.collect(); torch.cuda.empty_cache()
+    a = copy.copy(args)
+    a.steps, a.layers = 5, 6
+    res.append(brief(bench_fused_norm(synth.CONFIGS["c3_qwen8b_128k_mlp"], a),
+                     ("metric", "value", "unit", "steps", "ms_per_step", "config", "ms_per_layer",
+                      "hbm_bytes_per_layer", "roofline")))
+    gc.collect(); torch.cuda.empty_cache()
     return res
 
 
@@ -722,10 +814,12 @@ def main() -> int:
                          "paged attention over a shuffled page pool")
     ap.add_argument("--graph", action="store_true",
                     help="decode workload: also time the step replayed from a HIP graph")
-    ap.add_argument("--stage", default="evict", choices=["evict", "attend", "teacher"],
+    ap.add_argument("--stage", default="evict", choices=["evict", "attend", "teacher", "fused-norm"],
                     help="decode workload: time the eviction step (default) or the attention "
                          "over the ragged cache it maintains; 'teacher' (any config): the "
-                         "KVzip+ training scores of one extended prompt")
+                         "KVzip+ training scores of one extended prompt; 'fused-norm' (a prefill "
+                         "config with an MLP surrogate): the surrogate fused into the layer's "
+                         "input RMSNorm")
     ap.add_argument("--teacher-tokens", type=int, default=8192,
                     help="--stage teacher: prompt length (the extended prompt is twice that + 32)")
     ap.add_argument("--query-heads", type=int, default=32,
@@ -745,6 +839,13 @@ def main() -> int:
     wl = synth.CONFIGS[args.config or "c3_qwen8b_128k_mlp"]
     if args.stage == "teacher":
         print(json.dumps(bench_teacher(wl, args)))
+        return 0
+    if args.stage == "fused-norm":
+        if wl.T == 1 or not wl.M:
+            print("bench.py: --stage fused-norm needs a prefill workload with an MLP surrogate",
+                  file=sys.stderr)
+            return 2
+        print(json.dumps(bench_fused_norm(wl, args)))
         return 0
     if wl.T == 1:
         print(json.dumps(bench_attend(wl, args) if args.stage == "attend" else bench_decode(wl, args)))

@@ -127,6 +127,49 @@ int kvzap_score(const void* hidden, const void* W1, const void* b1,
                 void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * kvzap_prepare_scorer_rmsnorm / kvzap_score_rmsnorm -- the MLP surrogate fused into the
+ * layer's input normalisation (Sec. 3: the surrogate is applied to the layer's input hidden
+ * states; Sec. 5: what an inference engine has to fuse).  The caller holds the un-normalised
+ * residual stream x; the layer's input RMSNorm
+ *
+ *     hidden[b,t,k] = x[b,t,k] * rstd[b,t] * gain[k],   rstd = 1 / sqrt(mean_k x[b,t,k]^2 + eps)
+ *
+ * and kvzap_score on `hidden` become one kernel that reads x once: the gain is folded into
+ * the prepared copy of W1 (W1[m,k] * gain[k], rounded to bf16, in the matrix cores' operand
+ * order), the sum of squares of every token is accumulated beside the first projection, and
+ * rstd is applied to the accumulators before b1 and GELU:
+ *
+ *     z[m] = rstd * sum_k x[k] * (W1[m,k] * gain[k]) + b1[m]
+ *
+ *   x            bf16 [B, T, Dh]   the residual stream (layer input before its norm)
+ *   gain         bf16 [Dh]
+ *   eps          >= 0
+ *   W1_prepared  from kvzap_prepare_scorer_rmsnorm(W1 bf16 [M, Dh], gain): device, 256-byte
+ *                aligned, at least M*Dh*2 bytes rounded up to 256, not overlapping W1
+ *   b1, W2, b2   as kvzap_score (MLP form)
+ *   scores       fp32 [B, H, T], fully overwritten
+ *   rstd         fp32 [B, T], fully overwritten: all that a consumer which folds the gain into
+ *                its own weights (as done here) needs in order to apply the norm in its epilogue
+ *   normed       bf16 [B, T, Dh] or NULL.  If given, it receives x * rstd * gain rounded to bf16
+ *                -- the states the layer's projections read.  A token's rstd is known only when
+ *                its whole row has passed, so each thread block then goes over its 128 (96) rows
+ *                a second time: x is read twice and `normed` written once, which is the traffic
+ *                of the separate norm and scorer, but inside one launch.  Must not overlap x.
+ *
+ * MLP surrogates only (M > 0; M == 0 returns KVZAP_ERR_UNSUPPORTED), Dh >= 256; always the
+ * single-kernel path (no workspace).  Arithmetic as kvzap_score's single-kernel path; the sum
+ * of squares is accumulated in fp32 from bf16 pairs.  Scores equal those of kvzap_score on a
+ * separately normalised input up to the bf16 rounding that pipeline applies to `hidden` and
+ * this one to W1 * gain: both are within the score tolerance of the un-rounded definition.
+ */
+int kvzap_prepare_scorer_rmsnorm(const void* W1, const void* gain, int Dh, int M,
+                                 void* W1_prepared, size_t prepared_bytes, void* stream);
+int kvzap_score_rmsnorm(const void* x, const void* W1_prepared, const void* gain, float eps,
+                        const void* b1, const void* W2, const void* b2,
+                        float* scores, float* rstd, void* normed,
+                        int B, int T, int Dh, int M, int H, void* stream);
+
+/*
  * kvzap_mask -- threshold plus sliding window (Sec. 3.3; Algorithm 1).
  *
  *   keep[b,h,t] = t < T_b  and  ( t >= T_b - window  or  scores[b,h,t] >= tau )

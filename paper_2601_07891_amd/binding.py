@@ -36,6 +36,10 @@ SIGNATURES = {
                                    _c_void_p, _c_void_p, _c_void_p, _c_void_p]),
     "kvzap_prepare_scorer": (_c_int, [_c_void_p, _c_int, _c_int, _c_void_p, _c_size_t, _c_void_p]),
     "kvzap_score_prepared": (_c_int, [_c_void_p] * 6 + [_c_int] * 5 + [_c_void_p]),
+    "kvzap_prepare_scorer_rmsnorm": (_c_int, [_c_void_p, _c_void_p, _c_int, _c_int, _c_void_p, _c_size_t,
+                                              _c_void_p]),
+    "kvzap_score_rmsnorm": (_c_int, [_c_void_p] * 3 + [_c_float] + [_c_void_p] * 6 + [_c_int] * 5 +
+                            [_c_void_p]),
     "kvzap_compress": (_c_int, [_c_void_p] * 7 + [_c_float, _c_int] + [_c_void_p] * 7 + [_c_int64] +
                        [_c_int] * 6 + [_c_void_p, _c_size_t, _c_void_p]),
     "kvzap_mask_compact": (_c_int, [_c_void_p, _c_float, _c_int] + [_c_void_p] * 8 + [_c_int64] +
@@ -715,6 +719,55 @@ def kvzap_prepare_scorer(W1: torch.Tensor, stream=None) -> torch.Tensor:
     if rc != 0:
         raise KvzapError(rc, "kvzap_prepare_scorer")
     return out
+
+
+def kvzap_prepare_scorer_rmsnorm(W1: torch.Tensor, gain: torch.Tensor, stream=None) -> torch.Tensor:
+    """W1 bf16 [M,Dh] and the norm's gain bf16 [Dh] -> the copy kvzap_score_rmsnorm takes."""
+    _check(W1, torch.bfloat16, "W1"); _check(gain, torch.bfloat16, "gain")
+    M, Dh = W1.shape
+    if gain.shape != (Dh,):
+        raise ValueError("gain must be [Dh]")
+    nbytes = max(kvzap_workspace_bytes(CALL_SCORE, 1, 1 << 20, Dh, M, 1), 256)
+    out = torch.empty(nbytes, dtype=torch.uint8, device=W1.device)
+    rc = lib().kvzap_prepare_scorer_rmsnorm(_ptr(W1), _ptr(gain), Dh, M, _ptr(out), nbytes,
+                                            _stream(stream))
+    if rc != 0:
+        raise KvzapError(rc, "kvzap_prepare_scorer_rmsnorm")
+    return out
+
+
+def kvzap_score_rmsnorm(x: torch.Tensor, W1_prepared: torch.Tensor, gain: torch.Tensor, eps: float,
+                        b1: Optional[torch.Tensor], W2: torch.Tensor, b2: Optional[torch.Tensor],
+                        want_normed: bool = False, scores: Optional[torch.Tensor] = None,
+                        rstd: Optional[torch.Tensor] = None, normed: Optional[torch.Tensor] = None,
+                        stream=None):
+    """The MLP surrogate on the un-normalised residual stream x bf16 [B,T,Dh].  Returns
+    (scores fp32 [B,H,T], rstd fp32 [B,T], normed bf16 [B,T,Dh] or None)."""
+    bf = torch.bfloat16
+    _check(x, bf, "x"); _check(gain, bf, "gain"); _check(b1, bf, "b1", True); _check(W2, bf, "W2")
+    _check(b2, bf, "b2", True)
+    B, T, Dh = x.shape
+    H, M = W2.shape
+    if W1_prepared.dtype != torch.uint8 or W1_prepared.numel() < M * Dh * 2:
+        raise ValueError("W1_prepared must come from kvzap_prepare_scorer_rmsnorm")
+    if gain.shape != (Dh,):
+        raise ValueError("gain must be [Dh]")
+    if scores is None:
+        scores = torch.empty((B, H, T), dtype=torch.float32, device=x.device)
+    if rstd is None:
+        rstd = torch.empty((B, T), dtype=torch.float32, device=x.device)
+    if normed is None and want_normed:
+        normed = torch.empty_like(x)
+    _check(scores, torch.float32, "scores"); _check(rstd, torch.float32, "rstd")
+    _check(normed, bf, "normed", True)
+    if scores.shape != (B, H, T) or rstd.shape != (B, T) or (normed is not None and normed.shape != x.shape):
+        raise ValueError("scores must be [B,H,T], rstd [B,T], normed like x")
+    rc = lib().kvzap_score_rmsnorm(_ptr(x), _ptr(W1_prepared), _ptr(gain), float(eps), _ptr(b1),
+                                   _ptr(W2), _ptr(b2), _ptr(scores), _ptr(rstd), _ptr(normed),
+                                   B, T, Dh, M, H, _stream(stream))
+    if rc != 0:
+        raise KvzapError(rc, "kvzap_score_rmsnorm")
+    return scores, rstd, normed
 
 
 def kvzap_score_prepared(hidden: torch.Tensor, W1_prepared: torch.Tensor, b1, W2: torch.Tensor, b2,

@@ -197,7 +197,43 @@ int kvzap_prepare_scorer(const void* W1, int Dh, int M, void* W1_prepared, size_
   const size_t n = (size_t)M * Dh * 2;
   const uintptr_t a = reinterpret_cast<uintptr_t>(W1), b = reinterpret_cast<uintptr_t>(W1_prepared);
   if (a < b + n && b < a + n) return KVZAP_ERR_SHAPE;     // not an in-place operation
-  return kvzap::launch_prepare_w1(W1, Dh, M, W1_prepared, static_cast<hipStream_t>(stream));
+  return kvzap::launch_prepare_w1(W1, nullptr, Dh, M, W1_prepared, static_cast<hipStream_t>(stream));
+}
+
+int kvzap_prepare_scorer_rmsnorm(const void* W1, const void* gain, int Dh, int M,
+                                 void* W1_prepared, size_t prepared_bytes, void* stream) {
+  const int rc = check_scorer_shape(Dh, M, 1);
+  if (rc != KVZAP_OK) return rc;
+  if (M == 0) return KVZAP_ERR_SHAPE;
+  if (!kvzap::score_rmsnorm_supports(Dh)) return KVZAP_ERR_UNSUPPORTED;
+  if (!W1 || !gain || !W1_prepared) return KVZAP_ERR_NULL;
+  if (!aligned16(W1) || !aligned16(gain) || !aligned256(W1_prepared)) return KVZAP_ERR_ALIGN;
+  if (prepared_bytes < kvzap::align_up((size_t)M * Dh * 2, 256)) return KVZAP_ERR_WORKSPACE;
+  const size_t n = (size_t)M * Dh * 2;
+  const uintptr_t a = reinterpret_cast<uintptr_t>(W1), b = reinterpret_cast<uintptr_t>(W1_prepared);
+  if (a < b + n && b < a + n) return KVZAP_ERR_SHAPE;     // not an in-place operation
+  return kvzap::launch_prepare_w1(W1, gain, Dh, M, W1_prepared, static_cast<hipStream_t>(stream));
+}
+
+int kvzap_score_rmsnorm(const void* x, const void* W1_prepared, const void* gain, float eps,
+                        const void* b1, const void* W2, const void* b2, float* scores,
+                        float* rstd, void* normed, int B, int T, int Dh, int M, int H,
+                        void* stream) {
+  if (M <= 0) return M == 0 ? KVZAP_ERR_UNSUPPORTED : KVZAP_ERR_SHAPE;   // MLP surrogate only
+  if (!(eps >= 0.0f)) return KVZAP_ERR_SHAPE;                          // also NaN
+  int rc = check_score(x, W1_prepared, b1, W2, b2, scores, B, T, Dh, M, H, W1_prepared, ~(size_t)0);
+  if (rc != KVZAP_OK) return rc == KVZAP_ERR_WORKSPACE ? KVZAP_ERR_ALIGN : rc;
+  if (!kvzap::score_rmsnorm_supports(Dh)) return KVZAP_ERR_UNSUPPORTED;
+  if ((long long)B * T == 0) return KVZAP_OK;
+  if (!gain || !rstd) return KVZAP_ERR_NULL;
+  if (!aligned16(gain) || !aligned16(rstd) || !aligned16(normed)) return KVZAP_ERR_ALIGN;
+  if (normed) {                                                        // not an in-place operation
+    const size_t n = (size_t)B * T * Dh * 2;
+    const uintptr_t a = reinterpret_cast<uintptr_t>(x), b = reinterpret_cast<uintptr_t>(normed);
+    if (a < b + n && b < a + n) return KVZAP_ERR_SHAPE;
+  }
+  return kvzap::launch_score_mlp_rmsnorm(x, W1_prepared, gain, eps, b1, W2, b2, scores, rstd, normed,
+                                         B, T, Dh, M, H, static_cast<hipStream_t>(stream));
 }
 
 int kvzap_score_prepared(const void* hidden, const void* W1_prepared, const void* b1,

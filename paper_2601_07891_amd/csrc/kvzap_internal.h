@@ -113,7 +113,14 @@ int launch_skinny_gemm(const void* hidden, const void* W1, float* partial, long 
                        int M, int ks, hipStream_t stream);
 // bytes kvzap_score's workspace needs for an MLP surrogate on `rows` tokens
 size_t score_mlp_workspace_bytes(long long rows, int Dh, int M);
-int launch_prepare_w1(const void* W1, int Dh, int M, void* out, hipStream_t stream);
+// gain (optional): the prepared copy holds W1 * diag(gain), for launch_score_mlp_rmsnorm
+int launch_prepare_w1(const void* W1, const void* gain, int Dh, int M, void* out, hipStream_t stream);
+// the MLP surrogate on the un-normalised residual stream (single-kernel path only)
+bool score_rmsnorm_supports(int Dh);
+int launch_score_mlp_rmsnorm(const void* x, const void* W1_prepared, const void* gain, float eps,
+                             const void* b1, const void* W2, const void* b2, float* scores,
+                             float* rstd, void* normed, int B, int T, int Dh, int M, int H,
+                             hipStream_t stream);
 // workspace == nullptr: W1 is the copy made by launch_prepare_w1
 int launch_score_mlp(const void* hidden, const void* W1, const void* b1, const void* W2,
                      const void* b2, float* scores, int B, int T, int Dh, int M, int H,

@@ -255,25 +255,53 @@ constexpr int kNS = kPD + 1;                 // LDS stages
 
 // W1 [M][Dh] -> A-fragment order: [Dh/64][M/32][4][64 lanes] x 16 B, where lane
 // (i = lane & 31, kg = lane >> 5) of k-step kk holds W1[rb*32 + i][kt*64 + kk*16 + kg*8 .. +8]
+// gain (optional, bf16 [Dh]): the copy holds W1[m][k] * gain[k] rounded to bf16 -- the first
+// projection of a surrogate that is applied to gain-scaled (normalised) states
 __global__ __launch_bounds__(256) void arrange_w1_kernel(const u32x4* __restrict__ W1,
-                                                         u32x4* __restrict__ W1f, int M, int Dh) {
+                                                         u32x4* __restrict__ W1f, int M, int Dh,
+                                                         const u32x4* __restrict__ gain) {
   const int n = M * (Dh / 8);
   const int rbs = M / 32;
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
     const int lane = i & 63, kk = (i >> 6) & 3, rb = (i >> 8) % rbs, kt = i / (256 * rbs);
     const int row = rb * 32 + (lane & 31), piece = kt * 8 + kk * 2 + (lane >> 5);
-    W1f[i] = W1[(size_t)row * (Dh / 8) + piece];
+    u32x4 w = W1[(size_t)row * (Dh / 8) + piece];
+    if (gain) {
+      const u32x4 g = gain[piece];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float lo = __uint_as_float(w[e] << 16) * __uint_as_float(g[e] << 16);
+        const float hi = __uint_as_float(w[e] & 0xffff0000u) * __uint_as_float(g[e] & 0xffff0000u);
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        const bf16x2 p = {(__bf16)lo, (__bf16)hi};
+        w[e] = __builtin_bit_cast(unsigned int, p);
+      }
+    }
+    W1f[i] = w;
   }
 }
 
+// What the kernel does besides scoring when its input is the un-normalised residual stream
+// (kNorm): every token's 1 / sqrt(mean x^2 + eps) is accumulated next to the first projection
+// (the B fragments are in registers anyway), applied to the accumulators before b1 and GELU
+// -- the gain is already in the prepared W1 -- written to `rstd`, and, if `normed` is given,
+// the block finally re-reads its own rows and writes x * rstd * gain as bf16.
+struct NormArgs {
+  const unsigned short* gain;    // bf16 [Dh]
+  float eps;
+  float* rstd;                   // fp32 [rows]
+  unsigned short* normed;        // bf16 [rows, Dh] or nullptr
+};
+
 // UB 32-unit blocks per wavefront, TB 32-token blocks per block; kSplit: the block covers one
 // K-slice (blockIdx.y) and writes its part of the first projection to `partial`
-template <int UB, int TB, bool kSplit>
+template <int UB, int TB, bool kSplit, bool kNorm = false>
 __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
     const unsigned short* hidden, const unsigned char* W1f,   // not __restrict__: their loads must stay ordered w.r.t. the waits
     const unsigned short* __restrict__ b1, const unsigned short* __restrict__ W2,
     const unsigned short* __restrict__ b2, float* __restrict__ scores,
-    long long rows, int T, int Dh, int H, int nk, float* __restrict__ partial) {
+    long long rows, int T, int Dh, int H, int nk, float* __restrict__ partial, NormArgs norm) {
+  static_assert(!(kSplit && kNorm), "the normalising form is the single-kernel path");
   constexpr int U = 128 * UB;
   constexpr int TOK = 32 * TB;               // tokens per block
   constexpr int STAGE = TOK * 128;           // bytes per LDS stage (TOK rows of one K tile)
@@ -336,6 +364,11 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
 
   floatx16 acc[UB][TB];
 
+  // kNorm: sum of x^2 of token 32*wid + l32 over this lane's half of every K step (a wavefront
+  // beyond the last token block re-reads that block and drops the result)
+  float ssq = 0.0f;
+  bf16x8 xb[4];
+  const int xrow = 32 * (wid < TB ? wid : TB - 1) + l32;
   // nk >= kPD + 1 tiles (checked by the launcher)
   bf16x8 a[4][UB];                         // a[kk]: step kk of the current tile, then of the next
   bf16x8 b[2][TB];
@@ -367,13 +400,28 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
     }
     reinterpret_cast<f16x8*>(sW2)[i * 256 + tid] = w;
   }
+  if constexpr (kNorm) {
+    // b1 comes after the row scale: it waits in LDS for the epilogue instead of riding in
+    // the accumulators (one lane of every 32 holds each unit's value)
+    float* const sB1 = reinterpret_cast<float*>(sW2 + 16 * U * 2 + TOK * sizeof(float));   // [U]
+    if (l32 == 0) {
+#pragma unroll
+      for (int ub = 0; ub < UB; ++ub)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const floatx4 v = {__uint_as_float(b1_stage[ub][q].x << 16), __uint_as_float(b1_stage[ub][q].x & 0xffff0000u),
+                             __uint_as_float(b1_stage[ub][q].y << 16), __uint_as_float(b1_stage[ub][q].y & 0xffff0000u)};
+          *reinterpret_cast<floatx4*>(sB1 + wid * (32 * UB) + 32 * ub + 8 * q + 4 * kg) = v;
+        }
+    }
+  }
   // the first projection accumulates on top of b1 (a K-slice of a split launch: on zero)
 #pragma unroll
   for (int ub = 0; ub < UB; ++ub)
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       float v[4] = {0.f, 0.f, 0.f, 0.f};
-      if constexpr (!kSplit) {
+      if constexpr (!kSplit && !kNorm) {
         v[0] = __uint_as_float(b1_stage[ub][q].x << 16); v[1] = __uint_as_float(b1_stage[ub][q].x & 0xffff0000u);
         v[2] = __uint_as_float(b1_stage[ub][q].y << 16); v[3] = __uint_as_float(b1_stage[ub][q].y & 0xffff0000u);
       }
@@ -429,6 +477,28 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
           for (int j = 0; j < NDJ; ++j)
             if (j * 2 * UB / NDJ == (kk - 2) * UB + ub) dma(j, t + kPD);
         }
+        if constexpr (kNorm) {
+          // Sum of squares of the tokens' states: wavefront w owns token block w and reads that
+          // block's four fragments of the current tile from LDS once more, into registers of
+          // its own (the copy among its B fragments sits in a register only a compile-time
+          // index reaches), during K steps 0-1; the 16 two-element dot products follow in K
+          // steps 2-3.  No branch; the extra LDS reads ride in the MFMA shadow.
+          constexpr int kHalf = 2 * UB;                  // groups in half a tile
+          const int G = kk * UB + ub;
+#pragma unroll
+          for (int f = 0; f < 4; ++f) {
+            if (f * kHalf / 4 == G)
+              xb[f] = *reinterpret_cast<const bf16x8*>(smem + (t % kNS) * STAGE + lds_off(xrow, f * 2 + kg));
+            if (f * kHalf / 4 == G - kHalf) {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+                const bf16x2 p = {xb[f][2 * e], xb[f][2 * e + 1]};
+                ssq = __builtin_amdgcn_fdot2_f32_bf16(p, p, ssq, false);
+              }
+            }
+          }
+        }
         // token blocks in alternating direction: the MFMA that opens a group then keeps the B
         // operand of the one before it (both operands switch at once otherwise); measured 1-2 %
 #pragma unroll
@@ -476,6 +546,13 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
     }
     return;
   }
+  if constexpr (kNorm) {
+    // each token's sum of squares (both lane halves) goes through LDS to the lanes that hold
+    // its accumulators; the barrier below publishes it
+    float* sSsq = reinterpret_cast<float*>(sW2 + 16 * U * 2 + TOK * sizeof(float) + U * sizeof(float));  // [TOK]
+    const float both = ssq + __shfl_xor(ssq, 32, 64);
+    if (kg == 0 && wid < TB) sSsq[32 * wid + l32] = both;
+  }
   __syncthreads();      // LDS is reused for the reduction below
 
   // ---- epilogue: GELU, then the M -> H projection as a second MFMA (fp16 operands) ----
@@ -483,6 +560,21 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
   // Registers 8s..8s+7 form the B operand of MFMA step s; the matching A operand holds
   // W2[head = l32][the same eight units] (zero for heads >= H).
   const int ubase = wid * (32 * UB);
+  // kNorm: the row scale of token 32*tb + l32 (the lane pair l32, l32 + 32 holds the two
+  // halves of every K step); z = rstd * acc + b1
+  float rs[TB];
+  if constexpr (kNorm) {
+    const float* sSsq = reinterpret_cast<const float*>(sW2 + 16 * U * 2 + TOK * sizeof(float) + U * sizeof(float));
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) {
+      rs[tb] = 1.0f / sqrtf(sSsq[32 * tb + l32] / (float)Dh + norm.eps);
+    }
+    if (wid == 0 && kg == 0) {
+#pragma unroll
+      for (int tb = 0; tb < TB; ++tb)
+        if (32 * tb + l32 < rows_here) norm.rstd[row0 + 32 * tb + l32] = rs[tb];
+    }
+  }
   floatx16 acc2[TB];
 #pragma unroll
   for (int tb = 0; tb < TB; ++tb)
@@ -499,11 +591,23 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
         const uint2 p1 = *reinterpret_cast<const uint2*>(sW2 + ((size_t)l32 * U + u0 + 8) * 2);
         w2.x = p0.x; w2.y = p0.y; w2.z = p1.x; w2.w = p1.y;
       }
+      float bias[8];
+      if constexpr (kNorm) {
+        const float* sB1 = reinterpret_cast<const float*>(sW2 + 16 * U * 2 + TOK * sizeof(float));
+        const floatx4 lo = *reinterpret_cast<const floatx4*>(sB1 + u0);
+        const floatx4 hi = *reinterpret_cast<const floatx4*>(sB1 + u0 + 8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) bias[e] = e < 4 ? lo[e] : hi[e - 4];
+      }
 #pragma unroll
       for (int tb = 0; tb < TB; ++tb) {
         f16x8 g;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) g[e] = (_Float16)gelu_fused(acc[ub][tb][8 * s + e]);
+        for (int e = 0; e < 8; ++e) {
+          float z = acc[ub][tb][8 * s + e];
+          if constexpr (kNorm) z = fmaf(z, rs[tb], bias[e]);
+          g[e] = (_Float16)gelu_fused(z);
+        }
         acc2[tb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, w2), g,
                                                           acc2[tb], 0, 0, 0);
       }
@@ -544,6 +648,52 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
       long long t = (long long)t_first + tok;
       while (t >= T) { t -= T; ++bidx; }
       scores[((size_t)bidx * H + head) * T + t] = s;
+    }
+  }
+  if constexpr (kNorm) {
+    if (norm.normed) {
+      // the normalised states for the layer's own projections: the row scale is known only
+      // now, so the block goes over its rows a second time (x * rstd * gain, rounded to bf16)
+      float* sR = reinterpret_cast<float*>(sW2 + 16 * U * 2);     // [TOK]
+      if (wid == 0 && kg == 0) {
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) sR[32 * tb + l32] = rs[tb];
+      }
+      __syncthreads();
+      const int ppr = Dh / 8;                                      // 16-byte pieces per row
+      const u32x4* xin = reinterpret_cast<const u32x4*>(hidden + (size_t)row0 * Dh);
+      u32x4* yout = reinterpret_cast<u32x4*>(norm.normed + (size_t)row0 * Dh);
+      const u32x4* gain8 = reinterpret_cast<const u32x4*>(norm.gain);
+      const int total = rows_here * ppr;
+      // only this block's 256 threads are on the CU: eight 16-byte pieces in flight per thread
+      constexpr int kFly = 8;
+      for (int p0 = tid; p0 < total; p0 += 256 * kFly) {
+        u32x4 x[kFly];
+#pragma unroll
+        for (int u = 0; u < kFly; ++u) {
+          const int p = p0 + 256 * u;
+          if (p < total) x[u] = __builtin_nontemporal_load(xin + p);
+        }
+#pragma unroll
+        for (int u = 0; u < kFly; ++u) {
+          const int p = p0 + 256 * u;
+          if (p < total) {
+            const int r = p / ppr, c = p - r * ppr;
+            const u32x4 g = gain8[c];
+            const float sc = sR[r];
+            u32x4 y;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float lo = __uint_as_float(x[u][e] << 16) * sc * __uint_as_float(g[e] << 16);
+              const float hi = __uint_as_float(x[u][e] & 0xffff0000u) * sc * __uint_as_float(g[e] & 0xffff0000u);
+              typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+              const bf16x2 pr = {(__bf16)lo, (__bf16)hi};
+              y[e] = __builtin_bit_cast(unsigned int, pr);
+            }
+            __builtin_nontemporal_store(y, yout + p);
+          }
+        }
+      }
     }
   }
 }
@@ -622,11 +772,13 @@ inline int frag_ksplit(long long blocks, int nk_total) {
 template <int UB, int TB>
 int launch_frag(const void* hidden, const void* W1, const void* b1, const void* W2,
                 const void* b2, float* scores, long long rows, int T, int Dh, int H,
-                void* workspace, hipStream_t stream) {
+                void* workspace, hipStream_t stream, const NormArgs* norm) {
   constexpr int TOK = 32 * TB;
   constexpr size_t ring = (size_t)kNS * TOK * 128;
   static_assert(ring >= (size_t)4 * 16 * TOK * sizeof(float), "reduction buffer fits");
-  constexpr size_t lds = ring + (size_t)16 * (128 * UB) * 2;   // + W2 as [16][M] fp16
+  // + W2 as [16][M] fp16, then (normalising form) the row scales, b1 and the sums of squares as fp32
+  constexpr size_t lds = ring + (size_t)16 * (128 * UB) * 2 + TOK * sizeof(float) +
+                         (128 * UB) * sizeof(float) + TOK * sizeof(float);
   // once per process, which drives one GPU (thread-safe: a function-local static)
   static const hipError_t attr_rc =
       hipFuncSetAttribute(reinterpret_cast<const void*>(score_mlp_frag_kernel<UB, TB, false>),
@@ -634,12 +786,23 @@ int launch_frag(const void* hidden, const void* W1, const void* b1, const void* 
   static const hipError_t attr_rc_split =
       hipFuncSetAttribute(reinterpret_cast<const void*>(score_mlp_frag_kernel<UB, TB, true>),
       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  if (attr_rc != hipSuccess || attr_rc_split != hipSuccess) return KVZAP_ERR_RUNTIME;
+  static const hipError_t attr_rc_norm =
+      hipFuncSetAttribute(reinterpret_cast<const void*>(score_mlp_frag_kernel<UB, TB, false, true>),
+      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (attr_rc != hipSuccess || attr_rc_split != hipSuccess || attr_rc_norm != hipSuccess)
+    return KVZAP_ERR_RUNTIME;
   const int M = 128 * UB;
+  if (norm) {     // residual stream in, W1 already prepared with the gain folded in
+    score_mlp_frag_kernel<UB, TB, false, true><<<dim3((unsigned)((rows + TOK - 1) / TOK)), 256, lds, stream>>>(
+        static_cast<const unsigned short*>(hidden), static_cast<const unsigned char*>(W1),
+        static_cast<const unsigned short*>(b1), static_cast<const unsigned short*>(W2),
+        static_cast<const unsigned short*>(b2), scores, rows, T, Dh, H, Dh / kBK, nullptr, *norm);
+    return hipGetLastError() == hipSuccess ? KVZAP_OK : KVZAP_ERR_RUNTIME;
+  }
   // workspace == nullptr: W1 already is the fragment-ordered copy (launch_prepare_w1)
   if (workspace)
     arrange_w1_kernel<<<512, 256, 0, stream>>>(static_cast<const u32x4*>(W1),
-                                               static_cast<u32x4*>(workspace), M, Dh);
+                                               static_cast<u32x4*>(workspace), M, Dh, nullptr);
   const void* w1f = workspace ? workspace : W1;
   const long long blocks = (rows + TOK - 1) / TOK;
   // Few blocks (mid-length prompts): a block needs 50-85 us for all of K whatever the grid,
@@ -653,12 +816,12 @@ int launch_frag(const void* hidden, const void* W1, const void* b1, const void* 
     score_mlp_frag_kernel<UB, TB, true><<<dim3((unsigned)blocks, ks), 256, lds, stream>>>(
         static_cast<const unsigned short*>(hidden), static_cast<const unsigned char*>(w1f),
         static_cast<const unsigned short*>(b1), static_cast<const unsigned short*>(W2),
-        static_cast<const unsigned short*>(b2), scores, rows, T, Dh, H, Dh / kBK / ks, partial);
+        static_cast<const unsigned short*>(b2), scores, rows, T, Dh, H, Dh / kBK / ks, partial, NormArgs{});
   else
     score_mlp_frag_kernel<UB, TB, false><<<dim3((unsigned)blocks), 256, lds, stream>>>(
         static_cast<const unsigned short*>(hidden), static_cast<const unsigned char*>(w1f),
         static_cast<const unsigned short*>(b1), static_cast<const unsigned short*>(W2),
-        static_cast<const unsigned short*>(b2), scores, rows, T, Dh, H, Dh / kBK, nullptr);
+        static_cast<const unsigned short*>(b2), scores, rows, T, Dh, H, Dh / kBK, nullptr, NormArgs{});
   if (hipGetLastError() != hipSuccess) return KVZAP_ERR_RUNTIME;
   if (ks > 1)
     score_finish_kernel<<<dim3((unsigned)((rows + 3) / 4)), 256, 0, stream>>>(
@@ -695,11 +858,13 @@ __global__ __launch_bounds__(256) void copy_w1_kernel(const u32x4* __restrict__ 
 
 // The form of W1 that launch_score_mlp takes with workspace == nullptr: fragment order for
 // the main kernel, a plain copy for the small-D_h kernel.
-int launch_prepare_w1(const void* W1, int Dh, int M, void* out, hipStream_t stream) {
+int launch_prepare_w1(const void* W1, const void* gain, int Dh, int M, void* out, hipStream_t stream) {
   const bool frag = (Dh / kBK) >= kPD + 1;
+  if (gain && !frag) return KVZAP_ERR_UNSUPPORTED;
   if (frag)
     arrange_w1_kernel<<<512, 256, 0, stream>>>(static_cast<const u32x4*>(W1),
-                                               static_cast<u32x4*>(out), M, Dh);
+                                               static_cast<u32x4*>(out), M, Dh,
+                                               static_cast<const u32x4*>(gain));
   else
     copy_w1_kernel<<<64, 256, 0, stream>>>(static_cast<const u32x4*>(W1),
                                            static_cast<u32x4*>(out), M * (Dh / 8));
@@ -720,6 +885,25 @@ size_t score_mlp_workspace_bytes(long long rows, int Dh, int M) {
   return need;
 }
 
+bool score_rmsnorm_supports(int Dh) { return (Dh / kBK) >= kPD + 1; }
+
+int launch_score_mlp_rmsnorm(const void* x, const void* W1_prepared, const void* gain, float eps,
+                             const void* b1, const void* W2, const void* b2, float* scores,
+                             float* rstd, void* normed, int B, int T, int Dh, int M, int H,
+                             hipStream_t stream) {
+  const long long rows = (long long)B * T;
+  const NormArgs norm{static_cast<const unsigned short*>(gain), eps, rstd,
+                      static_cast<unsigned short*>(normed)};
+  switch (M / 128) {
+    case 1: return launch_frag<1, 4>(x, W1_prepared, b1, W2, b2, scores, rows, T, Dh, H, nullptr, stream, &norm);
+    case 2: return launch_frag<2, 4>(x, W1_prepared, b1, W2, b2, scores, rows, T, Dh, H, nullptr, stream, &norm);
+    case 3: return launch_frag<3, 4>(x, W1_prepared, b1, W2, b2, scores, rows, T, Dh, H, nullptr, stream, &norm);
+    case 4: return launch_frag<4, 4>(x, W1_prepared, b1, W2, b2, scores, rows, T, Dh, H, nullptr, stream, &norm);
+    case 5: return launch_frag<5, 3>(x, W1_prepared, b1, W2, b2, scores, rows, T, Dh, H, nullptr, stream, &norm);
+    default: return KVZAP_ERR_UNSUPPORTED;
+  }
+}
+
 int launch_score_mlp(const void* hidden, const void* W1, const void* b1, const void* W2,
                      const void* b2, float* scores, int B, int T, int Dh, int M, int H,
                      void* workspace, hipStream_t stream) {
@@ -738,7 +922,7 @@ int launch_score_mlp(const void* hidden, const void* W1, const void* b1, const v
 #define KVZAP_MLP_CASE(UBV)                                                                     \
   case UBV:                                                                                     \
     return frag ? launch_frag<UBV, (UBV <= 4 ? 4 : 3)>(hidden, W1, b1, W2, b2, scores, rows, T, \
-                                                       Dh, H, workspace, stream)                \
+                                                       Dh, H, workspace, stream, nullptr)       \
                 : launch_one<UBV>(hidden, W1, b1, W2, b2, scores, rows, T, Dh, H, stream);
   switch (M / 128) {
     KVZAP_MLP_CASE(1)

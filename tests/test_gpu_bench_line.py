@@ -59,7 +59,8 @@ def test_default_line_carries_the_other_workloads():
     others = d["other_workloads"]
     names = [o["config"]["workload"] for o in others]
     assert names == ["c1_t1k_linear", "c2_llama8b_32k_mlp", "c4_qwen32b_4x64k_linear",
-                     "c4_qwen32b_4x64k_mlp", "c5_qwen8b_decode", "c5_qwen8b_decode+attend"]
+                     "c4_qwen32b_4x64k_mlp", "c5_qwen8b_decode", "c5_qwen8b_decode+attend",
+                     "c3_qwen8b_128k_mlp+fused-norm"]
     for o in others[:4]:
         assert o["value"] > 0 and o["unit"] == "tokens/s"
         assert 0.05 < o["config"]["kept_fraction_measured"] < 0.95
@@ -67,6 +68,9 @@ def test_default_line_carries_the_other_workloads():
     assert others[2]["roofline"]["bound"] == "hbm" and others[3]["roofline"]["bound"] == "mfma"
     assert others[4]["us_per_layer_step"] > 0 and others[4]["hip_graph"]["us_per_layer_step"] > 0
     assert others[5]["roofline"]["bound"] == "hbm" and 0.3 < others[5]["roofline"]["frac"] < 1.0
+    fn = others[6]
+    assert fn["roofline"]["bound"] == "mfma" and 0.2 < fn["roofline"]["frac"] < 1.0
+    assert len(fn["ms_per_layer"]) == 4 and all(v > 0 for v in fn["ms_per_layer"].values())
 
 
 def test_decode_lines():
