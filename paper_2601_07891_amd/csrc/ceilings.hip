@@ -1,7 +1,8 @@
 // kvzap_ceilings: measures, on the GPU it runs on, the practical ceilings the prune-step
 // kernels are compared with, next to the published peaks (HBM 8 TB/s, bf16 MFMA 2.5 PFLOP/s):
-//   1. sustained v_mfma_f32_32x32x16_bf16 rate from registers, constant vs random operands
-//      (random bf16 data toggles the datapath and the part then runs at a lower clock);
+//   1. sustained v_mfma_f32_32x32x16_bf16 rate from registers for constant, random-mantissa
+//      and normally distributed operands, with few and with many operand registers (the more
+//      the data toggles the datapath, the lower the clock the part sustains);
 //   2. HBM read-stream bandwidth (16-byte loads, 1.25 GiB);
 //   3. HBM copy bandwidth (read + write, 2 x 0.5 GiB).
 // Stand-alone host program: `kvzap_ceilings` prints one line per measurement.
@@ -25,30 +26,54 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-template <int RANDOM>
+// MODE 0: one constant bit pattern; 1: random sign and mantissa, exponent of 1.0; 2: roughly
+// normal values (sum of four uniform bytes), i.e. varying exponents too, as real activations
+// and weights have.  NA x NB operand registers are cycled through: with 4 x 4 every MFMA of an
+// iteration repeats the operands of the previous iteration, with 16 x 8 (what one K tile of the
+// scorer holds) the datapath sees new values every time.
+__device__ __forceinline__ unsigned next_rand(unsigned& x) { x ^= x << 13; x ^= x >> 17; x ^= x << 5; return x; }
+
+__device__ __forceinline__ unsigned normal_bf16(unsigned& x) {
+  const unsigned r = next_rand(x);
+  const float f = ((r & 255) + ((r >> 8) & 255) + ((r >> 16) & 255) + ((r >> 24) & 255) - 510.f) * (1.f / 147.8f);
+  return __float_as_uint(f) >> 16;
+}
+
+template <int MODE, int N>
+__device__ __forceinline__ void fill_operands(bf16x8* v, unsigned seed) {
+  for (int i = 0; i < N; ++i) {
+    unsigned x = (threadIdx.x * 2654435761u) ^ (seed + i * 977u) ^ (blockIdx.x * 40503u) ^ 0x9e3779b9u;
+    u32x4 w;
+    for (int e = 0; e < 4; ++e) {
+      if (MODE == 0) {
+        w[e] = 0x12345678u & 0x807f807fu | 0x3f003f00u;
+      } else if (MODE == 1) {
+        const unsigned r = next_rand(x);
+        w[e] = (r & 0x807f807fu) | 0x3f003f00u | ((r >> 3) & 0x00800080u);
+      } else {
+        const unsigned lo = normal_bf16(x), hi = normal_bf16(x);
+        w[e] = lo | (hi << 16);
+      }
+    }
+    v[i] = __builtin_bit_cast(bf16x8, w);
+  }
+}
+
+template <int MODE, int NA, int NB>
 __global__ __launch_bounds__(256) void mfma_rate_kernel(float* out, int iters, unsigned seed) {
   floatx16 acc[16];
   for (int i = 0; i < 16; ++i)
     for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
-  bf16x8 a[4], b[4];
-  for (int i = 0; i < 4; ++i) {
-    unsigned x = (threadIdx.x * 2654435761u) ^ (seed + i * 977u) ^ (blockIdx.x * 40503u);
-    u32x4 va, vb;
-    for (int e = 0; e < 4; ++e) {   // bf16 pairs of magnitude ~1 with random sign and mantissa
-      x ^= x << 13; x ^= x >> 17; x ^= x << 5;
-      const unsigned r1 = RANDOM ? x : 0x12345678u;
-      va[e] = (r1 & 0x807f807fu) | 0x3f003f00u | ((r1 >> 3) & 0x00800080u);
-      x ^= x << 13; x ^= x >> 17; x ^= x << 5;
-      const unsigned r2 = RANDOM ? x : 0x9abcdef0u;
-      vb[e] = (r2 & 0x807f807fu) | 0x3f003f00u | ((r2 >> 3) & 0x00800080u);
-    }
-    a[i] = __builtin_bit_cast(bf16x8, va);
-    b[i] = __builtin_bit_cast(bf16x8, vb);
-  }
+  bf16x8 a[NA], b[NB];
+  fill_operands<MODE, NA>(a, seed);
+  fill_operands<MODE, NB>(b, seed + 12345u);
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i)
-      acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i & 3], b[i >> 2], acc[i], 0, 0, 0);
+    for (int r = 0; r < NA / 4; ++r)
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(i & 3) + 4 * r], b[(i >> 2) + 4 * (r % (NB / 4))],
+                                                         acc[i], 0, 0, 0);
   }
   float s = 0;
   for (int i = 0; i < 16; ++i)
@@ -112,14 +137,19 @@ static float median_ms(F f, int reps) {
 int main() {
   float* out;
   CK(hipMalloc(&out, 1024 * 256 * sizeof(float)));
-  const int iters = 2000;
+  // ~0.3 s per launch: long enough for the clock to settle at what the power draw allows
+  const int iters = 256;
   const double flops = 1024.0 * 4 * iters * 16 * 32768.0;
-  for (int w = 0; w < 20; ++w) mfma_rate_kernel<1><<<1024, 256>>>(out, iters, 7u + w);   // clocks settle
+  for (int w = 0; w < 6; ++w) mfma_rate_kernel<2, 4, 4><<<1024, 256>>>(out, iters, 7u + w);   // clocks settle
   CK(hipDeviceSynchronize());
-  float t = median_ms([&](int r) { mfma_rate_kernel<0><<<1024, 256>>>(out, iters, 999u + r); }, 10);
-  std::printf("mfma_bf16_32x32x16 constant operands: %.0f TFLOP/s\n", flops / t / 1e9);
-  t = median_ms([&](int r) { mfma_rate_kernel<1><<<1024, 256>>>(out, iters, 999u + r); }, 10);
-  std::printf("mfma_bf16_32x32x16 random operands:   %.0f TFLOP/s\n", flops / t / 1e9);
+  float t = median_ms([&](int r) { mfma_rate_kernel<0, 4, 4><<<1024, 256>>>(out, iters, 999u + r); }, 5);
+  std::printf("mfma_bf16_32x32x16 constant operands, 4x4 registers:          %.0f TFLOP/s\n", flops / t / 1e9);
+  t = median_ms([&](int r) { mfma_rate_kernel<1, 4, 4><<<1024, 256>>>(out, iters, 999u + r); }, 5);
+  std::printf("mfma_bf16_32x32x16 random mantissas, 4x4 registers:           %.0f TFLOP/s\n", flops / t / 1e9);
+  t = median_ms([&](int r) { mfma_rate_kernel<2, 4, 4><<<1024, 256>>>(out, iters, 999u + r); }, 5);
+  std::printf("mfma_bf16_32x32x16 normal values, 4x4 registers:              %.0f TFLOP/s\n", flops / t / 1e9);
+  t = median_ms([&](int r) { mfma_rate_kernel<2, 16, 8><<<1024, 256>>>(out, iters / 4, 999u + r); }, 5);
+  std::printf("mfma_bf16_32x32x16 normal values, 16x8 registers (a K tile):   %.0f TFLOP/s\n", flops / t / 1e9);
 
   const size_t bytes = (size_t)1280 << 20, n = bytes / 16;
   u32x4 *a, *b;
