@@ -338,6 +338,11 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
                              : uint2{0u, 0u};
   }
 
+  // b2 is loaded here and waits in LDS for the very end: a global load in the tail would
+  // expose a memory round trip with nothing left to overlap it
+  float* const sB2 = reinterpret_cast<float*>(sW2 + 16 * U * 2 + 2 * TOK * sizeof(float) + U * sizeof(float));   // [16]
+  const unsigned short b2_stage = (b2 && tid < H) ? b2[tid] : (unsigned short)0;
+
   // hidden load-to-LDS: instruction j (0..3) of wavefront w fills LDS chunk j*4+w of a
   // stage = rows (j*4+w)*8 + lane/8, physical piece lane%8 <- logical piece (lane%8) ^ (row%8)
   // blockIdx.y: the K-slice of nk tiles this block covers (one slice unless `partial` is set)
@@ -400,6 +405,7 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
     }
     reinterpret_cast<f16x8*>(sW2)[i * 256 + tid] = w;
   }
+  if (tid < 16) sB2[tid] = bf16_bits_to_float(b2_stage);
   if constexpr (kNorm) {
     // b1 comes after the row scale: it waits in LDS for the epilogue instead of riding in
     // the accumulators (one lane of every 32 holds each unit's value)
@@ -643,7 +649,7 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
       s += red[(1 * H + head) * TOK + tok];
       s += red[(2 * H + head) * TOK + tok];
       s += red[(3 * H + head) * TOK + tok];
-      if (b2) s += bf16_bits_to_float(b2[head]);
+      s += sB2[head];
       long long bidx = b_first;
       long long t = (long long)t_first + tok;
       while (t >= T) { t -= T; ++bidx; }
@@ -778,7 +784,7 @@ int launch_frag(const void* hidden, const void* W1, const void* b1, const void* 
   static_assert(ring >= (size_t)4 * 16 * TOK * sizeof(float), "reduction buffer fits");
   // + W2 as [16][M] fp16, then (normalising form) the row scales, b1 and the sums of squares as fp32
   constexpr size_t lds = ring + (size_t)16 * (128 * UB) * 2 + TOK * sizeof(float) +
-                         (128 * UB) * sizeof(float) + TOK * sizeof(float);
+                         (128 * UB) * sizeof(float) + TOK * sizeof(float) + 16 * sizeof(float);   // + b2
   // once per process, which drives one GPU (thread-safe: a function-local static)
   static const hipError_t attr_rc =
       hipFuncSetAttribute(reinterpret_cast<const void*>(score_mlp_frag_kernel<UB, TB, false>),
