@@ -23,6 +23,7 @@
 // row, which keeps both the ds_write_b128 and the operand ds_read_b128 free of
 // bank conflicts.
 #include <type_traits>
+#include <utility>
 
 #include "kvzap_internal.h"
 
@@ -293,6 +294,34 @@ struct NormArgs {
   unsigned short* normed;        // bf16 [rows, Dh] or nullptr
 };
 
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), in order: loops whose index
+// has to be a constant expression (an instruction's immediate offset, a wait count)
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+// One A fragment: 16 bytes per lane from  sbase + voff + OFF  (sbase uniform, in scalar
+// registers).  Issued as inline asm so that the compiler does not size the wait for it:
+// its own count knows nothing of the load-to-LDS operations that share the in-order
+// vector-memory queue and therefore always waits for more than the fragment (the hidden
+// tiles issued behind it as well, i.e. for HBM).  The matching wait is wait_fragment().
+template <int OFF>
+__device__ __forceinline__ void load_fragment(bf16x8& dst, unsigned voff, const unsigned char* sbase) {
+  asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3" : "=v"(dst) : "v"(voff), "s"(sbase), "n"(OFF));
+}
+// Wait until at most N vector-memory operations issued after the fragment's load are still
+// outstanding; the fragment is an in/out operand so that no use of it moves above the wait.
+template <int N>
+__device__ __forceinline__ void wait_fragment(bf16x8& frag) {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  asm volatile("s_waitcnt vmcnt(%1)" : "+v"(frag) : "n"(N));
+}
+
 // UB 32-unit blocks per wavefront, TB 32-token blocks per block; kSplit: the block covers one
 // K-slice (blockIdx.y) and writes its part of the first projection to `partial`
 template <int UB, int TB, bool kSplit, bool kNorm = false>
@@ -361,11 +390,15 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
     load_to_lds_b128(hb + (size_t)tile * (kBK * 2) + h_off[j],
                      lds0 + (unsigned)((tile % kNS) * STAGE + (j * 4 + wid) * 1024));
   };
-  // A fragments of this wavefront: unit blocks rb = wid*UB + ub
-  const unsigned char* abase = W1f + ((size_t)kt0 * (U / 32) * 4 + (size_t)wid * UB * 4) * 1024 + lane * 16;
-  auto aload = [&](int tile, int ub, int kk) -> bf16x8 {
-    return *reinterpret_cast<const bf16x8*>(abase + ((size_t)(tile * (U / 32) + ub) * 4 + kk) * 1024);
-  };
+  // A fragments of this wavefront: unit blocks rb = wid*UB + ub; fragment (ub, kk) of K tile t
+  // is the KB at  abase + t*kATile + (ub*4 + kk)*1024, 16 bytes per lane.  They are loaded
+  // kLead tiles ahead into kLead register sets.
+  constexpr int kLead = (UB <= 4 && !kNorm) ? 2 : 1;
+  constexpr size_t kATile = (size_t)(U / 32) * 4 * 1024;
+  const unsigned char* abase = W1f + ((size_t)kt0 * (U / 32) * 4 + (size_t)wid * UB * 4) * 1024;
+  unsigned a_voff[UB];
+#pragma unroll
+  for (int ub = 0; ub < UB; ++ub) a_voff[ub] = (unsigned)lane * 16u + (unsigned)ub * 4096u;
 
   floatx16 acc[UB][TB];
 
@@ -375,25 +408,46 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
   bf16x8 xb[4];
   const int xrow = 32 * (wid < TB ? wid : TB - 1) + l32;
   // nk >= kPD + 1 tiles (checked by the launcher)
-  bf16x8 a[4][UB];                         // a[kk]: step kk of the current tile, then of the next
+  // a[s][kk][ub]: register set s holds step kk of K tile t for (t + nk) % kLead == s, and is
+  // re-filled fragment by fragment with tile t + kLead
+  bf16x8 a[kLead][4][UB];
   bf16x8 b[2][TB];
-  // ---- prologue: hidden tiles 0..kPD-1 in flight, A fragments of tile 0 ----
+  // ---- prologue: the A fragments of tiles 0..kLead-1, then hidden tiles 0..kPD-1 ----
+  auto load_tile_fragments = [&](auto set_, int tile) {
+    constexpr int set = decltype(set_)::value;
+    const unsigned char* sb = abase + (size_t)tile * kATile;
+    static_for<4 * UB>([&](auto g_) {
+      constexpr int kk = decltype(g_)::value / UB, ub = decltype(g_)::value % UB;
+      load_fragment<kk * 1024>(a[set][kk][ub], a_voff[ub], sb);
+    });
+  };
+  if constexpr (kLead == 1) {
+    load_tile_fragments(std::integral_constant<int, 0>{}, 0);
+  } else {
+    if (nk & 1) {
+      load_tile_fragments(std::integral_constant<int, 1>{}, 0);
+      load_tile_fragments(std::integral_constant<int, 0>{}, 1);
+    } else {
+      load_tile_fragments(std::integral_constant<int, 0>{}, 0);
+      load_tile_fragments(std::integral_constant<int, 1>{}, 1);
+    }
+  }
 #pragma unroll
   for (int d = 0; d < kPD; ++d)
 #pragma unroll
     for (int j = 0; j < NDJ; ++j) dma(j, d);
-  // same issue order as in the main loop (the compiler sizes its own waits on the A
-  // fragments by their position in the load stream, on both paths into the loop)
-#pragma unroll
-  for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-    for (int ub = 0; ub < UB; ++ub) {
-      a[kk][ub] = aload(0, ub, kk);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-  // hidden tile 0 = the four oldest operations; everything younger may stay in flight
+  // Everything but hidden tile kPD-1 must have arrived: the fragments (the first tiles' waits
+  // then hold whatever they count), hidden tile 0, and hidden tile 1, which tile 0's
+  // hand-over cannot count for because no whole tile of fragment loads follows it yet.
+  static_assert(kPD == 3, "the wait counts below are written for three hidden tiles in flight");
   __builtin_amdgcn_sched_barrier(0);
-  wait_vmcnt<NDJ * (kPD - 1) + 4 * UB>();
+  wait_vmcnt<NDJ>();
+#pragma unroll
+  for (int s2 = 0; s2 < kLead; ++s2)
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+      for (int ub = 0; ub < UB; ++ub) asm volatile("" : "+v"(a[s2][kk][ub]));
   block_barrier_no_drain();
 #pragma unroll
   for (int i = 0; i < kW2Pieces; ++i) {
@@ -443,94 +497,138 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
 #pragma unroll
   for (int tb = 0; tb < TB; ++tb) read_b(0, 0, 0, tb);
 
-  // One K tile.  MORE: tile t+1 exists; MORE_PD: tile t+kPD exists.  Both are compile-time
-  // so that the body is a single basic block whose instruction order is the source order.
+  // One K tile.  R = min(nk - t, kPD + 1) is a compile-time tag: it says which later tiles
+  // exist (t+1: hand-over; t+kLead: fragments to re-load; t+kPD: hidden tile to fetch) and
+  // which earlier tiles issued what, i.e. everything the wait counts depend on; the body is a
+  // single basic block whose instruction order is the source order.
   //
   // The hand-over to tile t+1 sits in the MIDDLE of tile t (before k-step 2), not at its
   // end: after that barrier the B reads of (t+1, step 0) are spread over k-step 3 like any
   // other step's, so no LDS latency is exposed between tiles, and the load-to-LDS of tile
   // t+kPD (which overwrites the stage of tile t-1, read for the last time before every
   // wavefront's arrival at this barrier) is issued during k-steps 2 and 3.
-  auto tile_body = [&](int t, auto more_tag, auto more_pd_tag) {
-    constexpr bool more = decltype(more_tag)::value, more_pd = decltype(more_pd_tag)::value;
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      if (more && kk == 2) {
-        // hidden tile t+1 must have landed.  Its load-to-LDS operations are followed in this
-        // wavefront's in-order vector-memory stream by at least one whole tile of A-fragment
-        // loads (4*UB) plus the 2*UB-1 issued so far in this tile (for tile 1: by the
-        // prologue's 4*UB and these), so allowing that many operations to stay outstanding
-        // is always sufficient.
-        wait_vmcnt<6 * UB - 1>();
+  //
+  // Vector-memory operations of a wavefront complete in issue order.  Per tile, in order:
+  //   group G = kk*UB + ub (0 .. 4*UB-1):  [load-to-LDS j of tile t+kPD, if G == dma_group(j)]
+  //                                        [wait for fragment G]  MFMAs  [load fragment G-1]
+  //   end of tile:                         [load fragment 4*UB-1]
+  // so the number of operations issued after fragment G's load (kLead tiles back) and before
+  // its wait is known at compile time, and that many may stay outstanding.
+  constexpr int NG = 4 * UB;
+  constexpr auto dma_group = [](int j) { return 2 * UB + j * 2 * UB / NDJ; };
+  constexpr auto dmas_between = [](int lo, int hi) {       // load-to-LDS groups in [lo, hi]
+    int n = 0;
+    for (int j = 0; j < NDJ; ++j) {
+      const int g = 2 * UB + j * 2 * UB / NDJ;
+      n += (g >= lo && g <= hi) ? 1 : 0;
+    }
+    return n;
+  };
+  auto tile_body = [&](int t, auto r_tag, auto set_tag) {
+    constexpr int R = decltype(r_tag)::value, set = decltype(set_tag)::value;
+    // what the tile d steps earlier does / did
+    constexpr auto has_pd = [](int d) { return R + d > kPD; };        // fetches hidden tile +kPD
+    constexpr auto has_more = [](int d) { return R + d > kLead; };    // re-loads fragments
+    constexpr bool next = R > 1, more = has_more(0), more_pd = has_pd(0);
+    const unsigned char* a_next = abase + (size_t)(t + kLead) * kATile;
+    static_for<NG>([&](auto g_) {
+      constexpr int G = decltype(g_)::value, kk = G / UB, ub = G % UB;
+      if constexpr (next && kk == 2 && ub == 0) {
+        // hidden tile t+1 must have landed.  Its last load-to-LDS (two tiles back, group
+        // dma_group(NDJ-1)) is followed by that tile's remaining fragment loads, the tile
+        // between and the 2*UB-1 fragment loads of this tile so far (load-to-LDS operations
+        // among them not counted: fewer allowed outstanding is the safe side).
+        constexpr int after = (has_more(2) ? NG - dma_group(NDJ - 1) + 1 : 0) + (has_more(1) ? NG : 0) +
+                              (more ? 2 * UB - 1 : 0);
+        wait_vmcnt<after>();
         block_barrier_no_drain();
       }
+      // B reads for the next step, (one hidden load-to-LDS), 4 MFMAs, then re-load an
+      // A fragment with data of tile t+kLead
+      if constexpr (kk < 3 || next) {
 #pragma unroll
-      for (int ub = 0; ub < UB; ++ub) {
-        // B reads for the next step, (one hidden load-to-LDS), 4 MFMAs, then re-load an
-        // A fragment with the next tile's data
-        if (kk < 3 || more) {
+        for (int tb = 0; tb < TB; ++tb)
+          if (tb * UB / TB == ub) {
+            if (kk < 3) read_b((kk + 1) & 1, t, kk + 1, tb);
+            else read_b(0, t + 1, 0, tb);
+          }
+      }
+      if constexpr (more_pd) {
 #pragma unroll
-          for (int tb = 0; tb < TB; ++tb)
-            if (tb * UB / TB == ub) {
-              if (kk < 3) read_b((kk + 1) & 1, t, kk + 1, tb);
-              else read_b(0, t + 1, 0, tb);
-            }
-        }
-        if (more_pd && kk >= 2) {
-          // the NDJ load-to-LDS instructions of tile t+kPD, spread over the 2*UB groups of
-          // k-steps 2 and 3
+        for (int j = 0; j < NDJ; ++j)
+          if (dma_group(j) == G) dma(j, t + kPD);
+      }
+      if constexpr (kNorm) {
+        // Sum of squares of the tokens' states: wavefront w owns token block w and reads that
+        // block's four fragments of the current tile from LDS once more, into registers of
+        // its own (the copy among its B fragments sits in a register only a compile-time
+        // index reaches), during K steps 0-1; the 16 two-element dot products follow in K
+        // steps 2-3.  No branch; the extra LDS reads ride in the MFMA shadow.
+        constexpr int kHalf = 2 * UB;                  // groups in half a tile
 #pragma unroll
-          for (int j = 0; j < NDJ; ++j)
-            if (j * 2 * UB / NDJ == (kk - 2) * UB + ub) dma(j, t + kPD);
-        }
-        if constexpr (kNorm) {
-          // Sum of squares of the tokens' states: wavefront w owns token block w and reads that
-          // block's four fragments of the current tile from LDS once more, into registers of
-          // its own (the copy among its B fragments sits in a register only a compile-time
-          // index reaches), during K steps 0-1; the 16 two-element dot products follow in K
-          // steps 2-3.  No branch; the extra LDS reads ride in the MFMA shadow.
-          constexpr int kHalf = 2 * UB;                  // groups in half a tile
-          const int G = kk * UB + ub;
+        for (int f = 0; f < 4; ++f) {
+          if (f * kHalf / 4 == G)
+            xb[f] = *reinterpret_cast<const bf16x8*>(smem + (t % kNS) * STAGE + lds_off(xrow, f * 2 + kg));
+          if (f * kHalf / 4 == G - kHalf) {
 #pragma unroll
-          for (int f = 0; f < 4; ++f) {
-            if (f * kHalf / 4 == G)
-              xb[f] = *reinterpret_cast<const bf16x8*>(smem + (t % kNS) * STAGE + lds_off(xrow, f * 2 + kg));
-            if (f * kHalf / 4 == G - kHalf) {
-#pragma unroll
-              for (int e = 0; e < 4; ++e) {
-                typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-                const bf16x2 p = {xb[f][2 * e], xb[f][2 * e + 1]};
-                ssq = __builtin_amdgcn_fdot2_f32_bf16(p, p, ssq, false);
-              }
+            for (int e = 0; e < 4; ++e) {
+              typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+              const bf16x2 p = {xb[f][2 * e], xb[f][2 * e + 1]};
+              ssq = __builtin_amdgcn_fdot2_f32_bf16(p, p, ssq, false);
             }
           }
         }
-        // token blocks in alternating direction: the MFMA that opens a group then keeps the B
-        // operand of the one before it (both operands switch at once otherwise); measured 1-2 %
-#pragma unroll
-        for (int i = 0; i < TB; ++i) {
-          const int tb = (ub & 1) ? TB - 1 - i : i;
-          acc[ub][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk][ub], b[kk & 1][tb],
-                                                                acc[ub][tb], 0, 0, 0);
-        }
-        // re-load the fragment of the PREVIOUS group: a load issued right behind the MFMAs
-        // that still read its destination registers costs extra issue cycles
-        if (more) {
-          if (ub > 0) a[kk][ub - 1] = aload(t + 1, ub - 1, kk);
-          else if (kk > 0) a[kk - 1][UB - 1] = aload(t + 1, UB - 1, kk - 1);
-        }
-        __builtin_amdgcn_sched_barrier(0);
       }
-    }
-    if (more) {
-      a[3][UB - 1] = aload(t + 1, UB - 1, 3);
+      {
+        // operations issued after this fragment's load: the rest of the tile that loaded it,
+        // (the tile between,) and this tile up to here
+        constexpr int after = (NG - 1 - G) + (has_pd(kLead) ? dmas_between(G + 2, NG) : 0) +
+                              (kLead == 2 ? (has_more(1) ? NG : 0) + (has_pd(1) ? NDJ : 0) : 0) +
+                              (more ? (G > 0 ? G - 1 : 0) : 0) + (more_pd ? dmas_between(0, G) : 0);
+        wait_fragment<after>(a[set][kk][ub]);
+      }
+      // token blocks in alternating direction: the MFMA that opens a group then keeps the B
+      // operand of the one before it (both operands switch at once otherwise); measured 1-2 %
+#pragma unroll
+      for (int i = 0; i < TB; ++i) {
+        const int tb = (ub & 1) ? TB - 1 - i : i;
+        acc[ub][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[set][kk][ub], b[kk & 1][tb],
+                                                              acc[ub][tb], 0, 0, 0);
+      }
+      // re-load the fragment of the PREVIOUS group: a load issued right behind the MFMAs
+      // that still read its destination registers costs extra issue cycles
+      if constexpr (more && G > 0) {
+        constexpr int pk = (G - 1) / UB, pu = (G - 1) % UB;
+        __builtin_amdgcn_sched_barrier(0);       // behind this group's MFMAs, not between the two
+        load_fragment<pk * 1024>(a[set][pk][pu], a_voff[pu], a_next);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    if constexpr (more) {
+      load_fragment<3 * 1024>(a[set][3][UB - 1], a_voff[UB - 1], a_next);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
-  int t = 0;
-  for (; t + kPD < nk; ++t) tile_body(t, std::true_type{}, std::true_type{});
-  for (; t + 1 < nk; ++t) tile_body(t, std::true_type{}, std::false_type{});
-  tile_body(t, std::false_type{}, std::false_type{});
+  // nk >= kPD + 1 (checked by the launcher): all tiles but the last kPD are of the full kind
+  {
+    using std::integral_constant;
+    constexpr integral_constant<int, 0> s0{};
+    constexpr integral_constant<int, kLead - 1> s1{};     // the set of the last tile
+    int t = 0;
+    if constexpr (kLead == 1) {
+      for (; t + kPD < nk; ++t) tile_body(t, integral_constant<int, kPD + 1>{}, s0);
+    } else {
+      // set of tile t = (t + nk) & 1: the last tile always uses set 1, whatever nk
+      if (!(nk & 1)) { tile_body(0, integral_constant<int, kPD + 1>{}, s0); t = 1; }
+      for (; t + kPD < nk; t += 2) {
+        tile_body(t, integral_constant<int, kPD + 1>{}, s1);
+        tile_body(t + 1, integral_constant<int, kPD + 1>{}, s0);
+      }
+    }
+    tile_body(nk - 3, integral_constant<int, 3>{}, s1);
+    tile_body(nk - 2, integral_constant<int, 2>{}, s0);
+    tile_body(nk - 1, integral_constant<int, 1>{}, s1);
+  }
   if constexpr (kSplit) {
     // split-K launch: the slice's part of the first projection goes to partial[slice][row][unit]
     // as it is; bias, GELU and the second projection follow in score_finish_kernel
