@@ -322,6 +322,20 @@ __device__ __forceinline__ void wait_fragment(bf16x8& frag) {
   asm volatile("s_waitcnt vmcnt(%1)" : "+v"(frag) : "n"(N));
 }
 
+// The same for a B fragment from LDS (16 bytes per lane at byte address addr + OFF): the
+// compiler places a wait for everything outstanding at the head of a loop whose entry and
+// back edge arrive with different reads in flight, which exposes the latency of the read
+// issued just before.  LDS operations of a wavefront complete in issue order.
+template <int OFF>
+__device__ __forceinline__ void read_fragment(bf16x8& dst, unsigned addr) {
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF));
+}
+template <int N>
+__device__ __forceinline__ void wait_lds_fragment(bf16x8& frag) {
+  static_assert(N >= 0 && N < 16, "lgkmcnt is a 4-bit counter");
+  asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(frag) : "n"(N));
+}
+
 // UB 32-unit blocks per wavefront, TB 32-token blocks per block; kSplit: the block covers one
 // K-slice (blockIdx.y) and writes its part of the first projection to `partial`
 template <int UB, int TB, bool kSplit, bool kNorm = false>
@@ -490,12 +504,22 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
 #pragma unroll
         for (int e = 0; e < 4; ++e) acc[ub][tb][4 * q + e] = v[e];
     }
-  auto read_b = [&](int buf, int tile, int kk, int tb) {
-    b[buf][tb] = *reinterpret_cast<const bf16x8*>(
-        smem + (tile % kNS) * STAGE + lds_off(32 * tb + l32, kk * 2 + kg));
-  };
+  // B fragment (step kk, token block tb) of a tile: lane (l32, kg) reads piece kk*2+kg of row
+  // 32*tb + l32; the swizzle depends on l32 and kk only, token blocks are 4 KB apart
+  unsigned b_off[4];
 #pragma unroll
-  for (int tb = 0; tb < TB; ++tb) read_b(0, 0, 0, tb);
+  for (int kk = 0; kk < 4; ++kk) b_off[kk] = lds0 + (unsigned)lds_off(l32, kk * 2 + kg);
+  auto read_b = [&](auto kk_, auto tb_, int tile) {          // into b[kk & 1][tb]
+    constexpr int kk = decltype(kk_)::value, tb = decltype(tb_)::value;
+    read_fragment<tb * 4096>(b[kk & 1][tb], b_off[kk] + (unsigned)((tile % kNS) * STAGE));
+  };
+  // the reads of step kk+1 are issued during step kk, token block tb's in group tb*UB/TB
+  constexpr auto reads_in_group = [](int ub) {
+    int n = 0;
+    for (int tb = 0; tb < TB; ++tb) n += (tb * UB / TB == ub) ? 1 : 0;
+    return n;
+  };
+  static_for<TB>([&](auto tb_) { read_b(std::integral_constant<int, 0>{}, tb_, 0); });
 
   // One K tile.  R = min(nk - t, kPD + 1) is a compile-time tag: it says which later tiles
   // exist (t+1: hand-over; t+kLead: fragments to re-load; t+kPD: hidden tile to fetch) and
@@ -545,13 +569,14 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
       }
       // B reads for the next step, (one hidden load-to-LDS), 4 MFMAs, then re-load an
       // A fragment with data of tile t+kLead
-      if constexpr (kk < 3 || next) {
-#pragma unroll
-        for (int tb = 0; tb < TB; ++tb)
-          if (tb * UB / TB == ub) {
-            if (kk < 3) read_b((kk + 1) & 1, t, kk + 1, tb);
-            else read_b(0, t + 1, 0, tb);
+      constexpr bool reads = kk < 3 || next;
+      if constexpr (reads) {
+        static_for<TB>([&](auto tb_) {
+          if constexpr (decltype(tb_)::value * UB / TB == ub) {
+            if constexpr (kk < 3) read_b(std::integral_constant<int, kk + 1>{}, tb_, t);
+            else read_b(std::integral_constant<int, 0>{}, tb_, t + 1);
           }
+        });
       }
       if constexpr (more_pd) {
 #pragma unroll
@@ -589,12 +614,19 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
       }
       // token blocks in alternating direction: the MFMA that opens a group then keeps the B
       // operand of the one before it (both operands switch at once otherwise); measured 1-2 %
-#pragma unroll
-      for (int i = 0; i < TB; ++i) {
-        const int tb = (ub & 1) ? TB - 1 - i : i;
+      static_for<TB>([&](auto i_) {
+        constexpr int tb = (ub & 1) ? TB - 1 - decltype(i_)::value : decltype(i_)::value;
+        if constexpr (ub == 0) {
+          // this step's B fragments were read during the step before; after token block tb's
+          // read came those of the higher blocks and this group's reads for the next step
+          wait_lds_fragment<(TB - 1 - tb) + (reads ? reads_in_group(0) : 0)>(b[kk & 1][tb]);
+        }
         acc[ub][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[set][kk][ub], b[kk & 1][tb],
                                                               acc[ub][tb], 0, 0, 0);
-      }
+        // keeps each wait directly in front of its MFMA (the waits would otherwise gather
+        // ahead of all four)
+        if constexpr (ub == 0 && decltype(i_)::value + 1 < TB) __builtin_amdgcn_sched_barrier(0);
+      });
       // re-load the fragment of the PREVIOUS group: a load issued right behind the MFMAs
       // that still read its destination registers costs extra issue cycles
       if constexpr (more && G > 0) {
