@@ -251,6 +251,7 @@ __global__ __launch_bounds__(kThreads) void score_mlp_kernel(
 //   * one barrier per 64-wide K tile; loads and LDS reads are interleaved
 //     between the MFMAs in source order and pinned with scheduling barriers.
 // ---------------------------------------------------------------------------
+constexpr int kChipCUs = 256;                // compute units of the part (8 XCDs x 32)
 constexpr int kPD = 3;                       // hidden tiles in flight
 constexpr int kNS = kPD + 1;                 // LDS stages
 
@@ -690,6 +691,24 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
     if (kg == 0 && wid < TB) sSsq[32 * wid + l32] = both;
   }
   __syncthreads();      // LDS is reused for the reduction below
+
+  if constexpr (!kSplit) {
+    // Warm the L2 for the block that starts on this CU when this one ends: workgroups go to
+    // the 8 XCDs round-robin and to a CU as it frees up, so with one block per CU that block is
+    // blockIdx.x + (number of CUs), on the same XCD and therefore behind the same L2.  One lane
+    // per 128-byte line of its first kPD hidden tiles.  The loaded dwords are never used, only
+    // where they leave the lines matters: they go to the ring's last stage, which nothing reads
+    // any more (the reduction below uses the first two), as load-to-LDS because an ordinary load
+    // would need a register that stays reserved until it returns.
+    const long long nrow0 = row0 + (long long)kChipCUs * TOK;
+#pragma unroll
+    for (int i0 = 0; i0 < kPD * TOK; i0 += 256) {
+      const int i = i0 + tid, d = i / TOK, r = i - d * TOK;
+      if (i < kPD * TOK && nrow0 + r < rows)
+        load_to_lds_b32(hidden + (size_t)(nrow0 + r) * Dh + (size_t)(kt0 + d) * kBK,
+                        lds0 + (unsigned)((kNS - 1) * STAGE + wid * 256));
+    }
+  }
 
   // ---- epilogue: GELU, then the M -> H projection as a second MFMA (fp16 operands) ----
   // acc[ub][tb][r] is z of unit  ubase + 32*ub + 8*(r/4) + 4*kg + r%4  of token 32*tb + l32.
