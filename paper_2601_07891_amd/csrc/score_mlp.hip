@@ -323,6 +323,27 @@ __device__ __forceinline__ void wait_fragment(bf16x8& frag) {
   asm volatile("s_waitcnt vmcnt(%1)" : "+v"(frag) : "n"(N));
 }
 
+// Small loads of the block's constants (W2, b1, b2), issued ahead of everything else and used
+// after the prologue's wait: issued by hand for the same reason -- the compiler, which does not
+// see the hand-issued operations behind them, would wait for ALL of those before the first
+// use.  Every lane loads, from an address clamped into the array, and what should not have been
+// loaded is zeroed after the wait: between a load and arrived() its destination must not pass
+// through a branch, where the compiler would copy the not yet written register.
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void load_async(u32x4& dst, const void* p) {
+  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(p));
+}
+__device__ __forceinline__ void load_async(u32x2& dst, const void* p) {
+  asm volatile("global_load_dwordx2 %0, %1, off" : "=v"(dst) : "v"(p));
+}
+__device__ __forceinline__ void load_async_u16(unsigned& dst, const void* p) {   // zero-extended
+  asm volatile("global_load_ushort %0, %1, off" : "=v"(dst) : "v"(p));
+}
+template <class T>
+__device__ __forceinline__ void arrived(T& v) {      // orders every use of v behind the wait before it
+  asm volatile("" : "+v"(v));
+}
+
 // The same for a B fragment from LDS (16 bytes per lane at byte address addr + OFF): the
 // compiler places a wait for everything outstanding at the head of a loop whose entry and
 // back edge arrive with different reads in flight, which exposes the latency of the read
@@ -368,24 +389,24 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
   u32x4 w2_stage[kW2Pieces];
 #pragma unroll
   for (int i = 0; i < kW2Pieces; ++i) {
-    const int piece = i * 256 + tid;
-    w2_stage[i] = piece < H * (U / 8) ? reinterpret_cast<const u32x4*>(W2)[piece] : u32x4{0u, 0u, 0u, 0u};
+    const int piece = i * 256 + tid, last = H * (U / 8) - 1;
+    load_async(w2_stage[i], reinterpret_cast<const u32x4*>(W2) + (piece < last ? piece : last));
   }
   // accumulator register 4q+e of block (ub, .) is unit wid*32*UB + 32*ub + 8*q + 4*kg + e
-  uint2 b1_stage[UB][4];
+  u32x2 b1_stage[UB][4];
   if constexpr (!kSplit) {
 #pragma unroll
     for (int ub = 0; ub < UB; ++ub)
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
-        b1_stage[ub][q] = b1 ? *reinterpret_cast<const uint2*>(b1 + wid * (32 * UB) + 32 * ub + 8 * q + 4 * kg)
-                             : uint2{0u, 0u};
+      for (int q = 0; q < 4; ++q)   // without b1: the same offsets into W2 (H*U >= U elements), zeroed later
+        load_async(b1_stage[ub][q], (b1 ? b1 : W2) + wid * (32 * UB) + 32 * ub + 8 * q + 4 * kg);
   }
 
   // b2 is loaded here and waits in LDS for the very end: a global load in the tail would
   // expose a memory round trip with nothing left to overlap it
   float* const sB2 = reinterpret_cast<float*>(sW2 + 16 * U * 2 + 2 * TOK * sizeof(float) + U * sizeof(float));   // [16]
-  const unsigned short b2_stage = (b2 && tid < H) ? b2[tid] : (unsigned short)0;
+  unsigned b2_stage;
+  load_async_u16(b2_stage, b2 ? b2 + (tid < H ? tid : 0) : W2);
 
   // hidden load-to-LDS: instruction j (0..3) of wavefront w fills LDS chunk j*4+w of a
   // stage = rows (j*4+w)*8 + lane/8, physical piece lane%8 <- logical piece (lane%8) ^ (row%8)
@@ -436,33 +457,58 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
       load_fragment<kk * 1024>(a[set][kk][ub], a_voff[ub], sb);
     });
   };
+  // Issue order: fragments of tile 0, hidden tiles 0 and 1, (fragments of tile 1,) hidden tile
+  // 2.  Everything up to hidden tile 1 must have arrived before tile 0 starts: its fragments,
+  // hidden tile 0, and hidden tile 1, which tile 0's hand-over cannot count for because no
+  // whole tile of fragment loads follows it yet.  Tile 1's fragments stay in flight; each is
+  // followed by hidden tile 2's NDJ operations, at least as many as tile_body() assumes behind
+  // a fragment's load.
+  static_assert(kPD == 3, "the wait counts are written for three hidden tiles in flight");
+  auto issue_hidden = [&](int d) {
+#pragma unroll
+    for (int j = 0; j < NDJ; ++j) dma(j, d);
+  };
   if constexpr (kLead == 1) {
     load_tile_fragments(std::integral_constant<int, 0>{}, 0);
+    issue_hidden(0); issue_hidden(1); issue_hidden(2);
+    __builtin_amdgcn_sched_barrier(0);
+    wait_vmcnt<NDJ>();
   } else {
     if (nk & 1) {
       load_tile_fragments(std::integral_constant<int, 1>{}, 0);
+      issue_hidden(0); issue_hidden(1);
       load_tile_fragments(std::integral_constant<int, 0>{}, 1);
     } else {
       load_tile_fragments(std::integral_constant<int, 0>{}, 0);
+      issue_hidden(0); issue_hidden(1);
       load_tile_fragments(std::integral_constant<int, 1>{}, 1);
     }
+    issue_hidden(2);
+    __builtin_amdgcn_sched_barrier(0);
+    wait_vmcnt<4 * UB + NDJ>();
   }
-#pragma unroll
-  for (int d = 0; d < kPD; ++d)
-#pragma unroll
-    for (int j = 0; j < NDJ; ++j) dma(j, d);
-  // Everything but hidden tile kPD-1 must have arrived: the fragments (the first tiles' waits
-  // then hold whatever they count), hidden tile 0, and hidden tile 1, which tile 0's
-  // hand-over cannot count for because no whole tile of fragment loads follows it yet.
-  static_assert(kPD == 3, "the wait counts below are written for three hidden tiles in flight");
-  __builtin_amdgcn_sched_barrier(0);
-  wait_vmcnt<NDJ>();
 #pragma unroll
   for (int s2 = 0; s2 < kLead; ++s2)
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-      for (int ub = 0; ub < UB; ++ub) asm volatile("" : "+v"(a[s2][kk][ub]));
+      for (int ub = 0; ub < UB; ++ub) arrived(a[s2][kk][ub]);
+#pragma unroll
+  for (int i = 0; i < kW2Pieces; ++i) {
+    arrived(w2_stage[i]);
+    if (i * 256 + tid >= H * (U / 8)) w2_stage[i] = u32x4{0u, 0u, 0u, 0u};
+  }
+  if constexpr (!kSplit) {
+#pragma unroll
+    for (int ub = 0; ub < UB; ++ub)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        arrived(b1_stage[ub][q]);
+        if (!b1) b1_stage[ub][q] = u32x2{0u, 0u};
+      }
+  }
+  arrived(b2_stage);
+  if (!b2 || tid >= H) b2_stage = 0u;
   block_barrier_no_drain();
 #pragma unroll
   for (int i = 0; i < kW2Pieces; ++i) {
@@ -474,7 +520,7 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
     }
     reinterpret_cast<f16x8*>(sW2)[i * 256 + tid] = w;
   }
-  if (tid < 16) sB2[tid] = bf16_bits_to_float(b2_stage);
+  if (tid < 16) sB2[tid] = bf16_bits_to_float((unsigned short)b2_stage);
   if constexpr (kNorm) {
     // b1 comes after the row scale: it waits in LDS for the epilogue instead of riding in
     // the accumulators (one lane of every 32 holds each unit's value)
