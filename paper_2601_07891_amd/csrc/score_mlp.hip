@@ -580,8 +580,9 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
   // wavefront's arrival at this barrier) is issued during k-steps 2 and 3.
   //
   // Vector-memory operations of a wavefront complete in issue order.  Per tile, in order:
-  //   group G = kk*UB + ub (0 .. 4*UB-1):  [load-to-LDS j of tile t+kPD, if G == dma_group(j)]
-  //                                        [wait for fragment G]  MFMAs  [load fragment G-1]
+  //   group G = kk*UB + ub (0 .. 4*UB-1):  [wait for fragment G]  MFMA  MFMA
+  //                                        [load-to-LDS j of tile t+kPD, if G == dma_group(j)]
+  //                                        MFMA  [load fragment G-1]  (MFMA)
   //   end of tile:                         [load fragment 4*UB-1]
   // so the number of operations issued after fragment G's load (kLead tiles back) and before
   // its wait is known at compile time, and that many may stay outstanding.
@@ -614,74 +615,78 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
         wait_vmcnt<after>();
         block_barrier_no_drain();
       }
-      // B reads for the next step, (one hidden load-to-LDS), 4 MFMAs, then re-load an
-      // A fragment with data of tile t+kLead
+      // The group's TB MFMAs with its other instructions spread between them, a few behind
+      // each MFMA (bunched at the group's head they take longer to issue than the MFMA before
+      // them runs, and the matrix pipe waits):
+      //   [wait: fragment G]  MFMA 0  [B reads for the next step]  MFMA 1  [load-to-LDS]
+      //   MFMA 2  [re-load fragment G-1 with tile t+kLead's data]  (MFMA 3)
       constexpr bool reads = kk < 3 || next;
-      if constexpr (reads) {
-        static_for<TB>([&](auto tb_) {
-          if constexpr (decltype(tb_)::value * UB / TB == ub) {
-            if constexpr (kk < 3) read_b(std::integral_constant<int, kk + 1>{}, tb_, t);
-            else read_b(std::integral_constant<int, 0>{}, tb_, t + 1);
-          }
-        });
-      }
-      if constexpr (more_pd) {
-#pragma unroll
-        for (int j = 0; j < NDJ; ++j)
-          if (dma_group(j) == G) dma(j, t + kPD);
-      }
-      if constexpr (kNorm) {
-        // Sum of squares of the tokens' states: wavefront w owns token block w and reads that
-        // block's four fragments of the current tile from LDS once more, into registers of
-        // its own (the copy among its B fragments sits in a register only a compile-time
-        // index reaches), during K steps 0-1; the 16 two-element dot products follow in K
-        // steps 2-3.  No branch; the extra LDS reads ride in the MFMA shadow.
-        constexpr int kHalf = 2 * UB;                  // groups in half a tile
-#pragma unroll
-        for (int f = 0; f < 4; ++f) {
-          if (f * kHalf / 4 == G)
-            xb[f] = *reinterpret_cast<const bf16x8*>(smem + (t % kNS) * STAGE + lds_off(xrow, f * 2 + kg));
-          if (f * kHalf / 4 == G - kHalf) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-              const bf16x2 p = {xb[f][2 * e], xb[f][2 * e + 1]};
-              ssq = __builtin_amdgcn_fdot2_f32_bf16(p, p, ssq, false);
-            }
-          }
-        }
-      }
       {
         // operations issued after this fragment's load: the rest of the tile that loaded it,
         // (the tile between,) and this tile up to here
         constexpr int after = (NG - 1 - G) + (has_pd(kLead) ? dmas_between(G + 2, NG) : 0) +
                               (kLead == 2 ? (has_more(1) ? NG : 0) + (has_pd(1) ? NDJ : 0) : 0) +
-                              (more ? (G > 0 ? G - 1 : 0) : 0) + (more_pd ? dmas_between(0, G) : 0);
+                              (more ? (G > 0 ? G - 1 : 0) : 0) + (more_pd ? dmas_between(0, G - 1) : 0);
         wait_fragment<after>(a[set][kk][ub]);
       }
       // token blocks in alternating direction: the MFMA that opens a group then keeps the B
       // operand of the one before it (both operands switch at once otherwise); measured 1-2 %
       static_for<TB>([&](auto i_) {
-        constexpr int tb = (ub & 1) ? TB - 1 - decltype(i_)::value : decltype(i_)::value;
+        constexpr int i = decltype(i_)::value, tb = (ub & 1) ? TB - 1 - i : i;
         if constexpr (ub == 0) {
           // this step's B fragments were read during the step before; after token block tb's
-          // read came those of the higher blocks and this group's reads for the next step
-          wait_lds_fragment<(TB - 1 - tb) + (reads ? reads_in_group(0) : 0)>(b[kk & 1][tb]);
+          // read came those of the higher blocks and (behind MFMA 0) this group's reads
+          wait_lds_fragment<(TB - 1 - tb) + ((reads && i > 0) ? reads_in_group(0) : 0)>(b[kk & 1][tb]);
         }
         acc[ub][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[set][kk][ub], b[kk & 1][tb],
                                                               acc[ub][tb], 0, 0, 0);
-        // keeps each wait directly in front of its MFMA (the waits would otherwise gather
-        // ahead of all four)
-        if constexpr (ub == 0 && decltype(i_)::value + 1 < TB) __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (i == 0 && reads) {
+          static_for<TB>([&](auto tb_) {
+            if constexpr (decltype(tb_)::value * UB / TB == ub) {
+              if constexpr (kk < 3) read_b(std::integral_constant<int, kk + 1>{}, tb_, t);
+              else read_b(std::integral_constant<int, 0>{}, tb_, t + 1);
+            }
+          });
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if constexpr (i == 1) {
+          if constexpr (more_pd) {
+#pragma unroll
+            for (int j = 0; j < NDJ; ++j)
+              if (dma_group(j) == G) dma(j, t + kPD);
+          }
+          if constexpr (kNorm) {
+            // Sum of squares of the tokens' states: wavefront w owns token block w and reads
+            // that block's four fragments of the current tile from LDS once more, into
+            // registers of its own (the copy among its B fragments sits in a register only a
+            // compile-time index reaches), during K steps 0-1; the 16 two-element dot
+            // products follow in K steps 2-3.  No branch; all in the MFMA shadow.
+            constexpr int kHalf = 2 * UB;                  // groups in half a tile
+#pragma unroll
+            for (int f = 0; f < 4; ++f) {
+              if (f * kHalf / 4 == G)
+                xb[f] = *reinterpret_cast<const bf16x8*>(smem + (t % kNS) * STAGE + lds_off(xrow, f * 2 + kg));
+              if (f * kHalf / 4 == G - kHalf) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+                  const bf16x2 p = {xb[f][2 * e], xb[f][2 * e + 1]};
+                  ssq = __builtin_amdgcn_fdot2_f32_bf16(p, p, ssq, false);
+                }
+              }
+            }
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        // the fragment of the PREVIOUS group: a load issued right behind the MFMAs that still
+        // read its destination registers costs extra issue cycles
+        if constexpr (i == 2 && more && G > 0) {
+          constexpr int pk = (G - 1) / UB, pu = (G - 1) % UB;
+          load_fragment<pk * 1024>(a[set][pk][pu], a_voff[pu], a_next);
+          __builtin_amdgcn_sched_barrier(0);
+        }
       });
-      // re-load the fragment of the PREVIOUS group: a load issued right behind the MFMAs
-      // that still read its destination registers costs extra issue cycles
-      if constexpr (more && G > 0) {
-        constexpr int pk = (G - 1) / UB, pu = (G - 1) % UB;
-        __builtin_amdgcn_sched_barrier(0);       // behind this group's MFMAs, not between the two
-        load_fragment<pk * 1024>(a[set][pk][pu], a_voff[pu], a_next);
-      }
-      __builtin_amdgcn_sched_barrier(0);
     });
     if constexpr (more) {
       load_fragment<3 * 1024>(a[set][3][UB - 1], a_voff[UB - 1], a_next);
