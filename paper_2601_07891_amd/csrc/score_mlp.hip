@@ -471,8 +471,6 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
   if constexpr (kLead == 1) {
     load_tile_fragments(std::integral_constant<int, 0>{}, 0);
     issue_hidden(0); issue_hidden(1); issue_hidden(2);
-    __builtin_amdgcn_sched_barrier(0);
-    wait_vmcnt<NDJ>();
   } else {
     if (nk & 1) {
       load_tile_fragments(std::integral_constant<int, 1>{}, 0);
@@ -484,15 +482,12 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
       load_tile_fragments(std::integral_constant<int, 1>{}, 1);
     }
     issue_hidden(2);
-    __builtin_amdgcn_sched_barrier(0);
-    wait_vmcnt<4 * UB + NDJ>();
   }
-#pragma unroll
-  for (int s2 = 0; s2 < kLead; ++s2)
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-      for (int ub = 0; ub < UB; ++ub) arrived(a[s2][kk][ub]);
+  // The block's constants were issued ahead of all that and arrive one L2 round trip later:
+  // they are converted and the accumulators are set while the fragments and the hidden tiles
+  // are still on their way.
+  __builtin_amdgcn_sched_barrier(0);
+  wait_vmcnt<kLead * 4 * UB + kPD * NDJ>();
 #pragma unroll
   for (int i = 0; i < kW2Pieces; ++i) {
     arrived(w2_stage[i]);
@@ -509,7 +504,6 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
   }
   arrived(b2_stage);
   if (!b2 || tid >= H) b2_stage = 0u;
-  block_barrier_no_drain();
 #pragma unroll
   for (int i = 0; i < kW2Pieces; ++i) {
     f16x8 w;
@@ -551,6 +545,16 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
 #pragma unroll
         for (int e = 0; e < 4; ++e) acc[ub][tb][4 * q + e] = v[e];
     }
+  // now everything up to hidden tile 1 (all but tile 1's fragments and hidden tile 2)
+  __builtin_amdgcn_sched_barrier(0);
+  wait_vmcnt<(kLead - 1) * 4 * UB + NDJ>();
+#pragma unroll
+  for (int s2 = 0; s2 < kLead; ++s2)
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+      for (int ub = 0; ub < UB; ++ub) arrived(a[s2][kk][ub]);
+  block_barrier_no_drain();
   // B fragment (step kk, token block tb) of a tile: lane (l32, kg) reads piece kk*2+kg of row
   // 32*tb + l32; the swizzle depends on l32 and kk only, token blocks are 4 KB apart
   unsigned b_off[4];
