@@ -69,6 +69,14 @@ __device__ __forceinline__ void load_to_lds_b128(const void* gptr, unsigned lds_
                : "memory");
 }
 
+// The same with the non-temporal hint: for data that is read once (streamed), so that it
+// does not push re-used lines out of the L2.
+__device__ __forceinline__ void load_to_lds_b128_stream(const void* gptr, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt"
+               ::"s"(lds_base), "v"(gptr)
+               : "memory");
+}
+
 __device__ __forceinline__ unsigned lds_address(const void* p) {
   return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
 }

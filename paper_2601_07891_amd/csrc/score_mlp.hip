@@ -423,7 +423,10 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
   }
   const unsigned lds0 = lds_address(smem);
   auto dma = [&](int j, int tile) {
-    load_to_lds_b128(hb + (size_t)tile * (kBK * 2) + h_off[j],
+    // streamed: every hidden byte is read once, while the W1 fragments all blocks share have to
+    // stay in the same L2 (with the plain policy a ninth of the launch's HBM reads was W1 coming
+    // back after eviction)
+    load_to_lds_b128_stream(hb + (size_t)tile * (kBK * 2) + h_off[j],
                      lds0 + (unsigned)((tile % kNS) * STAGE + (j * 4 + wid) * 1024));
   };
   // A fragments of this wavefront: unit blocks rb = wid*UB + ub; fragment (ub, kk) of K tile t
