@@ -2,9 +2,15 @@
 from __future__ import annotations
 
 import os
+import shutil
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
+
+try:
+    from .isa_lint import lint_scorer_asm
+except ImportError:        # run as a script
+    from isa_lint import lint_scorer_asm
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
@@ -22,14 +28,45 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",
          "-Wall", "-Wno-unused-command-line-argument"]
 
 
+# sources whose device assembly is checked after compilation (see isa_lint.py)
+LINTED = {"score_mlp.hip"}
+
+
+def _quiet(stderr: str) -> str:
+    # hipcc's host pass does not know the device-only target feature and says so for every
+    # function; anything else is passed on
+    return "\n".join(l for l in stderr.splitlines() if "packed-fp32-ops" not in l).strip()
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ_DIR, src.replace(".hip", ".o"))
     cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    tmp = None
+    if src in LINTED:     # keep the intermediate device assembly of this one compile
+        tmp = os.path.join(OBJ_DIR, "lint_" + src.replace(".hip", ""))
+        shutil.rmtree(tmp, ignore_errors=True)
+        os.makedirs(tmp)
+        cmd = [HIPCC, *FLAGS, "-save-temps=obj", "-c", os.path.join(CSRC, src), "-o",
+               os.path.join(tmp, os.path.basename(obj))]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed for {src}:\n{r.stdout}\n{r.stderr}")
-    if r.stderr.strip():
-        sys.stderr.write(r.stderr)
+    if _quiet(r.stderr):
+        sys.stderr.write(_quiet(r.stderr) + "\n")
+    if tmp:
+        try:
+            asm = [f for f in os.listdir(tmp) if f.endswith(".s") and "amdgcn" in f]
+            if len(asm) != 1:
+                raise RuntimeError(f"expected one device assembly file for {src}, found {asm}")
+            with open(os.path.join(tmp, asm[0])) as fh:
+                findings = lint_scorer_asm(fh.read())
+            bad = {k: v for k, v in findings.items() if v}
+            if bad:
+                msg = "\n".join(f"{k}: {len(v)} (first: {v[0][1]})" for k, v in bad.items())
+                raise RuntimeError(f"{src}: registers of outstanding loads are touched:\n{msg}")
+            os.replace(os.path.join(tmp, os.path.basename(obj)), obj)
+        finally:
+            shutil.rmtree(tmp, ignore_errors=True)
     return obj
 
 
