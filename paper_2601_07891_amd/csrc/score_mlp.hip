@@ -320,7 +320,9 @@ __device__ __forceinline__ void load_fragment(bf16x8& dst, unsigned voff, const 
 template <int N>
 __device__ __forceinline__ void wait_fragment(bf16x8& frag) {
   static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-  asm volatile("s_waitcnt vmcnt(%1)" : "+v"(frag) : "n"(N));
+  (void)frag;
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N));
+  __builtin_amdgcn_sched_barrier(0);
 }
 
 // Small loads of the block's constants (W2, b1, b2), issued ahead of everything else and used
@@ -355,7 +357,9 @@ __device__ __forceinline__ void read_fragment(bf16x8& dst, unsigned addr) {
 template <int N>
 __device__ __forceinline__ void wait_lds_fragment(bf16x8& frag) {
   static_assert(N >= 0 && N < 16, "lgkmcnt is a 4-bit counter");
-  asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(frag) : "n"(N));
+  (void)frag;
+  asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N));
+  __builtin_amdgcn_sched_barrier(0);
 }
 
 // UB 32-unit blocks per wavefront, TB 32-token blocks per block; kSplit: the block covers one
