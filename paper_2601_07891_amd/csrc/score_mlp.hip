@@ -233,23 +233,28 @@ __global__ __launch_bounds__(kThreads) void score_mlp_kernel(
 
 
 // ---------------------------------------------------------------------------
-// Main variant (D_h >= 256).  A 128k-token launch moves 4.3 TB of W1 operands from L2 to
+// Main variant (D_h >= 256).  A 128k-token launch moves 4.3 GB of W1 operands from L2 to
 // the CUs and 1 GB of hidden states from HBM; the structure keeps both off the matrix
-// cores' critical path (timing-only variants without either stream are 0-2 % and 6 %
-// faster), and W1 never passes through LDS:
+// cores' critical path, and W1 never passes through LDS:
 //   * a tiny pre-pass copies W1 into the workspace in MFMA A-fragment order
 //     ([k-tile][32-unit block][k-step][lane] x 16 B), so that every A fragment
 //     is ONE fully coalesced 1 KB load straight into registers;
 //   * each of the 4 wavefronts owns M/4 units x all 128 tokens (UB x 4
-//     accumulator blocks in the accumulation registers) and keeps a ring of
-//     one K tile of its own A fragments in registers: a fragment is re-loaded
-//     with the next tile's data right after its MFMAs, i.e. one tile ahead;
+//     accumulator blocks in the accumulation registers) and keeps up to two K tiles
+//     of its own A fragments in registers: a fragment is re-loaded with the data of
+//     tile t+2 one MFMA group after its last use;
 //   * only `hidden` goes through LDS: a ring of kPD+1 stages of 128 rows x
 //     128 B filled by load-to-LDS kPD tiles ahead (it is the HBM-latency
 //     stream), rows swizzled by XOR-ing the 16-byte piece index with row & 7
 //     on the global-address side;
-//   * one barrier per 64-wide K tile; loads and LDS reads are interleaved
-//     between the MFMAs in source order and pinned with scheduling barriers.
+//   * one barrier per 64-wide K tile; loads and LDS reads sit between the MFMAs in
+//     source order, pinned with scheduling barriers;
+//   * every operand load is issued as inline asm and waited for with a count that is a
+//     constant expression of that fixed order (the compiler's own counts do not see the
+//     load-to-LDS operations in the same in-order queue and always wait for too much).
+//     To the compiler such a load has written its register when it is issued: the build
+//     checks the generated assembly for any use of a register before its wait
+//     (isa_lint.py), and no branch may sit between such a load and its wait.
 // ---------------------------------------------------------------------------
 constexpr int kChipCUs = 256;                // compute units of the part (8 XCDs x 32)
 constexpr int kPD = 3;                       // hidden tiles in flight

@@ -10,7 +10,10 @@ a vector register while a load into it can still be outstanding by the wait inst
 so far.  `build.py` runs it on every build and fails the build on a finding.
 
 The walk is linear (program order as laid out, branches ignored) and models the two in-order
-queues of a wavefront: vector memory (`vmcnt`) and LDS/scalar memory (`lgkmcnt`)."""
+queues of a wavefront: vector memory (`vmcnt`) and LDS/scalar memory (`lgkmcnt`).  Because the
+two arms of a branch are laid out one after the other, loads of the first arm still count as
+outstanding in the second: a finding there can be a false one (it was, for a configuration
+that is not built).  A finding stops the build so that the listing gets read."""
 from __future__ import annotations
 
 import re
