@@ -72,7 +72,14 @@ def test_linear_one_hot_weights_pick_columns():
 MLP_SHAPES = [(1, 300, 256, 128, 8), (2, 129, 1024, 128, 8), (1, 1000, 4096, 512, 8),
               (1, 257, 5120, 640, 8), (1, 64, 2048, 256, 3), (1, 1, 3072, 384, 16),
               (3, 50, 4096, 512, 8), (1, 200, 448, 128, 8), (2, 70, 320, 256, 4),   # odd K-tile counts
-              (1, 97, 256, 640, 8), (1, 500, 192, 512, 8)]                          # 4 tiles; D_h < 256
+              (1, 97, 256, 640, 8), (1, 500, 192, 512, 8),                          # 4 tiles; D_h < 256
+              # the single kernel keeps two K tiles of W1 fragments in flight in alternating
+              # register sets: odd and even tile counts at every unit-block count, 5 to 65 tiles
+              (1, 300, 4160, 512, 8), (1, 260, 384, 512, 8), (1, 150, 576, 384, 8),
+              (1, 140, 320, 128, 8), (1, 131, 5184, 640, 8),
+              # more than one block per CU and a ragged last block: blocks touch the first hidden
+              # tiles of the block 256 further on, up to the end of the input and not beyond
+              (1, 40077, 1024, 128, 8), (2, 16500, 512, 256, 8)]
 
 
 # kvzap_score splits the first projection of short and mid-length prompts (a skinny GEMM up
