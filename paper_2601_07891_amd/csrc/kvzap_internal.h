@@ -77,6 +77,15 @@ __device__ __forceinline__ void load_to_lds_b128_stream(const void* gptr, unsign
                : "memory");
 }
 
+// ... and with the address as a uniform 64-bit base (scalar registers) plus a 32-bit offset per
+// lane: no 64-bit vector add per instruction when only the base moves from tile to tile.
+__device__ __forceinline__ void load_to_lds_b128_stream(const void* base, unsigned lane_offset,
+                                                        unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt"
+               ::"s"(lds_base), "v"(lane_offset), "s"(base)
+               : "memory");
+}
+
 __device__ __forceinline__ unsigned lds_address(const void* p) {
   return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
 }

@@ -432,11 +432,10 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
   }
   const unsigned lds0 = lds_address(smem);
   auto dma = [&](int j, int tile) {
-    // streamed: every hidden byte is read once, while the W1 fragments all blocks share have to
-    // stay in the same L2 (with the plain policy a ninth of the launch's HBM reads was W1 coming
-    // back after eviction)
-    load_to_lds_b128_stream(hb + (size_t)tile * (kBK * 2) + h_off[j],
-                     lds0 + (unsigned)((tile % kNS) * STAGE + (j * 4 + wid) * 1024));
+    // streamed (non-temporal): every hidden byte is read once, while the W1 fragments that all
+    // blocks share have to stay in the same L2; measured 2 % on the launch
+    load_to_lds_b128_stream(hb + (size_t)tile * (kBK * 2), h_off[j],
+                            lds0 + (unsigned)((tile % kNS) * STAGE + (j * 4 + wid) * 1024));
   };
   // A fragments of this wavefront: unit blocks rb = wid*UB + ub; fragment (ub, kk) of K tile t
   // is the KB at  abase + t*kATile + (ub*4 + kk)*1024, 16 bytes per lane.  They are loaded
