@@ -13,7 +13,11 @@ The walk is linear (program order as laid out, branches ignored) and models the 
 queues of a wavefront: vector memory (`vmcnt`) and LDS/scalar memory (`lgkmcnt`).  Because the
 two arms of a branch are laid out one after the other, loads of the first arm still count as
 outstanding in the second: a finding there can be a false one (it was, for a configuration
-that is not built).  A finding stops the build so that the listing gets read."""
+that is not built).  Following the branches instead does not help as it stands: the kernel
+decides the parity of its K-tile count twice (which register set gets tile 0; whether one tile
+runs ahead of the pair loop), and a walk over all paths takes the two impossible combinations
+as well and reports their mismatched counts.  A finding stops the build so that the listing
+gets read."""
 from __future__ import annotations
 
 import re
