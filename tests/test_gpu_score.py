@@ -106,6 +106,34 @@ def test_mlp_random(B, T, Dh, M, H, entry):
     assert err < 5e-3
 
 
+def test_mlp_randomised_shapes():
+    # 30 seeded shapes through the one-kernel path (kvzap_score_prepared) and through
+    # kvzap_score: every unit-block count, 4 to 40 K tiles (odd and even), 1 to 16 heads,
+    # ragged token counts, with and without the biases
+    rng = np.random.default_rng(7)
+    for case in range(30):
+        M = int(rng.choice([128, 256, 384, 512, 640]))
+        Dh = 64 * int(rng.integers(4, 41))
+        H = int(rng.integers(1, 17))
+        B = int(rng.integers(1, 4))
+        T = int(rng.choice([1, 31, 96, 127, 128, 129, 300, 517, 1000]))
+        g = torch.Generator().manual_seed(1000 + case)
+        bias = bool(rng.integers(0, 2))
+        w = {"W1": (torch.randn((M, Dh), generator=g) * Dh ** -0.5).bfloat16(),
+             "b1": (torch.randn((M,), generator=g) * 0.3).bfloat16() if bias else None,
+             "W2": (torch.randn((H, M), generator=g) * M ** -0.5).bfloat16(),
+             "b2": (torch.randn((H,), generator=g) * 0.3).bfloat16() if bias else None}
+        wl = synth.Workload("t", L=1, B=B, T=T, Dh=Dh, H=H, scorer="mlp", seed=case)
+        hid = synth.make_hidden(wl)
+        d = _dev(w)
+        want = _oracle_scores(hid, w)
+        got = binding.kvzap_score_prepared(hid.to(DEV), binding.kvzap_prepare_scorer(d["W1"]), d["b1"],
+                                           d["W2"], d["b2"])
+        torch.cuda.synchronize()
+        parity.assert_scores_close(got, want)
+        parity.assert_scores_close(_gpu_scores(hid, w), want)
+
+
 @pytest.mark.parametrize("B,T,Dh,M,H", [(1, 1024 + 77, 4096, 512, 8), (3, 731, 1024, 128, 8),
                                         (1, 1025, 5120, 640, 8), (1, 900, 2048, 256, 3),
                                         (1, 700, 3072, 384, 16), (1, 20000, 4096, 512, 8)])
