@@ -321,7 +321,9 @@ __device__ __forceinline__ void load_fragment(bf16x8& dst, unsigned voff, const 
   asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3" : "=v"(dst) : "v"(voff), "s"(sbase), "n"(OFF));
 }
 // Wait until at most N vector-memory operations issued after the fragment's load are still
-// outstanding; the fragment is an in/out operand so that no use of it moves above the wait.
+// outstanding.  A scheduling barrier keeps every use of the fragment behind the wait (a register
+// tie would do that too, but costs a hazard s_nop after each wait); the build's check of the
+// generated assembly is what holds it to that.
 template <int N>
 __device__ __forceinline__ void wait_fragment(bf16x8& frag) {
   static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
@@ -391,8 +393,8 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
   // fp16 and zero-filled up to 16 heads: read from global memory in the epilogue, every one of
   // its small loads would expose a full memory round trip with nothing to overlap it.  b1 is
   // what the accumulators start from.  Both are loaded here, ahead of the prologue's traffic,
-  // and used once the prologue has waited for hidden tile 0 (vector-memory operations
-  // complete in issue order).
+  // and used as soon as they have arrived, while that traffic is still on its way
+  // (vector-memory operations complete in issue order).
   constexpr int kW2Pieces = U / 128;                    // 16-byte pieces of the 16 x U matrix per thread
   unsigned char* const sW2 = smem + kNS * STAGE;        // [16][U] fp16
   u32x4 w2_stage[kW2Pieces];
