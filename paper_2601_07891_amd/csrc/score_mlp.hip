@@ -25,6 +25,7 @@
 #include <type_traits>
 #include <utility>
 
+#include "frag_schedule.h"
 #include "kvzap_internal.h"
 
 namespace kvzap {
@@ -560,7 +561,7 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
     }
   // now everything up to hidden tile 1 (all but tile 1's fragments and hidden tile 2)
   __builtin_amdgcn_sched_barrier(0);
-  wait_vmcnt<(kLead - 1) * 4 * UB + NDJ>();
+  wait_vmcnt<frag::prologue_wait(UB, NDJ, kLead)>();
 #pragma unroll
   for (int s2 = 0; s2 < kLead; ++s2)
 #pragma unroll
@@ -603,33 +604,19 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
   //   end of tile:                         [load fragment 4*UB-1]
   // so the number of operations issued after fragment G's load (kLead tiles back) and before
   // its wait is known at compile time, and that many may stay outstanding.
-  constexpr int NG = 4 * UB;
-  constexpr auto dma_group = [](int j) { return 2 * UB + j * 2 * UB / NDJ; };
-  constexpr auto dmas_between = [](int lo, int hi) {       // load-to-LDS groups in [lo, hi]
-    int n = 0;
-    for (int j = 0; j < NDJ; ++j) {
-      const int g = 2 * UB + j * 2 * UB / NDJ;
-      n += (g >= lo && g <= hi) ? 1 : 0;
-    }
-    return n;
-  };
+  // The counts live in frag_schedule.h (a host test simulates the queue against them).
+  constexpr int NG = frag::groups(UB);
+  static_assert(frag::kHiddenAhead == kPD, "one constant, two names");
+  static_assert(frag::lead_is_safe(UB, NDJ, kLead), "tile 1's hand-over is not covered with this shape");
   auto tile_body = [&](int t, auto r_tag, auto set_tag) {
     constexpr int R = decltype(r_tag)::value, set = decltype(set_tag)::value;
-    // what the tile d steps earlier does / did
-    constexpr auto has_pd = [](int d) { return R + d > kPD; };        // fetches hidden tile +kPD
-    constexpr auto has_more = [](int d) { return R + d > kLead; };    // re-loads fragments
-    constexpr bool next = R > 1, more = has_more(0), more_pd = has_pd(0);
+    constexpr bool next = R > 1, more = frag::reloads_fragments(R, 0, kLead),
+                   more_pd = frag::fetches_hidden(R, 0);
     const unsigned char* a_next = abase + (size_t)(t + kLead) * kATile;
     static_for<NG>([&](auto g_) {
       constexpr int G = decltype(g_)::value, kk = G / UB, ub = G % UB;
-      if constexpr (next && kk == 2 && ub == 0) {
-        // hidden tile t+1 must have landed.  Its last load-to-LDS (two tiles back, group
-        // dma_group(NDJ-1)) is followed by that tile's remaining fragment loads, the tile
-        // between and the 2*UB-1 fragment loads of this tile so far (load-to-LDS operations
-        // among them not counted: fewer allowed outstanding is the safe side).
-        constexpr int after = (has_more(2) ? NG - dma_group(NDJ - 1) + 1 : 0) + (has_more(1) ? NG : 0) +
-                              (more ? 2 * UB - 1 : 0);
-        wait_vmcnt<after>();
+      if constexpr (next && kk == 2 && ub == 0) {      // hidden tile t+1 must have landed
+        wait_vmcnt<frag::handover_wait(UB, NDJ, kLead, R)>();
         block_barrier_no_drain();
       }
       // The group's TB MFMAs with its other instructions spread between them, a few behind
@@ -638,14 +625,7 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
       //   [wait: fragment G]  MFMA 0  [B reads for the next step]  MFMA 1  [load-to-LDS]
       //   MFMA 2  [re-load fragment G-1 with tile t+kLead's data]  (MFMA 3)
       constexpr bool reads = kk < 3 || next;
-      {
-        // operations issued after this fragment's load: the rest of the tile that loaded it,
-        // (the tile between,) and this tile up to here
-        constexpr int after = (NG - 1 - G) + (has_pd(kLead) ? dmas_between(G + 2, NG) : 0) +
-                              (kLead == 2 ? (has_more(1) ? NG : 0) + (has_pd(1) ? NDJ : 0) : 0) +
-                              (more ? (G > 0 ? G - 1 : 0) : 0) + (more_pd ? dmas_between(0, G - 1) : 0);
-        wait_fragment<after>(a[set][kk][ub]);
-      }
+      wait_fragment<frag::fragment_wait(UB, NDJ, kLead, R, G)>(a[set][kk][ub]);
       // token blocks in alternating direction: the MFMA that opens a group then keeps the B
       // operand of the one before it (both operands switch at once otherwise); measured 1-2 %
       static_for<TB>([&](auto i_) {
@@ -671,7 +651,7 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
           if constexpr (more_pd) {
 #pragma unroll
             for (int j = 0; j < NDJ; ++j)
-              if (dma_group(j) == G) dma(j, t + kPD);
+              if (frag::dma_group(UB, NDJ, j) == G) dma(j, t + kPD);
           }
           if constexpr (kNorm) {
             // Sum of squares of the tokens' states: wavefront w owns token block w and reads
