@@ -71,8 +71,14 @@ __device__ __forceinline__ float gelu_fused(float z) {
   return z * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
+// LDS tile of 128-byte rows (eight 16-byte pieces): byte offset of logical piece `piece` of
+// `row`.  The piece index is XOR-ed with bits 1..3 of the row: a ds_read_b128 serves 16 lanes
+// (16 consecutive rows, one piece each) at a time, and with two rows per 256 bytes of banks
+// the 16 accesses then fall on 16 different 16-byte bank groups (with row & 7 rows r and r+8
+// met in the same group).
+__device__ __forceinline__ int lds_swizzle(int row) { return (row >> 1) & 7; }
 __device__ __forceinline__ int lds_off(int row, int piece) {   // bytes
-  return row * 128 + ((piece ^ (row & 7)) << 4);
+  return row * 128 + ((piece ^ lds_swizzle(row)) << 4);
 }
 
 template <int UB>
@@ -246,7 +252,7 @@ __global__ __launch_bounds__(kThreads) void score_mlp_kernel(
 //     tile t+2 one MFMA group after its last use;
 //   * only `hidden` goes through LDS: a ring of kPD+1 stages of 128 rows x
 //     128 B filled by load-to-LDS kPD tiles ahead (it is the HBM-latency
-//     stream), rows swizzled by XOR-ing the 16-byte piece index with row & 7
+//     stream), rows swizzled by XOR-ing the 16-byte piece index with bits 1..3 of the row
 //     on the global-address side;
 //   * one barrier per 64-wide K tile; loads and LDS reads sit between the MFMAs in
 //     source order, pinned with scheduling barriers;
@@ -421,7 +427,7 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
   load_async_u16(b2_stage, b2 ? b2 + (tid < H ? tid : 0) : W2);
 
   // hidden load-to-LDS: instruction j (0..3) of wavefront w fills LDS chunk j*4+w of a
-  // stage = rows (j*4+w)*8 + lane/8, physical piece lane%8 <- logical piece (lane%8) ^ (row%8)
+  // stage = rows (j*4+w)*8 + lane/8, physical piece lane%8 <- logical piece (lane%8) ^ lds_swizzle(row)
   // blockIdx.y: the K-slice of nk tiles this block covers (one slice unless `partial` is set)
   const int kt0 = kSplit ? blockIdx.y * nk : 0;
   const unsigned char* hb = reinterpret_cast<const unsigned char*>(hidden + (size_t)row0 * Dh) + (size_t)kt0 * (kBK * 2);
@@ -429,7 +435,7 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
 #pragma unroll
   for (int j = 0; j < NDJ; ++j) {
     int r = (j * 4 + wid) * 8 + (lane >> 3);
-    const int p = (lane & 7) ^ (r & 7);
+    const int p = (lane & 7) ^ lds_swizzle(r);
     if (r > rows_here - 1) r = rows_here - 1;            // clamp: in bounds, result discarded
     h_off[j] = (unsigned)r * (unsigned)Dh * 2u + (unsigned)p * 16u;
   }
