@@ -33,7 +33,7 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 TRAFFIC_SOURCE = {"c3_qwen8b_128k_mlp": "constant from profiles/c3_hbm_traffic.txt",
                   "c5_qwen8b_decode+attend": "constant from profiles/c5_attend_hbm_traffic.txt"}
 MEASURED_HBM_TRAFFIC = {
-    ("c3_qwen8b_128k_mlp", "score_mlp_frag_kernel"): 1213.7e6 + 4.2e6,
+    ("c3_qwen8b_128k_mlp", "score_mlp_frag_kernel"): 1213.9e6 + 4.2e6,
     ("c3_qwen8b_128k_mlp", "compact_kernel"): 146.5e6 + 143.3e6,
     # profiles/c5_attend_hbm_traffic.txt (default rows-per-head range, 32 query heads)
     ("c5_qwen8b_decode+attend", "attend_partial_kernel"): 4926.1e6 + 10.4e6,
