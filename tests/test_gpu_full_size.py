@@ -81,6 +81,27 @@ def test_config4_full_layer_linear():
     _full_size_case("c4_qwen32b_4x64k_linear")
 
 
+def test_config3_scores_repeat_bit_for_bit_under_load():
+    """The single-kernel scorer at the benchmark's size (1024 blocks, four per CU, every block
+    warming the L2 for a later one, operand loads waited for by hand-counted s_waitcnt): twelve
+    launches back to back on the same input, alternating with launches on another input so that
+    the chip stays busy, give the same bits every time.  A wait that is one operation short
+    shows up here as a score that differs between launches."""
+    wl = synth.CONFIGS["c3_qwen8b_128k_mlp"]
+    w = synth.make_weights(wl, 0, DEV)
+    hid = synth.make_hidden(wl, 0, DEV)
+    other = synth.make_hidden(wl, 1, DEV)
+    prep = binding.kvzap_prepare_scorer(w["W1"])
+    first = binding.kvzap_score_prepared(hid, prep, w["b1"], w["W2"], w["b2"]).clone()
+    outs = []
+    for i in range(12):
+        binding.kvzap_score_prepared(other, prep, w["b1"], w["W2"], w["b2"])
+        outs.append(binding.kvzap_score_prepared(hid, prep, w["b1"], w["W2"], w["b2"]).clone())
+    torch.cuda.synchronize()
+    for o in outs:
+        assert torch.equal(o.view(torch.int32), first.view(torch.int32))
+
+
 def test_decode_attention_at_the_benchmark_shape():
     """kvzap_attend_decode at the decode workload's cache shape (64 sequences x 8 KV heads of
     4096..32768 rows + a full 128-row ring, 32 query heads), as bench.py launches it; the
