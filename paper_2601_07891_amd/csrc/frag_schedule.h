@@ -6,7 +6,7 @@
 // NG = 4*UB MFMA groups G = (k-step, unit block), the wavefront issues, in this order:
 //
 //   group G:      [hand-over wait, only at G == 2*UB]
-//                 [wait for A fragment G of this tile]            MFMA  MFMA
+//                 [wait for A fragments G and G+1 of this tile, G even]   MFMA  MFMA
 //                 [load-to-LDS j of hidden tile t+3, if G == dma_group(j)]   (tile t+3 exists)
 //                 MFMA  [load A fragment G-1 of tile t+lead]  (MFMA)         (tile t+lead exists)
 //   end of tile:  [load A fragment NG-1 of tile t+lead]
@@ -44,6 +44,16 @@ constexpr int fragment_wait(int UB, int NDJ, int lead, int R, int G) {
   n += (reloads_fragments(R, 0, lead) ? (G > 0 ? G - 1 : 0) : 0) +
        (fetches_hidden(R, 0) ? dmas_between(UB, NDJ, 0, G - 1) : 0);
   return n;
+}
+
+// One wait for two fragments: issued in front of an even group G it covers G and G+1 (groups
+// come in pairs: 4*UB is even), so the odd group needs none.  Fragment G+1's load is the younger
+// of the two; between this wait and where G+1's own wait would sit, group G issues its
+// load-to-LDS operations (if it has any) and the re-load of fragment G-1.
+constexpr int fragment_pair_wait(int UB, int NDJ, int lead, int R, int G) {
+  const int in_group = (fetches_hidden(R, 0) ? dmas_between(UB, NDJ, G, G) : 0) +
+                       ((reloads_fragments(R, 0, lead) && G > 0) ? 1 : 0);
+  return fragment_wait(UB, NDJ, lead, R, G + 1) - in_group;
 }
 
 // The hand-over in the middle of a tile of kind R > 1: hidden tile t+1 must have landed.  Its

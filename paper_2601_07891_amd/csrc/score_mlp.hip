@@ -631,15 +631,17 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
       //   [wait: fragment G]  MFMA 0  [B reads for the next step]  MFMA 1  [load-to-LDS]
       //   MFMA 2  [re-load fragment G-1 with tile t+kLead's data]  (MFMA 3)
       constexpr bool reads = kk < 3 || next;
-      wait_fragment<frag::fragment_wait(UB, NDJ, kLead, R, G)>(a[set][kk][ub]);
+      // one wait per pair of groups (every instruction between the MFMAs costs issue time)
+      if constexpr (G % 2 == 0) wait_fragment<frag::fragment_pair_wait(UB, NDJ, kLead, R, G)>(a[set][kk][ub]);
       // token blocks in alternating direction: the MFMA that opens a group then keeps the B
       // operand of the one before it (both operands switch at once otherwise); measured 1-2 %
       static_for<TB>([&](auto i_) {
         constexpr int i = decltype(i_)::value, tb = (ub & 1) ? TB - 1 - i : i;
-        if constexpr (ub == 0) {
-          // this step's B fragments were read during the step before; after token block tb's
-          // read came those of the higher blocks and (behind MFMA 0) this group's reads
-          wait_lds_fragment<(TB - 1 - tb) + ((reads && i > 0) ? reads_in_group(0) : 0)>(b[kk & 1][tb]);
+        if constexpr (ub == 0 && i < 2) {
+          // this step's B fragments were read during the step before, token block 0's first:
+          // MFMA 0 waits for that one (TB-1 younger reads), MFMA 1 for all the others, behind
+          // which only this group's reads for the next step (issued after MFMA 0) may remain
+          wait_lds_fragment<i == 0 ? TB - 1 : (reads ? reads_in_group(0) : 0)>(b[kk & 1][tb]);
         }
         acc[ub][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[set][kk][ub], b[kk & 1][tb],
                                                               acc[ub][tb], 0, 0, 0);

@@ -55,10 +55,13 @@ struct Sim {
           wait(handover_wait(UB, NDJ, lead, R));
           need(hidden_at[t + 1], "hidden tile", t + 1, G);
         }
-        const int count = fragment_wait(UB, NDJ, lead, R, G) + plant;
-        const int exact = issued - frag_at[{t, G}] - 1;     // what could have been allowed
-        if (exact - count > max_slack) max_slack = exact - count;
-        wait(count);
+        if (G % 2 == 0) {                                   // one wait covers groups G and G+1
+          const int count = fragment_pair_wait(UB, NDJ, lead, R, G) + plant;
+          const int exact = issued - frag_at[{t, G + 1}] - 1;   // what could have been allowed
+          if (exact - count > max_slack) max_slack = exact - count;
+          if (count < 0) { ++errors; std::printf("negative count\n"); }
+          wait(count);
+        }
         need(frag_at[{t, G}], "fragment", t, G);
         if (more_hidden)
           for (int j = 0; j < NDJ; ++j)
