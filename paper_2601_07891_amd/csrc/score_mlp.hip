@@ -462,7 +462,7 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
   // beyond the last token block re-reads that block and drops the result)
   float ssq = 0.0f;
   bf16x8 xb[4];
-  const int xrow = 32 * (wid < TB ? wid : TB - 1) + l32;
+  const int xblock = wid < TB ? wid : TB - 1;
   // nk >= kPD + 1 tiles (checked by the launcher)
   // a[s][kk][ub]: register set s holds step kk of K tile t for (t + nk) % kLead == s, and is
   // re-filled fragment by fragment with tile t + kLead
@@ -670,9 +670,14 @@ __global__ __launch_bounds__(256) void score_mlp_frag_kernel(
             constexpr int kHalf = 2 * UB;                  // groups in half a tile
 #pragma unroll
             for (int f = 0; f < 4; ++f) {
+              // (the same read as B fragment (step f, token block xblock); hand-issued like those,
+              // or the compiler's wait for it would also wait for the B reads just issued.  No
+              // wait of its own: it is used two K steps later, behind that step's waits, which
+              // leave only reads younger than this one outstanding)
               if (f * kHalf / 4 == G)
-                xb[f] = *reinterpret_cast<const bf16x8*>(smem + (t % kNS) * STAGE + lds_off(xrow, f * 2 + kg));
+                read_fragment<0>(xb[f], b_off[f] + (unsigned)((t % kNS) * STAGE + xblock * 4096));
               if (f * kHalf / 4 == G - kHalf) {
+                arrived(xb[f]);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                   typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
